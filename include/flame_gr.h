@@ -1,0 +1,181 @@
+/*
+ * flame_gr.h - C ABI of the MI355X (gfx950) generative-recommendation forward.
+ *
+ * The library scores a jagged batch of requests.  A request is one user history of L_i items
+ * followed by M_i upstream candidate items ("single user, multiple items" per request: Section 1
+ * and Section 3.2 of the FLAME paper); candidates are appended after the behaviour sequence
+ * (Section 2.1) and a customised attention mask lets every candidate be scored in the same pass,
+ * independently of the other candidates (Section 3.2).  The number of candidates differs from
+ * request to request (Section 3.3), hence the offset arrays.  Inputs arrive as embeddings that
+ * the CPU side has already looked up (Section 2.3: embedding look-up is CPU work), and no device
+ * memory is allocated on the request path (Section 3.3: run-time allocation is what the
+ * explicit-shape executors remove): every workspace is sized at flame_gr_create.
+ *
+ * Per layer the forward computes, for the merged token matrix X (history rows then candidate
+ * rows of each request):
+ *     [U V Q K] = silu(X W1^T + b1)
+ *     O_r(head h) = sum over allowed keys c of silu(alpha <Q_r,K_c>_h + rab[l,h,bucket(p_r-p_c)]) V_c(h)
+ *     X <- X + (LayerNorm(O) * U) W2^T + b2
+ * and finally score_j = <w_s, X_{cand j}> + b_s.  A history row r may look at keys c <= r of its
+ * own request; a candidate row may look at the whole history of its request and at itself.
+ * History token t has position t, every candidate has position L_i.
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative flame_gr_status.  Nothing throws, aborts
+ *     or prints.  flame_gr_last_error gives a message for the most recent failure on a handle
+ *     (or, with a NULL handle, for the most recent failing flame_gr_create on this thread).
+ *   - "device" pointers are HIP device memory on the device that was current at create time;
+ *     "host" pointers are ordinary host memory.  The caller owns every pointer it passes; the
+ *     library owns the handle and its workspaces.
+ *   - A handle is used by one host thread at a time.
+ */
+#ifndef FLAME_GR_H
+#define FLAME_GR_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct flame_gr flame_gr_t; /* opaque */
+
+typedef enum {
+  FLAME_GR_OK = 0,
+  FLAME_GR_INVALID_ARGUMENT = -1, /* null pointer, bad offsets, bad configuration */
+  FLAME_GR_CAPACITY_EXCEEDED = -2, /* batch larger than the capacity given at create */
+  FLAME_GR_HIP_ERROR = -3,         /* a HIP runtime call failed */
+  FLAME_GR_BAD_HANDLE = -4,        /* NULL or destroyed handle */
+  FLAME_GR_UNSUPPORTED = -5        /* shape outside what the kernels are built for */
+} flame_gr_status;
+
+typedef enum { FLAME_GR_F32 = 0, FLAME_GR_BF16 = 1 } flame_gr_dtype;
+
+/* Model shape and capacity.  Fixed for the life of a handle. */
+typedef struct {
+  int32_t n_layers;      /* >= 1 */
+  int32_t d_model;       /* d; multiple of n_heads.  bf16: d % 64 == 0 and d/n_heads in {32,64,128} */
+  int32_t n_heads;       /* H */
+  int32_t n_buckets;     /* relative-position buckets: power of two, >= 2 */
+  int32_t max_rel_dist;  /* D: power of two >= n_buckets/2; distances >= D share the last bucket */
+  int32_t dtype;         /* flame_gr_dtype of embeddings and weights (rab and b_s are always fp32) */
+  float ln_eps;          /* LayerNorm epsilon; 0 selects 1e-6 */
+  float attn_scale;      /* alpha; 0 selects 1.0 */
+  int32_t max_requests;      /* capacity: requests per forward */
+  int32_t max_total_tokens;  /* capacity: sum over requests of (L_i + M_i) per forward */
+  int32_t max_seq_tokens;    /* 0 = unlimited; else a request with L_i + M_i above this is split by
+                                candidates into chunks (largest first), each chunk re-running the
+                                history, as the descending-size split of Section 3.3 does */
+  int32_t n_streams;         /* 0 or 1 = everything on the caller's stream; k > 1 = requests are
+                                partitioned into k cost-balanced groups that run on k internal
+                                streams, joined to the caller's stream by events (Section 3.3) */
+} flame_gr_config;
+
+/* Model weights: device pointers, caller-owned, read-only, element type = config.dtype unless
+ * stated.  All matrices are row-major with the input feature contiguous (y = x W^T). */
+typedef struct {
+  const void *w1;     /* [n_layers][4*d][d]   output rows ordered U | V | Q | K */
+  const void *b1;     /* [n_layers][4*d] */
+  const float *rab;   /* [n_layers][n_heads][n_buckets]   fp32 */
+  const void *ln_g;   /* [n_layers][d] */
+  const void *ln_b;   /* [n_layers][d] */
+  const void *w2;     /* [n_layers][d][d] */
+  const void *b2;     /* [n_layers][d] */
+  const void *w_s;    /* [d] */
+  float b_s;
+} flame_gr_weights;
+
+/* Create a handle on the current HIP device and allocate all workspaces for the given capacity.
+ * Errors: INVALID_ARGUMENT (bad shape), UNSUPPORTED (shape the bf16 kernels do not cover),
+ * HIP_ERROR (no device / out of memory).  *out is set to NULL on failure. */
+int flame_gr_create(const flame_gr_config *cfg, flame_gr_t **out);
+
+/* Score one jagged batch (the problem statement of Sections 1 and 3.2-3.3).
+ *   weights          host struct of device pointers (see above)
+ *   history_emb      device [sum L_i][d], rows of request i at history_offsets[i]..[i+1]
+ *   history_offsets  HOST   int32 [n_requests+1], [0] == 0, non-decreasing
+ *   cand_emb         device [sum M_i][d]
+ *   cand_offsets     HOST   int32 [n_requests+1], [0] == 0, non-decreasing
+ *   scores           device fp32 [sum M_i], written in cand_offsets order
+ *   stream           hipStream_t (or NULL for the default stream)
+ * The call validates and plans on the host, stages the plan through pinned memory, enqueues all
+ * kernels and returns; scores are valid once `stream` has been synchronised.  L_i = 0, M_i = 0
+ * and n_requests = 0 are legal.  Embedding pointers may be NULL when the matching total is 0.
+ * The host offset arrays may be reused as soon as the call returns.  The device buffers must stay
+ * alive and unmodified until the stream has passed the call.  Two forwards on one handle are
+ * serialised by the library (the second waits for the first on the device).
+ * Errors: BAD_HANDLE, INVALID_ARGUMENT (offsets not starting at 0 or decreasing, null pointers),
+ * CAPACITY_EXCEEDED, HIP_ERROR.  On error nothing is enqueued. */
+int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *weights,
+                     const void *history_emb, const int32_t *history_offsets,
+                     const void *cand_emb, const int32_t *cand_offsets,
+                     int32_t n_requests, float *scores, void *stream);
+
+/* Release the handle and its workspaces (synchronises the device work of the handle first).
+ * NULL is a no-op that returns 0. */
+int flame_gr_destroy(flame_gr_t *h);
+
+/* Message for the last error on `h` (never NULL; "" if none).  The string is owned by the handle
+ * (or by the thread, for h == NULL) and valid until the next call on it. */
+const char *flame_gr_last_error(const flame_gr_t *h);
+
+/* ------------------------------------------------------------------------------------------
+ * Host-only helpers: integer planning logic, usable without a GPU.  They expose what the forward
+ * uses internally so that it can be compared bit for bit with an independent implementation.
+ * ------------------------------------------------------------------------------------------ */
+
+/* bucket(delta) for delta = 0..max_rel_dist-1 into out[max_rel_dist] (HOST).  The near half of the
+ * table is exact (delta < n_buckets/2 maps to itself); above it every octave up to max_rel_dist is
+ * cut into 2^m equal sub-buckets, m the largest value such that all octaves fit in the far half. */
+int flame_gr_host_bucket_table(int32_t n_buckets, int32_t max_rel_dist, int32_t *out);
+
+/* Attention mask and bucket index of one request with L history items and M candidates (the mask
+ * of Section 3.2), as HOST arrays of (L+M)*(L+M) entries, row = query, column = key:
+ * mask 1 = allowed; bucket = bucket(p_r - p_c) on allowed pairs and -1 elsewhere (may be NULL). */
+int flame_gr_host_mask(int32_t L, int32_t M, int32_t n_buckets, int32_t max_rel_dist,
+                       uint8_t *mask, int32_t *bucket);
+
+/* Plan of a batch without running it (all arrays HOST).
+ *   tok_off   [n_requests+1]  start of each request in the merged token order (history_offsets +
+ *                             cand_offsets), i.e. the logical, unpadded layout
+ *   n_segments                number of scheduled segments (>= n_requests when requests are split)
+ *   seg       [cap_segments][6] per segment: request, hist_len, cand_begin (first candidate of
+ *                             the request handled by this segment), cand_len, row_start (first
+ *                             row of the segment in the library's padded workspace), stream group
+ * seg may be NULL to query n_segments only.  Errors as flame_gr_forward. */
+int flame_gr_host_plan(const flame_gr_config *cfg, const int32_t *history_offsets,
+                       const int32_t *cand_offsets, int32_t n_requests, int32_t *tok_off,
+                       int32_t *n_segments, int32_t *seg, int32_t cap_segments);
+
+/* ------------------------------------------------------------------------------------------
+ * Debug / parity exports (device work; not on the timed path).
+ * ------------------------------------------------------------------------------------------ */
+
+/* Select a layer (0-based) whose intermediates the next forwards keep, or -1 to stop capturing.
+ * Allocates the capture buffers (this call may allocate; forward still does not). */
+int flame_gr_debug_capture(flame_gr_t *h, int32_t layer);
+
+/* After a forward with capture on and a stream synchronisation: copy one captured tensor of the
+ * whole batch to HOST fp32 [sum(L_i+M_i)][d], rows in merged token order (request by request,
+ * history then candidates; padding rows removed).  which: 0=U 1=V 2=Q 3=K 4=O (attention output
+ * before LayerNorm) 5=X (residual stream after the layer).  Only valid if no request was split. */
+int flame_gr_debug_stage(flame_gr_t *h, int32_t which, float *host_out);
+
+/* Evaluate, on the device and with the very predicate and table the attention kernel uses, the
+ * mask and bucket of one request of shape (L, M); HOST outputs as flame_gr_host_mask. */
+int flame_gr_debug_device_mask(flame_gr_t *h, int32_t L, int32_t M, uint8_t *mask, int32_t *bucket);
+
+/* Per-kernel timing for measurements.  With enable != 0 every kernel launch of the following
+ * forwards is bracketed by HIP events on the stream it is launched on (this serialises nothing but
+ * adds event overhead, so leave it off when timing whole forwards). */
+int flame_gr_debug_profile(flame_gr_t *h, int32_t enable);
+
+/* After a profiled forward: summed milliseconds and launch counts of its kernels by kind, HOST
+ * arrays of 7 entries in the order assemble, bias expansion, UVQK projection, attention,
+ * LayerNorm-gate, output projection, score head.  Waits for the forward to finish. */
+int flame_gr_debug_profile_read(flame_gr_t *h, float *ms_by_kind, int32_t *launches_by_kind);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FLAME_GR_H */

@@ -1,0 +1,235 @@
+"""ctypes binding of libflame_gr.so: argument marshalling only.
+
+Function names mirror the C ABI (include/flame_gr.h).  PyTorch tensors are accepted wherever the
+ABI takes a device pointer; numpy arrays wherever it takes a host pointer.  Nothing here computes
+any part of the forward, and nothing falls back to another implementation: if the library has not
+been built, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libflame_gr.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it first (python -c 'import __graft_entry__ as g; g.build()' "
+        "or python paper_2509_22681_amd/build.py)")
+
+_lib = C.CDLL(LIB_PATH)
+
+FLAME_GR_F32, FLAME_GR_BF16 = 0, 1
+STATUS = {0: "OK", -1: "INVALID_ARGUMENT", -2: "CAPACITY_EXCEEDED", -3: "HIP_ERROR", -4: "BAD_HANDLE",
+          -5: "UNSUPPORTED"}
+KERNEL_KINDS = ("assemble", "bias", "uvqk", "attn", "ln_gate", "outproj", "score")
+
+
+class flame_gr_config(C.Structure):
+    _fields_ = [("n_layers", C.c_int32), ("d_model", C.c_int32), ("n_heads", C.c_int32),
+                ("n_buckets", C.c_int32), ("max_rel_dist", C.c_int32), ("dtype", C.c_int32),
+                ("ln_eps", C.c_float), ("attn_scale", C.c_float),
+                ("max_requests", C.c_int32), ("max_total_tokens", C.c_int32),
+                ("max_seq_tokens", C.c_int32), ("n_streams", C.c_int32)]
+
+
+class flame_gr_weights(C.Structure):
+    _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("rab", C.c_void_p), ("ln_g", C.c_void_p),
+                ("ln_b", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p), ("w_s", C.c_void_p),
+                ("b_s", C.c_float)]
+
+
+_i32p = C.POINTER(C.c_int32)
+_lib.flame_gr_create.argtypes = [C.POINTER(flame_gr_config), C.POINTER(C.c_void_p)]
+_lib.flame_gr_create.restype = C.c_int
+_lib.flame_gr_forward.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
+                                  C.c_int32, C.c_void_p, C.c_void_p]
+_lib.flame_gr_forward.restype = C.c_int
+_lib.flame_gr_destroy.argtypes = [C.c_void_p]
+_lib.flame_gr_destroy.restype = C.c_int
+_lib.flame_gr_last_error.argtypes = [C.c_void_p]
+_lib.flame_gr_last_error.restype = C.c_char_p
+_lib.flame_gr_host_bucket_table.argtypes = [C.c_int32, C.c_int32, _i32p]
+_lib.flame_gr_host_bucket_table.restype = C.c_int
+_lib.flame_gr_host_mask.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.flame_gr_host_mask.restype = C.c_int
+_lib.flame_gr_host_plan.argtypes = [C.POINTER(flame_gr_config), _i32p, _i32p, C.c_int32, _i32p, _i32p, _i32p, C.c_int32]
+_lib.flame_gr_host_plan.restype = C.c_int
+_lib.flame_gr_debug_capture.argtypes = [C.c_void_p, C.c_int32]
+_lib.flame_gr_debug_capture.restype = C.c_int
+_lib.flame_gr_debug_stage.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
+_lib.flame_gr_debug_stage.restype = C.c_int
+_lib.flame_gr_debug_device_mask.argtypes = [C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.flame_gr_debug_device_mask.restype = C.c_int
+_lib.flame_gr_debug_profile.argtypes = [C.c_void_p, C.c_int32]
+_lib.flame_gr_debug_profile.restype = C.c_int
+_lib.flame_gr_debug_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), _i32p]
+_lib.flame_gr_debug_profile_read.restype = C.c_int
+
+EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_destroy", "flame_gr_last_error",
+           "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan",
+           "flame_gr_debug_capture", "flame_gr_debug_stage", "flame_gr_debug_device_mask",
+           "flame_gr_debug_profile", "flame_gr_debug_profile_read")
+
+
+class FlameGRError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"{STATUS.get(code, code)}: {msg}")
+        self.code = code
+
+
+def _check(rc: int, h=None):
+    if rc != 0:
+        msg = _lib.flame_gr_last_error(h)
+        raise FlameGRError(rc, msg.decode() if msg else "")
+
+
+def _i32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int32)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device (torch tensor) or host (numpy) pointer, or None."""
+    if t is None:
+        return None
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr() if t.numel() else None
+
+
+def make_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dtype, *, ln_eps=1e-6, attn_scale=1.0,
+                max_requests=0, max_total_tokens=0, max_seq_tokens=0, n_streams=0) -> flame_gr_config:
+    dt = {"f32": FLAME_GR_F32, "bf16": FLAME_GR_BF16}.get(dtype, dtype)
+    return flame_gr_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dt, ln_eps, attn_scale,
+                           max_requests, max_total_tokens, max_seq_tokens, n_streams)
+
+
+# ---------------------------------------------------------------------------------------------
+# the three calls of the boundary, plus helpers, under their C names
+# ---------------------------------------------------------------------------------------------
+def flame_gr_create(cfg: flame_gr_config) -> C.c_void_p:
+    h = C.c_void_p()
+    _check(_lib.flame_gr_create(C.byref(cfg), C.byref(h)))
+    return h
+
+
+def flame_gr_destroy(h) -> None:
+    _check(_lib.flame_gr_destroy(h))
+
+
+def pack_weights(w: Dict[str, object]) -> flame_gr_weights:
+    """dict of device tensors (+ python float b_s) -> struct of device pointers."""
+    return flame_gr_weights(_ptr(w["w1"]), _ptr(w["b1"]), _ptr(w["rab"]), _ptr(w["ln_g"]), _ptr(w["ln_b"]),
+                            _ptr(w["w2"]), _ptr(w["b2"]), _ptr(w["w_s"]), float(w["b_s"]))
+
+
+def flame_gr_forward(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores, stream=None) -> None:
+    """weights: flame_gr_weights or dict; *_emb / scores: device tensors; *_offsets: host int32 arrays.
+    stream: torch.cuda.Stream, raw hipStream_t integer, or None for the current torch stream."""
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    ho, co = _i32(history_offsets), _i32(cand_offsets)
+    n = len(ho) - 1
+    if len(co) - 1 != n:
+        raise ValueError("offset arrays differ in length")
+    if stream is None:
+        import torch
+        sp = torch.cuda.current_stream().cuda_stream
+    else:
+        sp = getattr(stream, "cuda_stream", stream)
+    rc = _lib.flame_gr_forward(h, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
+                               co.ctypes.data_as(_i32p), n, _ptr(scores), C.c_void_p(sp))
+    _check(rc, h)
+
+
+def flame_gr_last_error(h=None) -> str:
+    return _lib.flame_gr_last_error(h).decode()
+
+
+def flame_gr_host_bucket_table(n_buckets: int, max_rel_dist: int) -> np.ndarray:
+    out = np.empty(max(max_rel_dist, 0), np.int32)
+    _check(_lib.flame_gr_host_bucket_table(n_buckets, max_rel_dist, out.ctypes.data_as(_i32p)))
+    return out
+
+
+def flame_gr_host_mask(L: int, M: int, n_buckets: int, max_rel_dist: int):
+    N = L + M
+    mask = np.empty((N, N), np.uint8)
+    bucket = np.empty((N, N), np.int32)
+    _check(_lib.flame_gr_host_mask(L, M, n_buckets, max_rel_dist, mask.ctypes.data, bucket.ctypes.data))
+    return mask, bucket
+
+
+def flame_gr_host_plan(cfg: flame_gr_config, history_offsets, cand_offsets):
+    """-> (tok_off [B+1], segments [S,6]: request, L, cand_begin, M, row_start, group)"""
+    ho, co = _i32(history_offsets), _i32(cand_offsets)
+    n = len(ho) - 1
+    tok = np.zeros(n + 1, np.int32)
+    nseg = C.c_int32(0)
+    _check(_lib.flame_gr_host_plan(C.byref(cfg), ho.ctypes.data_as(_i32p), co.ctypes.data_as(_i32p), n,
+                                   tok.ctypes.data_as(_i32p), C.byref(nseg), None, 0))
+    seg = np.zeros((max(nseg.value, 1), 6), np.int32)
+    _check(_lib.flame_gr_host_plan(C.byref(cfg), ho.ctypes.data_as(_i32p), co.ctypes.data_as(_i32p), n,
+                                   tok.ctypes.data_as(_i32p), C.byref(nseg), seg.ctypes.data_as(_i32p), len(seg)))
+    return tok, seg[:nseg.value]
+
+
+def flame_gr_debug_capture(h, layer: int) -> None:
+    _check(_lib.flame_gr_debug_capture(h, layer), h)
+
+
+def flame_gr_debug_stage(h, which: int, n_tokens: int, d: int) -> np.ndarray:
+    out = np.empty((n_tokens, d), np.float32)
+    _check(_lib.flame_gr_debug_stage(h, which, out.ctypes.data), h)
+    return out
+
+
+def flame_gr_debug_device_mask(h, L: int, M: int):
+    N = L + M
+    mask = np.empty((N, N), np.uint8)
+    bucket = np.empty((N, N), np.int32)
+    _check(_lib.flame_gr_debug_device_mask(h, L, M, mask.ctypes.data, bucket.ctypes.data), h)
+    return mask, bucket
+
+
+def flame_gr_debug_profile(h, enable: bool) -> None:
+    _check(_lib.flame_gr_debug_profile(h, int(enable)), h)
+
+
+def flame_gr_debug_profile_read(h):
+    """-> {kind: (milliseconds, launches)} for the last forward run with profiling on."""
+    ms = (C.c_float * len(KERNEL_KINDS))()
+    n = (C.c_int32 * len(KERNEL_KINDS))()
+    _check(_lib.flame_gr_debug_profile_read(h, ms, n), h)
+    return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_KINDS)}
+
+
+# ---------------------------------------------------------------------------------------------
+# marshalling of a numpy workload into device tensors
+# ---------------------------------------------------------------------------------------------
+def to_device(workload, device="cuda:0"):
+    """Upload a workloads.Workload: returns (cfg struct fields dict, weights dict, hist, cand) as
+    torch tensors of the workload's storage dtype (bf16 values are already exactly representable)."""
+    import torch
+    dt = torch.bfloat16 if workload.cfg.dtype == "bf16" else torch.float32
+
+    def up(a, dtype=dt):
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device=device, dtype=dtype)
+
+    w = workload.weights
+    dw = {k: up(w[k]) for k in ("w1", "b1", "ln_g", "ln_b", "w2", "b2", "w_s")}
+    dw["rab"] = up(w["rab"], torch.float32)
+    dw["b_s"] = float(w["b_s"])
+    return dw, up(workload.history_emb), up(workload.cand_emb)
+
+
+def config_for(workload, *, n_streams=0, max_seq_tokens=0, slack_requests=0) -> flame_gr_config:
+    c = workload.cfg
+    tot = int(workload.history_offsets[-1]) + int(workload.cand_offsets[-1])
+    return make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype,
+                       ln_eps=c.ln_eps, attn_scale=c.attn_scale,
+                       max_requests=workload.n_requests + slack_requests, max_total_tokens=tot,
+                       max_seq_tokens=max_seq_tokens, n_streams=n_streams)

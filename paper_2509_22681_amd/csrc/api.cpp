@@ -1,0 +1,538 @@
+// C ABI of the GR forward (flame_gr.h): handle, validation, plan staging, kernel sequencing.
+//
+// A handle is the analogue of the paper's executor (Section 3.3): pre-allocated buffers plus
+// streams, created once; the request path allocates nothing.
+#include <hip/hip_runtime.h>
+
+#include <cstring>
+#include <new>
+#include <utility>
+#include <string>
+#include <vector>
+
+#include "../../include/flame_gr.h"
+#include "kernels.h"
+#include "plan.h"
+
+using namespace flame;
+
+namespace {
+
+constexpr uint32_t kMagic = 0x464c4752u;  // "FLGR"
+constexpr int kStageSlots = 2;
+constexpr int kMaxGroups = 16;
+enum { KIND_ASSEMBLE = 0, KIND_BIAS, KIND_UVQK, KIND_ATTN, KIND_LNGATE, KIND_OUTPROJ, KIND_SCORE, KIND_COUNT };
+
+thread_local std::string g_create_error;
+
+struct StageLayout {  // byte offsets inside one staging buffer (host pinned and device mirror)
+  size_t blocks, items, cand_items, cand_blocks, total;
+};
+
+struct ProfEvent { hipEvent_t a, b; int kind; };
+
+}  // namespace
+
+struct flame_gr {
+  uint32_t magic = kMagic;
+  flame_gr_config cfg{};
+  Shape sh{};
+  int device = 0;
+  int n_groups = 1;
+  int q_tile = 0;
+  int64_t ws_rows = 0;
+  size_t elt = 4;
+  std::string err;
+  // workspaces (device)
+  float *X = nullptr;
+  void *Xb = nullptr, *planes = nullptr, *O = nullptr, *G = nullptr;
+  float *bias = nullptr;
+  int32_t *bucket_tab = nullptr;
+  // plan staging
+  StageLayout lay{};
+  char *stage_host[kStageSlots] = {};
+  hipEvent_t stage_done[kStageSlots] = {};
+  bool stage_used[kStageSlots] = {};
+  int stage_next = 0;
+  char *stage_dev = nullptr;
+  // streams / events
+  hipStream_t gstream[kMaxGroups] = {};
+  hipEvent_t ev_fork = nullptr, ev_join[kMaxGroups] = {}, ev_done = nullptr;
+  bool has_prev = false;
+  // last plan (kept for the debug exports)
+  Plan plan;
+  // debug capture
+  int capture_layer = -1;
+  void *cap_planes = nullptr, *cap_O = nullptr;
+  float *cap_X = nullptr;
+  bool cap_valid = false;
+  // per-kernel timing
+  bool profiling = false;
+  std::vector<ProfEvent> prof_pool;
+  size_t prof_used = 0;
+};
+
+namespace {
+
+#define HIP_TRY(h, expr)                                                                   \
+  do {                                                                                     \
+    hipError_t e_ = (expr);                                                                \
+    if (e_ != hipSuccess) {                                                                \
+      (h)->err = std::string(#expr) + ": " + hipGetErrorString(e_);                        \
+      return FLAME_GR_HIP_ERROR;                                                           \
+    }                                                                                      \
+  } while (0)
+
+bool live(const flame_gr *h) { return h && h->magic == kMagic; }
+
+void free_all(flame_gr *h) {
+  (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->O); (void)hipFree(h->G);
+  (void)hipFree(h->bias); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
+  (void)hipFree(h->cap_planes); (void)hipFree(h->cap_O); (void)hipFree(h->cap_X);
+  for (int i = 0; i < kStageSlots; ++i) {
+    if (h->stage_host[i]) (void)hipHostFree(h->stage_host[i]);
+    if (h->stage_done[i]) (void)hipEventDestroy(h->stage_done[i]);
+  }
+  for (int g = 0; g < kMaxGroups; ++g) {
+    if (h->gstream[g]) (void)hipStreamDestroy(h->gstream[g]);
+    if (h->ev_join[g]) (void)hipEventDestroy(h->ev_join[g]);
+  }
+  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+  if (h->ev_done) (void)hipEventDestroy(h->ev_done);
+  for (auto &p : h->prof_pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
+}
+
+// Bracket one launch with events when profiling is on.
+struct Timed {
+  flame_gr *h; hipStream_t s; ProfEvent *pe = nullptr;
+  Timed(flame_gr *h_, int kind, hipStream_t s_) : h(h_), s(s_) {
+    if (!h->profiling) return;
+    if (h->prof_used == h->prof_pool.size()) {
+      ProfEvent p{};
+      if (hipEventCreate(&p.a) != hipSuccess || hipEventCreate(&p.b) != hipSuccess) return;
+      h->prof_pool.push_back(p);
+    }
+    pe = &h->prof_pool[h->prof_used++];
+    pe->kind = kind;
+    (void)hipEventRecord(pe->a, s);
+  }
+  ~Timed() { if (pe) (void)hipEventRecord(pe->b, s); }
+};
+
+// The layer sequence of one stream group.
+void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const void *hist, const void *cand,
+               float *scores, hipStream_t s) {
+  const Shape &sh = h->sh;
+  const int dt = h->cfg.dtype;
+  const int d = sh.d;
+  const size_t e = h->elt;
+  const RowBlock *blocks = (const RowBlock *)(h->stage_dev + h->lay.blocks);
+  const AttnItem *items = (const AttnItem *)(h->stage_dev + h->lay.items);
+  const AttnItem *citems = (const AttnItem *)(h->stage_dev + h->lay.cand_items);
+  const int32_t *cblks = (const int32_t *)(h->stage_dev + h->lay.cand_blocks);
+  const int n_blk = G.blk_end - G.blk_begin;
+  if (n_blk == 0) return;
+  { Timed t(h, KIND_ASSEMBLE, s); launch_assemble(dt, blocks, G.blk_begin, G.blk_end, hist, cand, h->X, h->Xb, d, s); }
+  const int64_t plane = sh.ws_rows * d;
+  for (int l = 0; l < sh.n_layers; ++l) {
+    const bool last = (l == sh.n_layers - 1) && h->capture_layer != l;
+    const char *w1 = (const char *)w.w1 + (size_t)l * 4 * d * d * e;
+    const char *b1 = (const char *)w.b1 + (size_t)l * 4 * d * e;
+    const char *w2 = (const char *)w.w2 + (size_t)l * d * d * e;
+    const char *b2 = (const char *)w.b2 + (size_t)l * d * e;
+    const char *lg = (const char *)w.ln_g + (size_t)l * d * e;
+    const char *lb = (const char *)w.ln_b + (size_t)l * d * e;
+    const float *bias_l = h->bias + (size_t)l * sh.H * sh.D;
+    // In the last layer only candidate rows feed the scores, and history rows never look at
+    // candidates: history rows need K and V only, attention and the output projection run on
+    // candidate rows only.
+    const int32_t *cl = cblks + G.cblk_begin;
+    const int n_cblk = G.cblk_end - G.cblk_begin;
+    if (dt == FLAME_GR_BF16) {
+      Timed t(h, KIND_UVQK, s);
+      if (!last) {
+        launch_uvqk_bf16(h->Xb, w1, b1, h->planes, nullptr, n_blk, G.blk_begin, 0xF, sh, s);
+      } else {
+        launch_uvqk_bf16(h->Xb, w1, b1, h->planes, nullptr, n_blk, G.blk_begin, 0xA, sh, s);  // V, K: all rows
+        launch_uvqk_bf16(h->Xb, w1, b1, h->planes, cl, n_cblk, 0, 0x5, sh, s);                // U, Q: candidates
+      }
+    } else {
+      Timed t(h, KIND_UVQK, s);
+      launch_uvqk_f32(h->X, (const float *)w1, (const float *)b1, (float *)h->planes, G.blk_begin, n_blk, sh, s);
+    }
+    {
+      Timed t(h, KIND_ATTN, s);
+      const AttnItem *it = last ? citems + G.citem_begin : items + G.item_begin;
+      const int n_it = last ? G.citem_end - G.citem_begin : G.item_end - G.item_begin;
+      if (dt == FLAME_GR_BF16) launch_attn_bf16(h->planes, bias_l, h->O, it, n_it, sh, s);
+      else launch_attn_f32((const float *)h->planes, bias_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
+    }
+    {
+      Timed t(h, KIND_LNGATE, s);
+      if (last) launch_ln_gate(dt, h->O, h->planes, lg, lb, h->G, blocks, cl, n_cblk, 0, d, sh.eps, s);
+      else launch_ln_gate(dt, h->O, h->planes, lg, lb, h->G, blocks, nullptr, n_blk, G.blk_begin, d, sh.eps, s);
+    }
+    {
+      Timed t(h, KIND_OUTPROJ, s);
+      const int32_t *bl = last ? cl : nullptr;
+      const int nb = last ? n_cblk : n_blk;
+      const int bf = last ? 0 : G.blk_begin;
+      if (dt == FLAME_GR_BF16) launch_outproj_bf16(h->G, w2, b2, h->X, h->Xb, bl, nb, bf, sh, s);
+      else launch_outproj_f32((const float *)h->G, (const float *)w2, (const float *)b2, h->X, bl, nb, bf, sh, s);
+    }
+    if (h->capture_layer == l && h->cap_planes) {
+      const size_t r0 = (size_t)G.row_begin * d, nr = (size_t)(G.row_end - G.row_begin) * d;
+      if (dt == FLAME_GR_BF16) {
+        // U, Q, K are row-major planes; V is stored transposed ([d][ws_rows]) and copied whole by group 0
+        for (int p = 0; p < 4; ++p) {
+          if (p == 1) continue;
+          (void)hipMemcpyAsync((char *)h->cap_planes + ((size_t)p * plane + r0) * e, (char *)h->planes + ((size_t)p * plane + r0) * e, nr * e, hipMemcpyDeviceToDevice, s);
+        }
+      } else {
+        for (int p = 0; p < 4; ++p)
+          (void)hipMemcpyAsync((char *)h->cap_planes + ((size_t)p * plane + r0) * e, (char *)h->planes + ((size_t)p * plane + r0) * e, nr * e, hipMemcpyDeviceToDevice, s);
+      }
+      (void)hipMemcpyAsync((char *)h->cap_O + r0 * e, (char *)h->O + r0 * e, nr * e, hipMemcpyDeviceToDevice, s);
+      (void)hipMemcpyAsync(h->cap_X + r0, h->X + r0, nr * sizeof(float), hipMemcpyDeviceToDevice, s);
+    }
+  }
+  {
+    Timed t(h, KIND_SCORE, s);
+    launch_scores(dt, h->X, w.w_s, w.b_s, blocks, cblks + G.cblk_begin, G.cblk_end - G.cblk_begin, scores, d, s);
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *flame_gr_last_error(const flame_gr_t *h) {
+  if (!h) return g_create_error.c_str();
+  if (!live(h)) return "bad handle";
+  return h->err.c_str();
+}
+
+int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
+  if (out) *out = nullptr;
+  if (!cfg_in || !out) { g_create_error = "cfg or out is NULL"; return FLAME_GR_INVALID_ARGUMENT; }
+  flame_gr_config cfg = *cfg_in;
+  if (cfg.ln_eps == 0.f) cfg.ln_eps = 1e-6f;
+  if (cfg.attn_scale == 0.f) cfg.attn_scale = 1.0f;
+  int rc = validate_config(cfg, g_create_error);
+  if (rc) return rc;
+  flame_gr *h = new (std::nothrow) flame_gr();
+  if (!h) { g_create_error = "out of host memory"; return FLAME_GR_HIP_ERROR; }
+  h->cfg = cfg;
+  h->n_groups = cfg.n_streams > 1 ? cfg.n_streams : 1;
+  h->q_tile = cfg.dtype == FLAME_GR_BF16 ? kAttnQTileBf16 : kAttnQTileF32;
+  h->elt = cfg.dtype == FLAME_GR_BF16 ? 2 : 4;
+  h->ws_rows = workspace_rows(cfg);
+  h->sh = Shape{cfg.d_model, cfg.n_heads, cfg.d_model / cfg.n_heads, cfg.n_layers, cfg.n_buckets,
+                cfg.max_rel_dist, cfg.ln_eps, cfg.attn_scale, h->ws_rows};
+  auto fail = [&](const std::string &m, int code) {
+    g_create_error = m;
+    free_all(h);
+    h->magic = 0;
+    delete h;
+    return code;
+  };
+#define CR(expr)                                                                            \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(std::string(#expr) + ": " + hipGetErrorString(e_), FLAME_GR_HIP_ERROR); \
+  } while (0)
+  CR(hipGetDevice(&h->device));
+  const size_t rows = (size_t)h->ws_rows, d = (size_t)cfg.d_model, e = h->elt;
+  CR(hipMalloc(&h->X, rows * d * sizeof(float)));
+  CR(hipMalloc(&h->planes, 4 * rows * d * e));
+  CR(hipMalloc(&h->O, rows * d * e));
+  CR(hipMalloc(&h->G, rows * d * e));
+  if (cfg.dtype == FLAME_GR_BF16) CR(hipMalloc(&h->Xb, rows * d * e));
+  CR(hipMalloc(&h->bias, (size_t)cfg.n_layers * cfg.n_heads * cfg.max_rel_dist * sizeof(float)));
+  CR(hipMalloc(&h->bucket_tab, (size_t)cfg.max_rel_dist * sizeof(int32_t)));
+  // Every workspace starts finite: rows that a batch leaves as padding are read (and multiplied
+  // by zero weights) by the tiled kernels.
+  CR(hipMemset(h->X, 0, rows * d * sizeof(float)));
+  CR(hipMemset(h->planes, 0, 4 * rows * d * e));
+  CR(hipMemset(h->O, 0, rows * d * e));
+  CR(hipMemset(h->G, 0, rows * d * e));
+  if (h->Xb) CR(hipMemset(h->Xb, 0, rows * d * e));
+  {
+    std::vector<int32_t> tab(cfg.max_rel_dist);
+    bucket_table(cfg.n_buckets, cfg.max_rel_dist, tab.data());
+    CR(hipMemcpy(h->bucket_tab, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+  }
+  const size_t nblk = rows / kRowAlign;
+  h->lay.blocks = 0;
+  h->lay.items = h->lay.blocks + nblk * sizeof(RowBlock);
+  h->lay.cand_items = h->lay.items + nblk * sizeof(AttnItem);
+  h->lay.cand_blocks = h->lay.cand_items + nblk * sizeof(AttnItem);
+  h->lay.total = h->lay.cand_blocks + nblk * sizeof(int32_t);
+  CR(hipMalloc(&h->stage_dev, h->lay.total));
+  for (int i = 0; i < kStageSlots; ++i) {
+    CR(hipHostMalloc((void **)&h->stage_host[i], h->lay.total, hipHostMallocDefault));
+    CR(hipEventCreateWithFlags(&h->stage_done[i], hipEventDisableTiming));
+  }
+  CR(hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming));
+  CR(hipEventCreateWithFlags(&h->ev_done, hipEventDisableTiming));
+  if (h->n_groups > 1)
+    for (int g = 0; g < h->n_groups; ++g) {
+      CR(hipStreamCreateWithFlags(&h->gstream[g], hipStreamNonBlocking));
+      CR(hipEventCreateWithFlags(&h->ev_join[g], hipEventDisableTiming));
+    }
+  CR(hipDeviceSynchronize());
+#undef CR
+  *out = h;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_destroy(flame_gr_t *h) {
+  if (!h) return FLAME_GR_OK;
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  if (h->has_prev) (void)hipEventSynchronize(h->ev_done);
+  for (int g = 0; g < kMaxGroups; ++g)
+    if (h->gstream[g]) (void)hipStreamSynchronize(h->gstream[g]);
+  free_all(h);
+  h->magic = 0;
+  delete h;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+                     const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
+                     int32_t n_requests, float *scores, void *stream_v) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  h->err.clear();
+  auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  if (!w) return bad("weights is NULL");
+  if (n_requests < 0) return bad("n_requests < 0");
+  if (n_requests > 0 && (!history_offsets || !cand_offsets)) return bad("offset arrays are NULL");
+  Plan plan;
+  int rc = build_plan(h->cfg, history_offsets, cand_offsets, n_requests, h->q_tile, h->n_groups, h->ws_rows, plan, h->err);
+  if (rc) return rc;
+  const int64_t sumL = n_requests ? history_offsets[n_requests] : 0, sumM = n_requests ? cand_offsets[n_requests] : 0;
+  if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
+  if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
+  if (plan.total_rows > 0 && (!w->w1 || !w->b1 || !w->rab || !w->ln_g || !w->ln_b || !w->w2 || !w->b2 || !w->w_s))
+    return bad("a weight pointer is NULL");
+  h->plan = std::move(plan);
+  h->cap_valid = false;
+  if (h->plan.total_rows == 0) return FLAME_GR_OK;
+
+  hipStream_t s0 = (hipStream_t)stream_v;
+  const Plan &P = h->plan;
+  // stage the plan: one pinned buffer, one copy
+  const int slot = h->stage_next;
+  h->stage_next = (slot + 1) % kStageSlots;
+  if (h->stage_used[slot]) HIP_TRY(h, hipEventSynchronize(h->stage_done[slot]));
+  char *sh_ = h->stage_host[slot];
+  std::memcpy(sh_ + h->lay.blocks, P.blocks.data(), P.blocks.size() * sizeof(RowBlock));
+  std::memcpy(sh_ + h->lay.items, P.items.data(), P.items.size() * sizeof(AttnItem));
+  std::memcpy(sh_ + h->lay.cand_items, P.cand_items.data(), P.cand_items.size() * sizeof(AttnItem));
+  std::memcpy(sh_ + h->lay.cand_blocks, P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t));
+  // a forward on another stream must not overtake the previous one on this handle
+  if (h->has_prev) HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_done, 0));
+  // the four tables are copied separately only as far as they are filled
+  HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.blocks, sh_ + h->lay.blocks, P.blocks.size() * sizeof(RowBlock), hipMemcpyHostToDevice, s0));
+  if (!P.items.empty())
+    HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.items, sh_ + h->lay.items, P.items.size() * sizeof(AttnItem), hipMemcpyHostToDevice, s0));
+  if (!P.cand_items.empty())
+    HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.cand_items, sh_ + h->lay.cand_items, P.cand_items.size() * sizeof(AttnItem), hipMemcpyHostToDevice, s0));
+  if (!P.cand_blocks.empty())
+    HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.cand_blocks, sh_ + h->lay.cand_blocks, P.cand_blocks.size() * sizeof(int32_t), hipMemcpyHostToDevice, s0));
+  HIP_TRY(h, hipEventRecord(h->stage_done[slot], s0));
+  h->stage_used[slot] = true;
+  h->prof_used = 0;
+  {
+    Timed t(h, KIND_BIAS, s0);
+    launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D, s0);
+  }
+  if (h->n_groups == 1) {
+    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0);
+  } else {
+    HIP_TRY(h, hipEventRecord(h->ev_fork, s0));
+    for (int g = 0; g < h->n_groups; ++g) {
+      if (P.groups[g].blk_end == P.groups[g].blk_begin) continue;
+      HIP_TRY(h, hipStreamWaitEvent(h->gstream[g], h->ev_fork, 0));
+      run_group(h, *w, P.groups[g], history_emb, cand_emb, scores, h->gstream[g]);
+      HIP_TRY(h, hipEventRecord(h->ev_join[g], h->gstream[g]));
+      HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_join[g], 0));
+    }
+  }
+  if (h->capture_layer >= 0 && h->cap_planes && h->cfg.dtype == FLAME_GR_BF16) {
+    // transposed V plane, whole (after all groups have joined)
+    const size_t plane = (size_t)h->ws_rows * h->sh.d * h->elt;
+    (void)hipMemcpyAsync((char *)h->cap_planes + plane, (char *)h->planes + plane, plane, hipMemcpyDeviceToDevice, s0);
+  }
+  HIP_TRY(h, hipEventRecord(h->ev_done, s0));
+  h->has_prev = true;
+  h->cap_valid = h->capture_layer >= 0 && h->cap_planes;
+  hipError_t le = hipGetLastError();
+  if (le != hipSuccess) { h->err = std::string("kernel launch: ") + hipGetErrorString(le); return FLAME_GR_HIP_ERROR; }
+  return FLAME_GR_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// host-only helpers
+// ---------------------------------------------------------------------------------------------
+int flame_gr_host_bucket_table(int32_t n_buckets, int32_t max_rel_dist, int32_t *out) {
+  flame_gr_config c{};
+  c.n_layers = 1; c.d_model = 1; c.n_heads = 1; c.n_buckets = n_buckets; c.max_rel_dist = max_rel_dist;
+  std::string err;
+  if (!out) return FLAME_GR_INVALID_ARGUMENT;
+  int rc = validate_config(c, err);
+  if (rc) { g_create_error = err; return rc; }
+  bucket_table(n_buckets, max_rel_dist, out);
+  return FLAME_GR_OK;
+}
+
+int flame_gr_host_mask(int32_t L, int32_t M, int32_t n_buckets, int32_t max_rel_dist, uint8_t *mask, int32_t *bucket) {
+  if (L < 0 || M < 0 || !mask) return FLAME_GR_INVALID_ARGUMENT;
+  std::vector<int32_t> tab;
+  if (bucket) {
+    tab.resize(max_rel_dist > 0 ? max_rel_dist : 0);
+    int rc = flame_gr_host_bucket_table(n_buckets, max_rel_dist, tab.data());
+    if (rc) return rc;
+  }
+  const int64_t N = (int64_t)L + M;
+  for (int64_t r = 0; r < N; ++r)
+    for (int64_t c = 0; c < N; ++c) {
+      const bool ok = allowed((int32_t)r, (int32_t)c, L);
+      mask[r * N + c] = ok;
+      if (bucket) {
+        const int32_t pr = r < L ? (int32_t)r : L, pc = c < L ? (int32_t)c : L;
+        int32_t delta = pr - pc;
+        if (delta > max_rel_dist - 1) delta = max_rel_dist - 1;
+        bucket[r * N + c] = ok ? tab[delta] : -1;
+      }
+    }
+  return FLAME_GR_OK;
+}
+
+int flame_gr_host_plan(const flame_gr_config *cfg_in, const int32_t *history_offsets, const int32_t *cand_offsets,
+                       int32_t n_requests, int32_t *tok_off, int32_t *n_segments, int32_t *seg, int32_t cap_segments) {
+  if (!cfg_in) return FLAME_GR_INVALID_ARGUMENT;
+  flame_gr_config cfg = *cfg_in;
+  std::string err;
+  int rc = validate_config(cfg, err);
+  if (!rc) {
+    Plan P;
+    const int q_tile = cfg.dtype == FLAME_GR_BF16 ? kAttnQTileBf16 : kAttnQTileF32;
+    rc = build_plan(cfg, history_offsets, cand_offsets, n_requests, q_tile, cfg.n_streams > 1 ? cfg.n_streams : 1,
+                    workspace_rows(cfg), P, err);
+    if (!rc) {
+      if (tok_off) std::memcpy(tok_off, P.tok_off.data(), P.tok_off.size() * sizeof(int32_t));
+      if (n_segments) *n_segments = (int32_t)P.segs.size();
+      if (seg) {
+        if ((int32_t)P.segs.size() > cap_segments) { g_create_error = "cap_segments too small"; return FLAME_GR_CAPACITY_EXCEEDED; }
+        for (size_t i = 0; i < P.segs.size(); ++i) {
+          const Segment &s = P.segs[i];
+          int32_t *o = seg + 6 * i;
+          o[0] = s.req; o[1] = s.L; o[2] = s.cand_begin; o[3] = s.M; o[4] = s.row_start; o[5] = s.group;
+        }
+      }
+    }
+  }
+  if (rc) g_create_error = err;
+  return rc;
+}
+
+// ---------------------------------------------------------------------------------------------
+// debug exports
+// ---------------------------------------------------------------------------------------------
+int flame_gr_debug_capture(flame_gr_t *h, int32_t layer) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  if (layer >= h->cfg.n_layers) { h->err = "layer out of range"; return FLAME_GR_INVALID_ARGUMENT; }
+  h->capture_layer = layer < 0 ? -1 : layer;
+  h->cap_valid = false;
+  if (layer >= 0 && !h->cap_planes) {
+    const size_t n = (size_t)h->ws_rows * h->sh.d;
+    HIP_TRY(h, hipMalloc(&h->cap_planes, 4 * n * h->elt));
+    HIP_TRY(h, hipMalloc(&h->cap_O, n * h->elt));
+    HIP_TRY(h, hipMalloc((void **)&h->cap_X, n * sizeof(float)));
+  }
+  return FLAME_GR_OK;
+}
+
+int flame_gr_debug_stage(flame_gr_t *h, int32_t which, float *host_out) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  if (!h->cap_valid) { h->err = "no captured forward"; return FLAME_GR_INVALID_ARGUMENT; }
+  if (which < 0 || which > 5 || !host_out) { h->err = "bad stage selector"; return FLAME_GR_INVALID_ARGUMENT; }
+  if (h->plan.split) { h->err = "stage export needs unsplit requests"; return FLAME_GR_UNSUPPORTED; }
+  HIP_TRY(h, hipEventSynchronize(h->ev_done));
+  const size_t d = h->sh.d, rows = (size_t)h->plan.total_rows, e = h->elt, wsr = (size_t)h->ws_rows;
+  const bool bf = h->cfg.dtype == FLAME_GR_BF16;
+  const bool transposed = bf && which == 1;
+  std::vector<char> raw;
+  size_t esz = which == 5 ? 4 : e;
+  if (transposed) {
+    raw.resize(wsr * d * e);
+    HIP_TRY(h, hipMemcpy(raw.data(), (char *)h->cap_planes + wsr * d * e, raw.size(), hipMemcpyDeviceToHost));
+  } else {
+    raw.resize(rows * d * esz);
+    const void *src = which < 4 ? (const void *)((char *)h->cap_planes + (size_t)which * wsr * d * e)
+                      : which == 4 ? h->cap_O : (const void *)h->cap_X;
+    HIP_TRY(h, hipMemcpy(raw.data(), src, raw.size(), hipMemcpyDeviceToHost));
+  }
+  auto get = [&](size_t row, size_t k) -> float {
+    if (esz == 4) return ((const float *)raw.data())[row * d + k];
+    const uint16_t *p = (const uint16_t *)raw.data();
+    uint32_t bits = (uint32_t)(transposed ? p[k * wsr + row] : p[row * d + k]) << 16;
+    float f;
+    std::memcpy(&f, &bits, 4);
+    return f;
+  };
+  // segments are in workspace order; the output is in request order (merged token offsets)
+  for (const Segment &s : h->plan.segs) {
+    float *dst = host_out + (size_t)h->plan.tok_off[s.req] * d;
+    for (int32_t t = 0; t < s.L; ++t)
+      for (size_t k = 0; k < d; ++k) dst[(size_t)t * d + k] = get((size_t)s.row_start + t, k);
+    for (int32_t j = 0; j < s.M; ++j)
+      for (size_t k = 0; k < d; ++k) dst[(size_t)(s.L + j) * d + k] = get((size_t)s.row_start + s.Lp + j, k);
+  }
+  return FLAME_GR_OK;
+}
+
+int flame_gr_debug_device_mask(flame_gr_t *h, int32_t L, int32_t M, uint8_t *mask, int32_t *bucket) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  if (L < 0 || M < 0 || !mask) { h->err = "bad arguments"; return FLAME_GR_INVALID_ARGUMENT; }
+  const size_t n = (size_t)(L + M) * (L + M);
+  if (n == 0) return FLAME_GR_OK;
+  uint8_t *dm = nullptr;
+  int32_t *db = nullptr;
+  HIP_TRY(h, hipMalloc((void **)&dm, n));
+  if (bucket) {
+    hipError_t e_ = hipMalloc((void **)&db, n * sizeof(int32_t));
+    if (e_ != hipSuccess) { (void)hipFree(dm); h->err = "hipMalloc failed"; return FLAME_GR_HIP_ERROR; }
+  }
+  launch_debug_mask(L, M, h->bucket_tab, h->sh.D, dm, db, nullptr);
+  hipError_t e1 = hipMemcpy(mask, dm, n, hipMemcpyDeviceToHost);
+  hipError_t e2 = bucket ? hipMemcpy(bucket, db, n * sizeof(int32_t), hipMemcpyDeviceToHost) : hipSuccess;
+  (void)hipFree(dm);
+  (void)hipFree(db);
+  if (e1 != hipSuccess || e2 != hipSuccess) { h->err = "debug mask copy failed"; return FLAME_GR_HIP_ERROR; }
+  return FLAME_GR_OK;
+}
+
+int flame_gr_debug_profile(flame_gr_t *h, int32_t enable) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  h->profiling = enable != 0;
+  h->prof_used = 0;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_debug_profile_read(flame_gr_t *h, float *ms_by_kind, int32_t *launches_by_kind) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  if (!ms_by_kind || !launches_by_kind) { h->err = "NULL output"; return FLAME_GR_INVALID_ARGUMENT; }
+  for (int k = 0; k < KIND_COUNT; ++k) { ms_by_kind[k] = 0.f; launches_by_kind[k] = 0; }
+  if (h->has_prev) HIP_TRY(h, hipEventSynchronize(h->ev_done));
+  for (size_t i = 0; i < h->prof_used; ++i) {
+    float ms = 0.f;
+    HIP_TRY(h, hipEventElapsedTime(&ms, h->prof_pool[i].a, h->prof_pool[i].b));
+    ms_by_kind[h->prof_pool[i].kind] += ms;
+    launches_by_kind[h->prof_pool[i].kind] += 1;
+  }
+  return FLAME_GR_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// Device-side helpers shared by the gfx950 kernels of the GR forward.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace flame {
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+
+template <typename T> __device__ __forceinline__ T from_f32(float v);
+template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round to nearest even
+
+// silu(x) = x / (1 + exp(-x)).  exp2 of a large positive argument gives +inf and the quotient 0,
+// of a large negative one gives 0 and the quotient x: both limits are the right ones.
+__device__ __forceinline__ float silu_f32(float x) {
+  return x / (1.0f + __expf(-x));
+}
+
+// Faster variant for the attention inner loop: hardware exp2 and reciprocal (about 1 ulp each).
+__device__ __forceinline__ float silu_fast(float x) {
+  float e = __builtin_amdgcn_exp2f(x * -1.4426950408889634f);
+  return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+// Number of history keys a query row may look at (the mask of the single-user-multiple-items
+// scoring pass): a history row at index q sees keys 0..q, a candidate row sees all L.
+__device__ __forceinline__ int visible_history(int is_cand, int q_index, int L) {
+  return is_cand ? L : q_index + 1;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+
+}  // namespace flame

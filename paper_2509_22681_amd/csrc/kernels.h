@@ -1,0 +1,60 @@
+// Launch interface between the host API and the gfx950 kernels.  All pointers are device
+// pointers unless stated; every launcher only enqueues work on `s`.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include "plan.h"
+
+namespace flame {
+
+// Shapes every launcher needs.
+struct Shape {
+  int d, H, dh, n_layers, n_buckets, D;
+  float eps, alpha;
+  int64_t ws_rows;  // rows of every workspace matrix (plane stride = ws_rows * d)
+};
+
+// ---- shared small kernels (misc.hip) --------------------------------------------------------
+// X[rows of blocks) <- embeddings (fp32 copy, and a bf16 copy when Xb != nullptr); padding rows zeroed.
+void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
+                     const void *cand, float *X, void *Xb, int d, hipStream_t s);
+// bias[lh][delta] = rab[lh][bucket_tab[delta]] for all layers and heads.
+void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh,
+                        int n_buckets, int D, hipStream_t s);
+// G = (LayerNorm(O) * gamma + beta) * U, one row at a time (element type of O, U, G = dtype);
+// padding rows of a block get G = 0 so that they stay finite through the layers.
+void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, const void *beta,
+                    void *G, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first, int d,
+                    float eps, hipStream_t s);
+// scores[src_row + i] = <X[row], w_s> + b_s for the valid rows of every candidate block.
+void launch_scores(int dtype, const float *X, const void *w_s, float b_s, const RowBlock *blocks,
+                   const int32_t *cand_blocks, int n_cblk, float *scores, int d, hipStream_t s);
+// mask / bucket of one request evaluated with the device predicate (debug export).
+void launch_debug_mask(int L, int M, const int32_t *bucket_tab, int D, uint8_t *mask, int32_t *bucket,
+                       hipStream_t s);
+
+// ---- fp32 path (kernels_f32.hip): plain FMA kernels, correctness first ------------------------
+// planes[p][row][n] = silu(X W1^T + b1), p = U,V,Q,K; rows = 64-row blocks [blk_first, blk_first+n_blk)
+void launch_uvqk_f32(const float *X, const float *W1, const float *b1, float *planes, int blk_first,
+                     int n_blk, const Shape &sh, hipStream_t s);
+void launch_attn_f32(const float *planes, const float *bias_lh, float *O, const AttnItem *items,
+                     int n_items, int q_tile, const Shape &sh, hipStream_t s);
+// X[row] += G[row] W2^T + b2 for the rows of the listed blocks (blk_list == nullptr: contiguous)
+void launch_outproj_f32(const float *G, const float *W2, const float *b2, float *X,
+                        const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
+
+// ---- bf16 path (gemm_bf16.hip, attn_bf16.hip): MFMA kernels ----------------------------------
+// U, Q, K planes row-major [row][d]; the V plane is written transposed, Vt[n][row] (row stride ws_rows).
+// plane_mask bit p set = compute plane p (U=1, V=2, Q=4, K=8).
+void launch_uvqk_bf16(const void *Xb, const void *W1, const void *b1, void *planes, const int32_t *blk_list,
+                      int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s);
+void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const AttnItem *items, int n_items,
+                      const Shape &sh, hipStream_t s);
+// X[row] += G W2^T + b2, and Xb[row] = bf16(X[row])
+void launch_outproj_bf16(const void *G, const void *W2, const void *b2, float *X, void *Xb,
+                         const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
+
+constexpr int kAttnQTileBf16 = 128;  // query rows per attention work item, bf16 path
+constexpr int kAttnQTileF32 = 64;    // fp32 path
+
+}  // namespace flame

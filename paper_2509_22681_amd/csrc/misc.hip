@@ -1,0 +1,185 @@
+// Small bandwidth-bound kernels of the GR forward: input assembly, bias-table expansion,
+// LayerNorm * U gating, score head, and the debug evaluation of the mask predicate.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace flame {
+
+// ---------------------------------------------------------------------------------------------
+// Assembly: the token matrix of a request is its history rows followed by its candidate rows
+// (Section 2.1: candidates are appended after the behaviour sequence).  One workgroup per 64-row
+// block of the padded workspace; rows past n_valid are zero so that they stay finite downstream.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restrict__ blocks, int blk_begin,
+                                                       const T *__restrict__ hist, const T *__restrict__ cand,
+                                                       float *__restrict__ X, bf16_t *__restrict__ Xb, int d) {
+  const int b = blk_begin + blockIdx.x;
+  const RowBlock rb = blocks[b];
+  const T *src = rb.kind ? cand : hist;
+  const int64_t dst0 = (int64_t)b * kRowAlign * d;
+  const int n = kRowAlign * d;
+  const int nv = rb.n_valid * d;
+  for (int i = threadIdx.x; i < n; i += 256) {
+    float v = 0.f;
+    if (i < nv) v = to_f32(src[(int64_t)rb.src_row * d + i]);
+    X[dst0 + i] = v;
+    if (Xb) Xb[dst0 + i] = (bf16_t)v;
+  }
+}
+
+void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
+                     const void *cand, float *X, void *Xb, int d, hipStream_t s) {
+  const int n = blk_end - blk_begin;
+  if (n <= 0) return;
+  if (dtype == FLAME_GR_BF16)
+    assemble_kernel<bf16_t><<<n, 256, 0, s>>>(blocks, blk_begin, (const bf16_t *)hist, (const bf16_t *)cand, X, (bf16_t *)Xb, d);
+  else
+    assemble_kernel<float><<<n, 256, 0, s>>>(blocks, blk_begin, (const float *)hist, (const float *)cand, X, nullptr, d);
+}
+
+// ---------------------------------------------------------------------------------------------
+// bias[lh][delta] = rab[lh][bucket(delta)]: the attention kernels index the bias by distance.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void expand_bias_kernel(const float *__restrict__ rab, const int32_t *__restrict__ tab,
+                                                          float *__restrict__ bias, int nb, int D) {
+  const int lh = blockIdx.y;
+  for (int t = blockIdx.x * 256 + threadIdx.x; t < D; t += gridDim.x * 256)
+    bias[(int64_t)lh * D + t] = rab[(int64_t)lh * nb + tab[t]];
+}
+
+void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh, int n_buckets,
+                        int D, hipStream_t s) {
+  dim3 grid((D + 255) / 256 > 64 ? 64 : (D + 255) / 256, n_lh);
+  expand_bias_kernel<<<grid, 256, 0, s>>>(rab, bucket_tab, bias, n_buckets, D);
+}
+
+// ---------------------------------------------------------------------------------------------
+// G = (LayerNorm_d(O) * gamma + beta) * U.  One wavefront per row, statistics in fp32 by wavefront
+// reduction (mean first, then the centred second moment: biased variance).
+// ---------------------------------------------------------------------------------------------
+template <typename T, int MAXV>
+__global__ __launch_bounds__(256) void ln_gate_kernel(const T *__restrict__ O, const T *__restrict__ U,
+                                                      const T *__restrict__ gamma, const T *__restrict__ beta,
+                                                      T *__restrict__ G, const RowBlock *__restrict__ blocks,
+                                                      const int32_t *__restrict__ blk_list, int blk_first, int d,
+                                                      float eps) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int rb = blockIdx.x >> 4;                       // 16 workgroups of 4 rows per 64-row block
+  const int blk = blk_list ? blk_list[rb] : blk_first + rb;
+  const int in_blk = (blockIdx.x & 15) * 4 + wave;
+  const int64_t row = (int64_t)blk * kRowAlign + in_blk;
+  if (in_blk >= blocks[blk].n_valid) {                  // padding row: keep it finite (zero branch)
+    for (int k = lane; k < d; k += 64) G[row * d + k] = from_f32<T>(0.f);
+    return;
+  }
+  const T *o = O + row * d;
+  float v[MAXV];
+  float sum = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int k = lane + i * 64;
+    v[i] = k < d ? to_f32(o[k]) : 0.f;
+    sum += v[i];
+  }
+  const float mu = wave_sum(sum) / (float)d;
+  float sq = 0.f;
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int k = lane + i * 64;
+    const float c = k < d ? v[i] - mu : 0.f;
+    sq += c * c;
+  }
+  const float rstd = rsqrtf(wave_sum(sq) / (float)d + eps);
+#pragma unroll
+  for (int i = 0; i < MAXV; ++i) {
+    const int k = lane + i * 64;
+    if (k < d) {
+      const float y = ((v[i] - mu) * rstd * to_f32(gamma[k]) + to_f32(beta[k])) * to_f32(U[row * d + k]);
+      G[row * d + k] = from_f32<T>(y);
+    }
+  }
+}
+
+template <typename T>
+static void ln_gate_dispatch(const void *O, const void *U, const void *g, const void *b, void *G,
+                             const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first, int d, float eps, hipStream_t s) {
+  const int grid = n_blk * 16;
+#define LN_CASE(MV) ln_gate_kernel<T, MV><<<grid, 256, 0, s>>>((const T *)O, (const T *)U, (const T *)g, (const T *)b, (T *)G, blocks, blk_list, blk_first, d, eps)
+  if (d <= 64) LN_CASE(1);
+  else if (d <= 128) LN_CASE(2);
+  else if (d <= 256) LN_CASE(4);
+  else if (d <= 512) LN_CASE(8);
+  else if (d <= 1024) LN_CASE(16);
+  else LN_CASE(64);
+#undef LN_CASE
+}
+
+void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, const void *beta, void *G,
+                    const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first, int d, float eps, hipStream_t s) {
+  if (n_blk <= 0) return;
+  if (dtype == FLAME_GR_BF16) ln_gate_dispatch<bf16_t>(O, U, gamma, beta, G, blocks, blk_list, n_blk, blk_first, d, eps, s);
+  else ln_gate_dispatch<float>(O, U, gamma, beta, G, blocks, blk_list, n_blk, blk_first, d, eps, s);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Score head: one logit per candidate row, written in the caller's candidate order.
+// ---------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X, const T *__restrict__ w_s, float b_s,
+                                                    const RowBlock *__restrict__ blocks, const int32_t *__restrict__ cblk,
+                                                    float *__restrict__ scores, int d) {
+  const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int blk = cblk[blockIdx.x >> 4];
+  const RowBlock rb = blocks[blk];
+  const int i = (blockIdx.x & 15) * 4 + wave;
+  if (i >= rb.n_valid) return;
+  const float *x = X + ((int64_t)blk * kRowAlign + i) * d;
+  float acc = 0.f;
+  for (int k = lane; k < d; k += 64) acc += x[k] * to_f32(w_s[k]);
+  acc = wave_sum(acc);
+  if (lane == 0) scores[rb.src_row + i] = acc + b_s;
+}
+
+void launch_scores(int dtype, const float *X, const void *w_s, float b_s, const RowBlock *blocks,
+                   const int32_t *cand_blocks, int n_cblk, float *scores, int d, hipStream_t s) {
+  if (n_cblk <= 0) return;
+  if (dtype == FLAME_GR_BF16)
+    score_kernel<bf16_t><<<n_cblk * 16, 256, 0, s>>>(X, (const bf16_t *)w_s, b_s, blocks, cand_blocks, scores, d);
+  else
+    score_kernel<float><<<n_cblk * 16, 256, 0, s>>>(X, (const float *)w_s, b_s, blocks, cand_blocks, scores, d);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Debug: the mask predicate and bucket table as the attention kernels see them.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void debug_mask_kernel(int L, int M, const int32_t *__restrict__ tab, int D,
+                                                         uint8_t *__restrict__ mask, int32_t *__restrict__ bucket) {
+  const int N = L + M;
+  const int64_t total = (int64_t)N * N;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int r = (int)(i / N), c = (int)(i % N);
+    const int is_cand = r >= L;
+    const int q_index = is_cand ? L : r;
+    bool ok;
+    int delta;
+    if (c < L) {
+      ok = c < visible_history(is_cand, q_index, L);
+      delta = q_index - c;
+    } else {
+      ok = is_cand && c == r;   // among candidate keys a candidate sees itself only
+      delta = 0;
+    }
+    mask[i] = ok ? 1 : 0;
+    if (bucket) bucket[i] = ok ? tab[delta < D ? delta : D - 1] : -1;
+  }
+}
+
+void launch_debug_mask(int L, int M, const int32_t *bucket_tab, int D, uint8_t *mask, int32_t *bucket, hipStream_t s) {
+  const int64_t total = (int64_t)(L + M) * (L + M);
+  if (total == 0) return;
+  int grid = (int)((total + 255) / 256 > 4096 ? 4096 : (total + 255) / 256);
+  debug_mask_kernel<<<grid, 256, 0, s>>>(L, M, bucket_tab, D, mask, bucket);
+}
+
+}  // namespace flame

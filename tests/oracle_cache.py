@@ -1,0 +1,106 @@
+"""Oracle scores for the named workloads, with an on-disk cache.
+
+The expected values are always produced by `oracle.forward` (nothing else); because the big
+workloads take minutes of fp64 numpy per request, results are cached as .npy files keyed by a hash
+of the exact inputs.  Running this file as a script fills the cache:
+
+    python tests/oracle_cache.py [workload ...]
+
+The cache is an accelerator only: when a file is missing the tests compute the values in place.
+"""
+from __future__ import annotations
+
+import hashlib
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import oracle  # noqa: E402
+from paper_2509_22681_amd import workloads as W  # noqa: E402
+
+CACHE_DIR = os.path.join(ROOT, "tests", "golden", "cache")
+
+# requests whose oracle scores are compared at the full benchmark sizes (all requests where None)
+SAMPLED = {
+    "tiny_f32": None,
+    "uniform": None,
+    "jagged": None,
+    "long": [0, 11],
+    "production": "spread",     # smallest, median and largest request by cost, plus two seeded picks
+}
+
+
+def sample_requests(wl: W.Workload, name: str):
+    spec = SAMPLED[name]
+    if spec is None:
+        return list(range(wl.n_requests))
+    if spec == "spread":
+        L, M = wl.L.astype(np.int64), wl.M.astype(np.int64)
+        cost = 10 * (L + M) * wl.cfg.d_model + 4 * (L * (L + 1) // 2 + M * (L + 1))
+        order = np.argsort(cost, kind="stable")
+        picks = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+        rng = np.random.default_rng(12345)
+        for r in rng.permutation(wl.n_requests):
+            if int(r) not in picks:
+                picks.append(int(r))
+            if len(picks) == 5:
+                break
+        return picks
+    return list(spec)
+
+
+_weights_digest = {}
+
+
+def _key(wl: W.Workload, i: int) -> str:
+    wd = _weights_digest.get(id(wl.weights))
+    if wd is None:
+        hw = hashlib.sha1()
+        for k in sorted(wl.weights):
+            hw.update(np.ascontiguousarray(wl.weights[k]).tobytes())
+        wd = _weights_digest[id(wl.weights)] = hw.digest()
+    h = hashlib.sha1(wd)
+    ho, co = wl.history_offsets, wl.cand_offsets
+    h.update(repr(sorted(wl.cfg.to_dict().items())).encode())
+    h.update(np.ascontiguousarray(wl.history_emb[ho[i]:ho[i + 1]]).tobytes())
+    h.update(np.ascontiguousarray(wl.cand_emb[co[i]:co[i + 1]]).tobytes())
+    return h.hexdigest()[:20]
+
+
+def request_scores(wl: W.Workload, i: int, verbose: bool = False) -> np.ndarray:
+    """Oracle scores of request i of a workload (cached)."""
+    path = os.path.join(CACHE_DIR, f"{wl.name}_req{i}_{_key(wl, i)}.npy")
+    if os.path.exists(path):
+        return np.load(path)
+    t = time.time()
+    ho, co = wl.history_offsets, wl.cand_offsets
+    s = oracle.forward_request(wl.cfg.to_dict(), wl.weights, wl.history_emb[ho[i]:ho[i + 1]],
+                               wl.cand_emb[co[i]:co[i + 1]])
+    if verbose:
+        print(f"  oracle {wl.name} request {i}: L={ho[i + 1] - ho[i]} M={co[i + 1] - co[i]} "
+              f"{time.time() - t:.1f}s", flush=True)
+    try:
+        os.makedirs(CACHE_DIR, exist_ok=True)
+        tmp = path + f".tmp{os.getpid()}.npy"
+        np.save(tmp, s)
+        os.replace(tmp, path)
+    except OSError:
+        pass
+    return s
+
+
+def main(names):
+    for name in names:
+        wl = W.make_workload(name)
+        for i in sample_requests(wl, name):
+            request_scores(wl, i, verbose=True)
+
+
+if __name__ == "__main__":
+    main(sys.argv[1:] or list(SAMPLED))

@@ -1,0 +1,267 @@
+"""GPU parity: the HIP library, called through its C ABI, against the fp64 CPU oracle.
+
+Error measure for scores (logits cross zero, so a plain relative error is unbounded there):
+    err = max_j |g_j - o_j| / max(|o_j|, rms(o))
+Bars: 1e-4 for the fp32 path, 2e-2 for the bf16 path.  Intermediate tensors are compared with
+max |g - o| / rms(o) per tensor so that a residual-dominated score cannot hide a broken branch.
+Integer outputs (offsets, mask, buckets) must match bit for bit.
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2509_22681_amd import workloads as W
+from tests.oracle_cache import request_scores, sample_requests
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+STAGE_TOL = {"f32": 2e-4, "bf16": 3e-2}
+
+
+@pytest.fixture(scope="module")
+def B():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2509_22681_amd import binding
+    return binding
+
+
+def score_err(g, o):
+    g, o = np.asarray(g, np.float64), np.asarray(o, np.float64)
+    if o.size == 0:
+        return 0.0
+    rms = np.sqrt(np.mean(o * o))
+    return float(np.max(np.abs(g - o) / np.maximum(np.abs(o), rms)))
+
+
+def run_gpu(B, wl, *, n_streams=0, max_seq_tokens=0, capture=None, repeat=1):
+    import torch
+    cfg = B.config_for(wl, n_streams=n_streams, max_seq_tokens=max_seq_tokens)
+    if max_seq_tokens:
+        # splitting re-runs histories: give the workspace room for the copies
+        cfg.max_total_tokens = int(cfg.max_total_tokens * 8 + 1024)
+        cfg.max_requests = int(cfg.max_requests * 16 + 16)
+    h = B.flame_gr_create(cfg)
+    try:
+        dw, hist, cand = B.to_device(wl)
+        scores = torch.full((int(wl.cand_offsets[-1]),), float("nan"), device="cuda:0", dtype=torch.float32)
+        if capture is not None:
+            B.flame_gr_debug_capture(h, capture)
+        outs = []
+        for _ in range(repeat):
+            scores.fill_(float("nan"))
+            B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+            torch.cuda.synchronize()
+            outs.append(scores.cpu().numpy().copy())
+        stages = None
+        if capture is not None:
+            n_tok = int(wl.history_offsets[-1] + wl.cand_offsets[-1])
+            stages = {n: B.flame_gr_debug_stage(h, k, n_tok, wl.cfg.d_model)
+                      for k, n in enumerate(["U", "V", "Q", "K", "O", "X"])}
+        return outs if repeat > 1 else outs[0], stages
+    finally:
+        B.flame_gr_destroy(h)
+
+
+def oracle_all(wl, stages=None):
+    return oracle.forward(wl.cfg.to_dict(), wl.weights, wl.history_emb, wl.history_offsets, wl.cand_emb,
+                          wl.cand_offsets, stages)
+
+
+def stress(L, M, d, H, dtype, *, layers=2, nb=16, D=None, seed=7, name="stress", hot=True):
+    if hot:   # pre-activations of order +-5: exercises the SiLU tails, the bias and the affine terms
+        return W.make_custom(L, M, d=d, H=H, n_layers=layers, n_buckets=nb, max_rel_dist=D, dtype=dtype, seed=seed,
+                             emb_std=1.0, rab_std=1.0, bias_amp=0.1, affine_random=True, name=name)
+    return W.make_custom(L, M, d=d, H=H, n_layers=layers, n_buckets=nb, max_rel_dist=D, dtype=dtype, seed=seed, name=name)
+
+
+STRESS = {
+    # config-1 shape, hot values
+    "S1": dict(L=[64], M=[16], d=64, H=2, nb=128, D=128),
+    # empty history, single item, no candidates, far buckets and clamping (D = 256 < L)
+    "S2": dict(L=[0, 1, 300], M=[2, 0, 5], d=64, H=2, nb=16, D=256),
+    # lengths that are multiples of no tile size
+    "S3": dict(L=[700], M=[130], d=128, H=2, nb=16, D=1024),
+    # several ragged requests, head width 128
+    "S4": dict(L=[65, 127, 129, 3], M=[1, 63, 65, 200], d=128, H=1, nb=32, D=128),
+}
+
+
+# ------------------------------------------------------------------ integers, bit exact
+def test_device_mask_and_buckets_bit_exact(B):
+    for (L, M, nb, D) in [(64, 16, 128, 128), (0, 2, 16, 256), (1, 0, 16, 256), (300, 5, 16, 256), (700, 130, 16, 1024)]:
+        cfg = B.make_config(1, 64, 2, nb, D, "f32", max_requests=1, max_total_tokens=L + M)
+        h = B.flame_gr_create(cfg)
+        try:
+            mask, bucket = B.flame_gr_debug_device_mask(h, L, M)
+        finally:
+            B.flame_gr_destroy(h)
+        assert np.array_equal(mask.astype(bool), oracle.allow_mask(L, M))
+        assert np.array_equal(bucket, oracle.bucket_matrix(L, M, nb, D))
+
+
+# ------------------------------------------------------------------ fp32 path
+def test_tiny_f32_scores(B):
+    wl = W.make_workload("tiny_f32")
+    g, _ = run_gpu(B, wl)
+    o = oracle_all(wl)
+    assert score_err(g, o) <= TOL["f32"]
+
+
+@pytest.mark.parametrize("case", list(STRESS))
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stress_scores_and_stages(B, case, dtype):
+    wl = stress(dtype=dtype, name=case, **STRESS[case])
+    ost = []
+    o = oracle_all(wl, ost)
+    for layer in range(wl.cfg.n_layers):
+        g, st = run_gpu(B, wl, capture=layer)
+        assert not np.isnan(g).any()
+        assert score_err(g, o) <= TOL[dtype], (case, dtype, "scores", score_err(g, o))
+        for name in ["U", "V", "Q", "K", "O", "X"]:
+            ref = np.concatenate([ost[i][layer][name] for i in range(wl.n_requests)], 0)
+            rms = np.sqrt(np.mean(ref * ref)) + 1e-300
+            err = float(np.max(np.abs(st[name] - ref)) / rms)
+            assert err <= STAGE_TOL[dtype], (case, dtype, layer, name, err)
+
+
+def test_stress_without_capture_matches_with_capture(B):
+    """Capturing switches the last-layer pruning off; the scores must not notice."""
+    for dtype in ["f32", "bf16"]:
+        wl = stress(dtype=dtype, name="S3", **STRESS["S3"])
+        g0, _ = run_gpu(B, wl)
+        g1, _ = run_gpu(B, wl, capture=wl.cfg.n_layers - 1)
+        assert score_err(g0, oracle_all(wl)) <= TOL[dtype]
+        assert np.allclose(g0, g1, rtol=1e-5, atol=1e-6)
+
+
+# ------------------------------------------------------------------ the five benchmark workloads
+@pytest.mark.parametrize("name", ["uniform", "jagged", "long", "production"])
+def test_benchmark_workload_scores(B, name):
+    wl = W.make_workload(name)
+    g, _ = run_gpu(B, wl)
+    assert np.isfinite(g).all()
+    co = wl.cand_offsets
+    worst = 0.0
+    for i in sample_requests(wl, name):
+        o = request_scores(wl, i)
+        worst = max(worst, score_err(g[co[i]:co[i + 1]], o))
+    print(f"{name}: max score error {worst:.3e}")
+    assert worst <= TOL["bf16"]
+
+
+# ------------------------------------------------------------------ invariants on the GPU
+def test_determinism_and_batch_independence(B):
+    wl = stress(dtype="bf16", name="S4", hot=True, **STRESS["S4"])
+    (a, b), _ = run_gpu(B, wl, repeat=2)
+    assert np.array_equal(a, b)                       # fixed reduction order, no atomics
+    co = wl.cand_offsets
+    for i in range(wl.n_requests):
+        alone, _ = run_gpu(B, wl.subset([i]))
+        assert np.array_equal(alone, a[co[i]:co[i + 1]])   # a request never sees its neighbours
+    rev, _ = run_gpu(B, wl.subset(list(reversed(range(wl.n_requests)))))
+    want = np.concatenate([a[co[i]:co[i + 1]] for i in reversed(range(wl.n_requests))])
+    assert np.array_equal(rev, want)
+
+
+def test_candidate_permutation_and_alone(B):
+    for dtype in ["f32", "bf16"]:
+        wl = stress([150], [70], 64, 2, dtype, nb=16, D=256, name="perm")
+        g, _ = run_gpu(B, wl)
+        perm = np.random.default_rng(3).permutation(70)
+        wp = W.Workload("perm2", wl.cfg, wl.history_offsets, wl.cand_offsets, wl.history_emb, wl.cand_emb[perm], wl.weights)
+        gp, _ = run_gpu(B, wp)
+        tol = dict(rtol=1e-5, atol=1e-6) if dtype == "f32" else dict(rtol=0, atol=0)
+        assert np.allclose(gp, g[perm], **tol)
+        one = W.Workload("one", wl.cfg, wl.history_offsets, np.array([0, 1], np.int32), wl.history_emb, wl.cand_emb[5:6], wl.weights)
+        g1, _ = run_gpu(B, one)
+        assert np.allclose(g1[0], g[5], **(tol if dtype == "f32" else dict(rtol=1e-6, atol=1e-7)))
+
+
+def test_neighbour_garbage_does_not_leak(B):
+    """Huge finite values in the rows of the neighbouring requests leave a request's scores alone."""
+    wl = stress([100, 37, 90], [20, 9, 33], 64, 1, "bf16", nb=16, D=128, name="leak")
+    g, _ = run_gpu(B, wl)
+    h2, c2 = wl.history_emb.copy(), wl.cand_emb.copy()
+    ho, co = wl.history_offsets, wl.cand_offsets
+    h2[ho[0]:ho[1]] = 3.0e4
+    h2[ho[2]:ho[3]] = -3.0e4
+    c2[co[0]:co[1]] = 3.0e4
+    c2[co[2]:co[3]] = -3.0e4
+    g2, _ = run_gpu(B, W.Workload("leak2", wl.cfg, ho, co, h2, c2, wl.weights))
+    assert np.array_equal(g2[co[1]:co[2]], g[co[1]:co[2]])
+
+
+# ------------------------------------------------------------------ batcher: streams and splitting
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_stream_groups_and_split_routing_change_nothing(B, dtype):
+    wl = stress([200, 10, 64, 333, 0], [40, 300, 1, 17, 5], 64, 2, dtype, nb=16, D=512, name="batcher")
+    base, _ = run_gpu(B, wl)
+    assert score_err(base, oracle_all(wl)) <= TOL[dtype]
+    for ns in (2, 3, 5):
+        g, _ = run_gpu(B, wl, n_streams=ns)
+        assert np.array_equal(g, base), f"n_streams={ns}"
+    # requests longer than 128 tokens are split by candidates, largest chunk first
+    g, _ = run_gpu(B, wl.subset([1, 2, 4]), max_seq_tokens=128)
+    co = wl.cand_offsets
+    want = np.concatenate([base[co[i]:co[i + 1]] for i in (1, 2, 4)])
+    if dtype == "f32":
+        assert np.allclose(g, want, rtol=1e-5, atol=1e-6)
+    else:
+        assert np.array_equal(g, want)
+
+
+# ------------------------------------------------------------------ edge cases and errors
+def test_empty_and_degenerate_batches(B):
+    import torch
+    wl = stress([5, 0, 0], [0, 0, 3], 64, 2, "bf16", nb=16, D=128, name="edge")
+    g, _ = run_gpu(B, wl)
+    assert score_err(g, oracle_all(wl)) <= TOL["bf16"]
+    cfg = B.config_for(wl)
+    h = B.flame_gr_create(cfg)
+    try:
+        dw, hist, cand = B.to_device(wl)
+        scores = torch.zeros(3, device="cuda:0")
+        B.flame_gr_forward(h, dw, None, np.zeros(1, np.int32), None, np.zeros(1, np.int32), None)      # B = 0
+        B.flame_gr_forward(h, dw, hist, np.array([0, 5], np.int32), None, np.array([0, 0], np.int32), None)  # no candidates
+        torch.cuda.synchronize()
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_forward(h, dw, hist, np.array([1, 5], np.int32), cand, np.array([0, 3], np.int32), scores)
+        assert e.value.code == -1
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_forward(h, dw, hist, np.array([0, 5, 3], np.int32), cand, np.array([0, 0, 3], np.int32), scores)
+        assert e.value.code == -1
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_forward(h, dw, hist, np.array([0, 5000], np.int32), cand, np.array([0, 3], np.int32), scores)
+        assert e.value.code == -2
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_forward(h, dw, None, np.array([0, 5], np.int32), cand, np.array([0, 3], np.int32), scores)
+        assert e.value.code == -1
+        # the handle still works after the rejected calls
+        scores.fill_(float("nan"))
+        B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+        torch.cuda.synchronize()
+        assert np.array_equal(scores.cpu().numpy(), g)
+    finally:
+        B.flame_gr_destroy(h)
+
+
+def test_forward_on_a_side_stream_and_back_to_back(B):
+    import torch
+    wl = stress([90, 40], [30, 10], 64, 2, "bf16", nb=16, D=128, name="streams")
+    ref, _ = run_gpu(B, wl)
+    h = B.flame_gr_create(B.config_for(wl))
+    try:
+        dw, hist, cand = B.to_device(wl)
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        torch.cuda.synchronize()
+        a = torch.zeros(40, device="cuda:0")
+        b = torch.zeros(40, device="cuda:0")
+        B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, a, stream=s1)
+        B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, b, stream=s2)
+        B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, a, stream=s1)
+        torch.cuda.synchronize()
+        assert np.array_equal(a.cpu().numpy(), ref) and np.array_equal(b.cpu().numpy(), ref)
+    finally:
+        B.flame_gr_destroy(h)

@@ -1,0 +1,154 @@
+"""CPU-only tests of the library's host logic (no GPU, no compute calls).
+
+Checks that the C-ABI library loads and exports every declared symbol, and that its integer
+planning (bucket table, mask, merged offsets, segment layout, descending-size split, stream
+groups) agrees bit for bit with the oracle's independent implementation.
+"""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+from hypothesis import given, settings, strategies as st
+
+import oracle
+from paper_2509_22681_amd import binding as B
+from paper_2509_22681_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "flame_gr.h")).read()
+    declared = set(re.findall(r"\b(flame_gr_[a-z_]+)\s*\(", header))
+    assert {"flame_gr_create", "flame_gr_forward", "flame_gr_destroy"} <= declared
+    lib = ctypes.CDLL(B.LIB_PATH)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert declared == set(B.EXPORTS)
+
+
+@pytest.mark.parametrize("nb,D", [(128, 128), (128, 1024), (128, 4096), (128, 8192), (512, 16384),
+                                  (16, 512), (16, 256), (8, 32), (4, 4), (2, 2), (4, 8), (32, 128)])
+def test_bucket_table_matches_oracle(nb, D):
+    assert np.array_equal(B.flame_gr_host_bucket_table(nb, D), oracle.bucket_table(nb, D))
+
+
+def test_bucket_table_rejects_bad_shapes():
+    for nb, D in [(3, 8), (0, 8), (16, 4), (16, 100), (2, 8)]:
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_host_bucket_table(nb, D)
+        assert e.value.code == -1
+
+
+@pytest.mark.parametrize("L,M,nb,D", [(3, 2, 8, 8), (64, 16, 128, 128), (0, 4, 16, 256), (5, 0, 16, 256),
+                                      (300, 5, 16, 256), (0, 0, 4, 4)])
+def test_host_mask_matches_oracle(L, M, nb, D):
+    mask, bucket = B.flame_gr_host_mask(L, M, nb, D)
+    assert np.array_equal(mask.astype(bool), oracle.allow_mask(L, M))
+    assert np.array_equal(bucket, oracle.bucket_matrix(L, M, nb, D))
+
+
+def _cfg(dtype="bf16", **kw):
+    base = dict(n_layers=2, d_model=64, n_heads=2, n_buckets=16, max_rel_dist=1024, dtype=dtype,
+                max_requests=64, max_total_tokens=1 << 20)
+    base.update(kw)
+    return B.make_config(**base)
+
+
+def _check_layout(seg, ho, co, n_groups):
+    """Segments tile the candidates of every request exactly once, rows are aligned and disjoint."""
+    Bn = len(ho) - 1
+    covered = [[] for _ in range(Bn)]
+    end_prev = 0
+    for s in seg:
+        req, L, cb, M, row, grp = (int(v) for v in s)
+        assert L == ho[req + 1] - ho[req]
+        assert row % 64 == 0 and row >= end_prev
+        end_prev = row + (L + 63) // 64 * 64 + (M + 63) // 64 * 64
+        covered[req].append((cb, M))
+        assert 0 <= grp < n_groups
+    for i in range(Bn):
+        assert covered[i], f"request {i} has no segment"
+        pos = 0
+        for cb, M in sorted(covered[i]):
+            assert cb == pos
+            pos += M
+        assert pos == co[i + 1] - co[i]
+    assert list(seg[:, 5]) == sorted(seg[:, 5])       # groups occupy contiguous row ranges
+
+
+lens = st.lists(st.tuples(st.integers(0, 400), st.integers(0, 300)), min_size=0, max_size=12)
+
+
+@settings(max_examples=60, deadline=None)
+@given(lens, st.integers(1, 5))
+def test_plan_offsets_and_layout(lm, n_streams):
+    L = [a for a, _ in lm]
+    M = [b for _, b in lm]
+    ho = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
+    co = np.concatenate([[0], np.cumsum(M)]).astype(np.int32)
+    tok, seg = B.flame_gr_host_plan(_cfg(n_streams=n_streams), ho, co)
+    assert np.array_equal(tok, oracle.merged_token_offsets(ho, co))
+    assert len(seg) == len(L)
+    _check_layout(seg, ho, co, n_streams)
+
+
+def test_descending_split_routing():
+    ho = np.array([0, 100, 130], np.int32)
+    co = np.array([0, 250, 260], np.int32)
+    tok, seg = B.flame_gr_host_plan(_cfg(max_seq_tokens=200), ho, co)
+    _check_layout(seg, ho, co, 1)
+    chunks = [(int(s[2]), int(s[3])) for s in seg if s[0] == 0]
+    assert sorted(chunks) == [(0, 100), (100, 100), (200, 50)]          # largest first, remainder last
+    assert [int(s[3]) for s in seg if s[0] == 1] == [10]
+    with pytest.raises(B.FlameGRError) as e:                            # history alone fills the limit
+        B.flame_gr_host_plan(_cfg(max_seq_tokens=100), ho, co)
+    assert e.value.code == -2
+
+
+def test_stream_groups_are_cost_balanced():
+    wl = W.make_workload("production", lengths_only=True)
+    cfg = B.make_config(16, 512, 8, 128, 8192, "bf16", max_requests=128, max_total_tokens=1 << 20, n_streams=4)
+    _, seg = B.flame_gr_host_plan(cfg, wl.history_offsets, wl.cand_offsets)
+    L, M = seg[:, 1].astype(np.float64), seg[:, 3].astype(np.float64)
+    cost = 10 * (L + M) * 512 * 512 + 4 * (L * (L + 1) / 2 + M * (L + 1)) * 512
+    per = np.array([cost[seg[:, 5] == g].sum() for g in range(4)])
+    assert per.max() / per.min() < 1.05
+    for g in range(4):                                                   # big requests first inside a group
+        c = cost[seg[:, 5] == g]
+        assert (np.diff(c) <= 0).all()
+
+
+def test_offset_validation_codes():
+    good_h, good_c = np.array([0, 5, 9], np.int32), np.array([0, 2, 2], np.int32)
+    B.flame_gr_host_plan(_cfg(), good_h, good_c)
+    for ho, co, code in [([1, 5, 9], [0, 2, 2], -1), ([0, 5, 4], [0, 2, 2], -1), ([0, 5, 9], [0, 2, 1], -1),
+                         ([0, 5, 9], [3, 3, 3], -1)]:
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_host_plan(_cfg(), np.array(ho, np.int32), np.array(co, np.int32))
+        assert e.value.code == code
+    with pytest.raises(B.FlameGRError) as e:
+        B.flame_gr_host_plan(_cfg(max_requests=1), good_h, good_c)
+    assert e.value.code == -2
+    with pytest.raises(B.FlameGRError) as e:
+        B.flame_gr_host_plan(_cfg(max_total_tokens=10), good_h, good_c)
+    assert e.value.code == -2
+
+
+def test_config_validation_codes():
+    ho, co = np.array([0, 4], np.int32), np.array([0, 2], np.int32)
+    for kw, code in [(dict(n_layers=0), -1), (dict(d_model=65), -1), (dict(n_buckets=12), -1),
+                     (dict(max_rel_dist=1000), -1), (dict(dtype=7), -1), (dict(n_streams=99), -1),
+                     (dict(d_model=96, n_heads=2), -5), (dict(d_model=64, n_heads=4), -5)]:
+        with pytest.raises(B.FlameGRError) as e:
+            B.flame_gr_host_plan(_cfg(**kw), ho, co)
+        assert e.value.code == code, kw
+    # the fp32 path has no such shape restrictions
+    B.flame_gr_host_plan(_cfg(dtype="f32", d_model=96, n_heads=2), ho, co)
+
+
+def test_destroy_null_is_a_noop_and_bad_handle_is_reported():
+    assert B._lib.flame_gr_destroy(None) == 0
+    assert B._lib.flame_gr_forward(None, None, None, None, None, None, 0, None, None) == -4
