@@ -1,0 +1,193 @@
+#!/usr/bin/env python3
+"""Throughput benchmark of the GR forward on one MI355X.
+
+A step is one flame_gr_forward over the whole synthetic batch (all kernels of the hot path).
+Inputs are resident in HBM before the timed region.  Prints ONE JSON line:
+candidate scores/s, ms per step, the roofline of the dominant kernel (attention, bf16 MFMA) from
+HIP-event timings taken on the launch stream inside the timed region, and the CPU oracle timed on
+a bounded sample of the same workload on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+
+
+def attention_flops_per_layer(cfg, L, M):
+    """(full layer, last layer) algorithmic attention flops: 4*d per allowed (query, key) pair."""
+    L = L.astype(np.float64)
+    M = M.astype(np.float64)
+    full = 4.0 * cfg.d_model * (L * (L + 1) / 2 + M * (L + 1)).sum()
+    last = 4.0 * cfg.d_model * (M * (L + 1)).sum()
+    return full, last
+
+
+def cpu_baseline(wl, budget_s=12.0):
+    """Time the fp64 oracle on the cheapest requests of the workload until the budget is used, then
+    scale to the whole batch by the cost model (algorithmic flops)."""
+    import oracle
+    from paper_2509_22681_amd import workloads as W
+    L, M = wl.L.astype(np.int64), wl.M.astype(np.int64)
+    cost = np.array([W.algorithmic_flops(wl.cfg, L[i:i + 1], M[i:i + 1], pruned=False) for i in range(wl.n_requests)])
+    order = np.argsort(cost, kind="stable")
+    cfgd = wl.cfg.to_dict()
+    ho, co = wl.history_offsets, wl.cand_offsets
+    t0 = time.perf_counter()
+    done, flops, nsc = [], 0.0, 0
+    for i in order:
+        oracle.forward_request(cfgd, wl.weights, wl.history_emb[ho[i]:ho[i + 1]], wl.cand_emb[co[i]:co[i + 1]])
+        done.append(int(i))
+        flops += cost[i]
+        nsc += int(M[i])
+        if time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    total_flops = float(cost.sum())
+    est_total_s = dt * total_flops / flops
+    return {
+        "value": float(M.sum()) / est_total_s, "unit": "candidate scores/s", "cores": len(os.sched_getaffinity(0)),
+        "kind": "oracle",
+        "sample": f"{len(done)} cheapest of {wl.n_requests} requests ({nsc} scores, {flops:.3g} flop) in {dt:.1f} s; "
+                  f"whole batch extrapolated by flops to {est_total_s:.0f} s",
+        "oracle_gflops": flops / dt * 1e-9,
+    }
+
+
+def request_mode_latency(B, wl, dw, hist, cand, max_requests=64):
+    """Requests submitted one per call on one executor: per-request compute latency (submit -> scores ready)."""
+    import torch
+    Bn = wl.n_requests
+    idx = list(range(Bn)) if Bn <= max_requests else list(np.linspace(0, Bn - 1, max_requests).astype(int))
+    L, M = wl.L, wl.M
+    c = wl.cfg
+    cfg = B.make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype, ln_eps=c.ln_eps,
+                        attn_scale=c.attn_scale, max_requests=1, max_total_tokens=int((L + M).max()))
+    h = B.flame_gr_create(cfg)
+    ws = B.pack_weights(dw)
+    ho, co = wl.history_offsets, wl.cand_offsets
+    scores = torch.zeros(int(M.max()), device="cuda:0", dtype=torch.float32)
+    lat = []
+    try:
+        for rep in range(2):           # first pass warms up
+            lat = []
+            for i in idx:
+                hh, cc = hist[ho[i]:ho[i + 1]], cand[co[i]:co[i + 1]]
+                o1 = np.array([0, L[i]], np.int32)
+                o2 = np.array([0, M[i]], np.int32)
+                torch.cuda.synchronize()
+                t = time.perf_counter()
+                B.flame_gr_forward(h, ws, hh, o1, cc, o2, scores)
+                torch.cuda.synchronize()
+                lat.append((time.perf_counter() - t) * 1e3)
+    finally:
+        B.flame_gr_destroy(h)
+    lat = np.array(lat)
+    return {"p50_ms": float(np.percentile(lat, 50)), "p99_ms": float(np.percentile(lat, 99)),
+            "mean_ms": float(lat.mean()), "requests": len(idx),
+            "scores_per_s": float(M[idx].sum() / (lat.sum() * 1e-3))}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="production", help="tiny_f32 | uniform | jagged | long | production")
+    ap.add_argument("--streams", type=int, default=0, help="internal stream groups of the batcher (0/1 = caller's stream)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-latency", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (requests are independent; more GPUs would each run this same "
+              "library on a share of the requests, with no collective). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2509_22681_amd import binding as B
+    from paper_2509_22681_amd import workloads as W
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    wl = W.make_workload(args.workload)
+    cfg = wl.cfg
+    dw, hist, cand = B.to_device(wl)
+    ws = B.pack_weights(dw)
+    n_scores = int(wl.cand_offsets[-1])
+    scores = torch.zeros(n_scores, device="cuda:0", dtype=torch.float32)
+    h = B.flame_gr_create(B.config_for(wl, n_streams=args.streams))
+    try:
+        for _ in range(args.warmup):
+            B.flame_gr_forward(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+        torch.cuda.synchronize()
+        # timed region: K forwards, per-kernel HIP events recorded on the launch stream
+        B.flame_gr_debug_profile(h, True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            B.flame_gr_forward(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        prof = B.flame_gr_debug_profile_read(h)
+        B.flame_gr_debug_profile(h, False)
+        assert torch.isfinite(scores).all().item(), "non-finite scores"
+        # the same K steps without the per-kernel events, to show what the events cost
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            B.flame_gr_forward(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+        torch.cuda.synchronize()
+        dt_plain = time.perf_counter() - t1
+    finally:
+        B.flame_gr_destroy(h)
+
+    ms_per_step = dt / args.steps * 1e3
+    flops_pruned = W.algorithmic_flops(cfg, wl.L, wl.M, pruned=True)
+    flops_full = W.algorithmic_flops(cfg, wl.L, wl.M, pruned=False)
+    full, last = attention_flops_per_layer(cfg, wl.L, wl.M)
+    attn_ms, attn_launches = prof["attn"]
+    attn_flops_per_step = (cfg.n_layers - 1) * full + last
+    attn_avg_ms = attn_ms / max(attn_launches, 1)
+    attn_flops_per_launch = attn_flops_per_step / cfg.n_layers
+    achieved = attn_flops_per_launch / (attn_avg_ms * 1e-3) * 1e-12 if attn_avg_ms > 0 else 0.0
+    out = {
+        "metric": "candidate scores/sec + p50 request latency, 1 MI355X; % of bf16 MFMA peak",
+        "value": n_scores / (dt / args.steps),
+        "unit": "candidate scores/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "requests": wl.n_requests, "sum_L": int(wl.L.sum()), "sum_M": n_scores,
+                   "d_model": cfg.d_model, "n_heads": cfg.n_heads, "n_layers": cfg.n_layers,
+                   "batcher_streams": max(args.streams, 1)},
+        "algorithmic_flops_per_step": flops_pruned,
+        "algorithmic_flops_unpruned": flops_full,
+        "pct_of_bf16_mfma_peak": 100.0 * flops_pruned / (dt / args.steps) / (PEAK_BF16_TFLOPS * 1e12),
+        "ms_per_step_without_kernel_events": dt_plain / args.steps * 1e3,
+        "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
+        "roofline": {"kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
+                     "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "avg_launch_ms": attn_avg_ms, "launches": attn_launches,
+                     "algorithmic_flops_per_launch": attn_flops_per_launch},
+    }
+    if not args.no_latency:
+        out["request_latency"] = request_mode_latency(B, wl, dw, hist, cand)
+        out["p50_request_latency_ms"] = out["request_latency"]["p50_ms"]
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

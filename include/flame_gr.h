@@ -170,9 +170,10 @@ int flame_gr_debug_device_mask(flame_gr_t *h, int32_t L, int32_t M, uint8_t *mas
  * adds event overhead, so leave it off when timing whole forwards). */
 int flame_gr_debug_profile(flame_gr_t *h, int32_t enable);
 
-/* After a profiled forward: summed milliseconds and launch counts of its kernels by kind, HOST
- * arrays of 7 entries in the order assemble, bias expansion, UVQK projection, attention,
- * LayerNorm-gate, output projection, score head.  Waits for the forward to finish. */
+/* Summed milliseconds and launch counts, by kernel kind, of all forwards since profiling was
+ * enabled or last read: HOST arrays of 7 entries in the order assemble, bias expansion, UVQK
+ * projection, attention, LayerNorm-gate, output projection, score head.  Waits for the last forward
+ * to finish, then resets the sums. */
 int flame_gr_debug_profile_read(flame_gr_t *h, float *ms_by_kind, int32_t *launches_by_kind);
 
 #ifdef __cplusplus

@@ -12,6 +12,10 @@ import os
 from typing import Dict, Optional
 
 import numpy as np
+# PyTorch provides device memory and streams.  It must be imported before the library is loaded so
+# that both resolve libamdhip64.so.7 to the one HIP runtime PyTorch bundles: two HIP runtimes in one
+# process do not both see the device.
+import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libflame_gr.so")
@@ -136,7 +140,6 @@ def flame_gr_forward(h, weights, history_emb, history_offsets, cand_emb, cand_of
     if len(co) - 1 != n:
         raise ValueError("offset arrays differ in length")
     if stream is None:
-        import torch
         sp = torch.cuda.current_stream().cuda_stream
     else:
         sp = getattr(stream, "cuda_stream", stream)
@@ -213,7 +216,6 @@ def flame_gr_debug_profile_read(h):
 def to_device(workload, device="cuda:0"):
     """Upload a workloads.Workload: returns (cfg struct fields dict, weights dict, hist, cand) as
     torch tensors of the workload's storage dtype (bf16 values are already exactly representable)."""
-    import torch
     dt = torch.bfloat16 if workload.cfg.dtype == "bf16" else torch.float32
 
     def up(a, dtype=dt):

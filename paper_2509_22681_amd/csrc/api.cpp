@@ -182,15 +182,15 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
     }
     if (h->capture_layer == l && h->cap_planes) {
       const size_t r0 = (size_t)G.row_begin * d, nr = (size_t)(G.row_end - G.row_begin) * d;
-      if (dt == FLAME_GR_BF16) {
-        // U, Q, K are row-major planes; V is stored transposed ([d][ws_rows]) and copied whole by group 0
-        for (int p = 0; p < 4; ++p) {
-          if (p == 1) continue;
+      for (int p = 0; p < 4; ++p) {
+        if (dt == FLAME_GR_BF16 && p == 1) {
+          // V is stored feature-major ([d][ws_rows]): this group's tokens are a column range
+          const size_t off = ((size_t)plane + (size_t)G.row_begin) * e, pitch = (size_t)sh.ws_rows * e;
+          (void)hipMemcpy2DAsync((char *)h->cap_planes + off, pitch, (char *)h->planes + off, pitch,
+                                 (size_t)(G.row_end - G.row_begin) * e, (size_t)d, hipMemcpyDeviceToDevice, s);
+        } else {
           (void)hipMemcpyAsync((char *)h->cap_planes + ((size_t)p * plane + r0) * e, (char *)h->planes + ((size_t)p * plane + r0) * e, nr * e, hipMemcpyDeviceToDevice, s);
         }
-      } else {
-        for (int p = 0; p < 4; ++p)
-          (void)hipMemcpyAsync((char *)h->cap_planes + ((size_t)p * plane + r0) * e, (char *)h->planes + ((size_t)p * plane + r0) * e, nr * e, hipMemcpyDeviceToDevice, s);
       }
       (void)hipMemcpyAsync((char *)h->cap_O + r0 * e, (char *)h->O + r0 * e, nr * e, hipMemcpyDeviceToDevice, s);
       (void)hipMemcpyAsync(h->cap_X + r0, h->X + r0, nr * sizeof(float), hipMemcpyDeviceToDevice, s);
@@ -342,7 +342,6 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
     HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.cand_blocks, sh_ + h->lay.cand_blocks, P.cand_blocks.size() * sizeof(int32_t), hipMemcpyHostToDevice, s0));
   HIP_TRY(h, hipEventRecord(h->stage_done[slot], s0));
   h->stage_used[slot] = true;
-  h->prof_used = 0;
   {
     Timed t(h, KIND_BIAS, s0);
     launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D, s0);
@@ -358,11 +357,6 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
       HIP_TRY(h, hipEventRecord(h->ev_join[g], h->gstream[g]));
       HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_join[g], 0));
     }
-  }
-  if (h->capture_layer >= 0 && h->cap_planes && h->cfg.dtype == FLAME_GR_BF16) {
-    // transposed V plane, whole (after all groups have joined)
-    const size_t plane = (size_t)h->ws_rows * h->sh.d * h->elt;
-    (void)hipMemcpyAsync((char *)h->cap_planes + plane, (char *)h->planes + plane, plane, hipMemcpyDeviceToDevice, s0);
   }
   HIP_TRY(h, hipEventRecord(h->ev_done, s0));
   h->has_prev = true;
@@ -532,6 +526,7 @@ int flame_gr_debug_profile_read(flame_gr_t *h, float *ms_by_kind, int32_t *launc
     ms_by_kind[h->prof_pool[i].kind] += ms;
     launches_by_kind[h->prof_pool[i].kind] += 1;
   }
+  h->prof_used = 0;
   return FLAME_GR_OK;
 }
 
