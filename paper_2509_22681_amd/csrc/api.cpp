@@ -45,7 +45,8 @@ struct flame_gr {
   std::string err;
   // workspaces (device)
   float *X = nullptr;
-  void *Xb = nullptr, *planes = nullptr, *O = nullptr, *G = nullptr;
+  void *Xb = nullptr, *planes = nullptr, *O = nullptr, *G = nullptr;   // Xb: fp16 copy of X (MFMA path)
+  void *W1h = nullptr, *W2h = nullptr;                                   // fp16 copies of the projection matrices
   float *bias = nullptr;
   int32_t *bucket_tab = nullptr;
   // plan staging
@@ -85,9 +86,28 @@ namespace {
 
 bool live(const flame_gr *h) { return h && h->magic == kMagic; }
 
+// IEEE binary16 -> float on the host (debug export only)
+float half_bits_to_float(uint16_t b) {
+  const uint32_t sign = (uint32_t)(b & 0x8000u) << 16;
+  uint32_t exp = (b >> 10) & 0x1f, man = b & 0x3ffu, out;
+  if (exp == 0) {
+    if (man == 0) out = sign;
+    else {
+      int sh = 0;
+      while (!(man & 0x400u)) { man <<= 1; ++sh; }
+      out = sign | ((uint32_t)(113 - sh) << 23) | ((man & 0x3ffu) << 13);
+    }
+  } else if (exp == 31) out = sign | 0x7f800000u | (man << 13);
+  else out = sign | ((exp + 112) << 23) | (man << 13);
+  float f;
+  std::memcpy(&f, &out, 4);
+  return f;
+}
+
 void free_all(flame_gr *h) {
   (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->O); (void)hipFree(h->G);
   (void)hipFree(h->bias); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
+  (void)hipFree(h->W1h); (void)hipFree(h->W2h);
   (void)hipFree(h->cap_planes); (void)hipFree(h->cap_O); (void)hipFree(h->cap_X);
   for (int i = 0; i < kStageSlots; ++i) {
     if (h->stage_host[i]) (void)hipHostFree(h->stage_host[i]);
@@ -136,9 +156,9 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
   const int64_t plane = sh.ws_rows * d;
   for (int l = 0; l < sh.n_layers; ++l) {
     const bool last = (l == sh.n_layers - 1) && h->capture_layer != l;
-    const char *w1 = (const char *)w.w1 + (size_t)l * 4 * d * d * e;
+    const char *w1 = (const char *)(dt == FLAME_GR_BF16 ? h->W1h : w.w1) + (size_t)l * 4 * d * d * e;
     const char *b1 = (const char *)w.b1 + (size_t)l * 4 * d * e;
-    const char *w2 = (const char *)w.w2 + (size_t)l * d * d * e;
+    const char *w2 = (const char *)(dt == FLAME_GR_BF16 ? h->W2h : w.w2) + (size_t)l * d * d * e;
     const char *b2 = (const char *)w.b2 + (size_t)l * d * e;
     const char *lg = (const char *)w.ln_g + (size_t)l * d * e;
     const char *lb = (const char *)w.ln_b + (size_t)l * d * e;
@@ -247,7 +267,11 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   CR(hipMalloc(&h->planes, 4 * rows * d * e));
   CR(hipMalloc(&h->O, rows * d * e));
   CR(hipMalloc(&h->G, rows * d * e));
-  if (cfg.dtype == FLAME_GR_BF16) CR(hipMalloc(&h->Xb, rows * d * e));
+  if (cfg.dtype == FLAME_GR_BF16) {
+    CR(hipMalloc(&h->Xb, rows * d * e));
+    CR(hipMalloc(&h->W1h, (size_t)cfg.n_layers * 4 * d * d * e));
+    CR(hipMalloc(&h->W2h, (size_t)cfg.n_layers * d * d * e));
+  }
   CR(hipMalloc(&h->bias, (size_t)cfg.n_layers * cfg.n_heads * cfg.max_rel_dist * sizeof(float)));
   CR(hipMalloc(&h->bucket_tab, (size_t)cfg.max_rel_dist * sizeof(int32_t)));
   // Every workspace starts finite: rows that a batch leaves as padding are read (and multiplied
@@ -344,6 +368,12 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   h->stage_used[slot] = true;
   {
     Timed t(h, KIND_BIAS, s0);
+    if (h->cfg.dtype == FLAME_GR_BF16) {
+      // the caller owns the weights and may have changed them: convert on every forward
+      const int64_t dd = (int64_t)h->sh.d * h->sh.d;
+      launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dd, s0);
+      launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dd, s0);
+    }
     launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D, s0);
   }
   if (h->n_groups == 1) {
@@ -471,10 +501,7 @@ int flame_gr_debug_stage(flame_gr_t *h, int32_t which, float *host_out) {
   auto get = [&](size_t row, size_t k) -> float {
     if (esz == 4) return ((const float *)raw.data())[row * d + k];
     const uint16_t *p = (const uint16_t *)raw.data();
-    uint32_t bits = (uint32_t)(transposed ? p[k * wsr + row] : p[row * d + k]) << 16;
-    float f;
-    std::memcpy(&f, &bits, 4);
-    return f;
+    return half_bits_to_float(transposed ? p[k * wsr + row] : p[row * d + k]);
   };
   // segments are in workspace order; the output is in request order (merged token offsets)
   for (const Segment &s : h->plan.segs) {

@@ -9,6 +9,10 @@ typedef __bf16 bf16_t;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 half_t;
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 
@@ -16,10 +20,18 @@ constexpr int kWave = 64;
 
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return (float)v; }
+__device__ __forceinline__ float to_f32(half_t v) { return (float)v; }
+
+// fp16 storage of an fp32 value: round to nearest even, saturating at the largest finite fp16 so
+// that an out-of-range activation degrades gracefully instead of turning into inf (and then NaN).
+__device__ __forceinline__ half_t to_f16_sat(float v) {
+  return (half_t)__builtin_fminf(__builtin_fmaxf(v, -65504.f), 65504.f);
+}
 
 template <typename T> __device__ __forceinline__ T from_f32(float v);
 template <> __device__ __forceinline__ float from_f32<float>(float v) { return v; }
 template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float v) { return (bf16_t)v; }  // round to nearest even
+template <> __device__ __forceinline__ half_t from_f32<half_t>(float v) { return to_f16_sat(v); }
 
 // silu(x) = x / (1 + exp(-x)).  exp2 of a large positive argument gives +inf and the quotient 0,
 // of a large negative one gives 0 and the quotient x: both limits are the right ones.

@@ -15,9 +15,11 @@ struct Shape {
 };
 
 // ---- shared small kernels (misc.hip) --------------------------------------------------------
-// X[rows of blocks) <- embeddings (fp32 copy, and a bf16 copy when Xb != nullptr); padding rows zeroed.
+// X[rows of blocks) <- embeddings (fp32 copy, and an fp16 copy Xh in the MFMA path); padding rows zeroed.
 void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
-                     const void *cand, float *X, void *Xb, int d, hipStream_t s);
+                     const void *cand, float *X, void *Xh, int d, hipStream_t s);
+// out[i] = fp16(in[i]) for n bf16 elements (n % 8 == 0)
+void launch_bf16_to_f16(const void *in, void *out, int64_t n, hipStream_t s);
 // bias[lh][delta] = rab[lh][bucket_tab[delta]] for all layers and heads.
 void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh,
                         int n_buckets, int D, hipStream_t s);
@@ -43,15 +45,16 @@ void launch_attn_f32(const float *planes, const float *bias_lh, float *O, const 
 void launch_outproj_f32(const float *G, const float *W2, const float *b2, float *X,
                         const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
-// ---- bf16 path (gemm_bf16.hip, attn_bf16.hip): MFMA kernels ----------------------------------
+// ---- bf16-storage path (gemm_mfma.hip, attn_mfma.hip): fp16 MFMA kernels, fp32 accumulation --------
+// Activations (Xh, planes, O, G) and the converted matrices W1h/W2h are fp16; biases stay bf16.
 // U, Q, K planes row-major [row][d]; the V plane is written transposed, Vt[n][row] (row stride ws_rows).
 // plane_mask bit p set = compute plane p (U=1, V=2, Q=4, K=8).
-void launch_uvqk_bf16(const void *Xb, const void *W1, const void *b1, void *planes, const int32_t *blk_list,
+void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
                       int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s);
 void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const AttnItem *items, int n_items,
                       const Shape &sh, hipStream_t s);
-// X[row] += G W2^T + b2, and Xb[row] = bf16(X[row])
-void launch_outproj_bf16(const void *G, const void *W2, const void *b2, float *X, void *Xb,
+// X[row] += G W2h^T + b2, and Xh[row] = fp16(X[row])
+void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
 constexpr int kAttnQTileBf16 = 128;  // query rows per attention work item, bf16 path

@@ -13,7 +13,7 @@ namespace flame {
 template <typename T>
 __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restrict__ blocks, int blk_begin,
                                                        const T *__restrict__ hist, const T *__restrict__ cand,
-                                                       float *__restrict__ X, bf16_t *__restrict__ Xb, int d) {
+                                                       float *__restrict__ X, half_t *__restrict__ Xh, int d) {
   const int b = blk_begin + blockIdx.x;
   const RowBlock rb = blocks[b];
   const T *src = rb.kind ? cand : hist;
@@ -24,16 +24,16 @@ __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restric
     float v = 0.f;
     if (i < nv) v = to_f32(src[(int64_t)rb.src_row * d + i]);
     X[dst0 + i] = v;
-    if (Xb) Xb[dst0 + i] = (bf16_t)v;
+    if (Xh) Xh[dst0 + i] = to_f16_sat(v);
   }
 }
 
 void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
-                     const void *cand, float *X, void *Xb, int d, hipStream_t s) {
+                     const void *cand, float *X, void *Xh, int d, hipStream_t s) {
   const int n = blk_end - blk_begin;
   if (n <= 0) return;
   if (dtype == FLAME_GR_BF16)
-    assemble_kernel<bf16_t><<<n, 256, 0, s>>>(blocks, blk_begin, (const bf16_t *)hist, (const bf16_t *)cand, X, (bf16_t *)Xb, d);
+    assemble_kernel<bf16_t><<<n, 256, 0, s>>>(blocks, blk_begin, (const bf16_t *)hist, (const bf16_t *)cand, X, (half_t *)Xh, d);
   else
     assemble_kernel<float><<<n, 256, 0, s>>>(blocks, blk_begin, (const float *)hist, (const float *)cand, X, nullptr, d);
 }
@@ -55,12 +55,35 @@ void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias
 }
 
 // ---------------------------------------------------------------------------------------------
+// bf16 -> fp16 copy of the projection matrices.  The MFMA path works on fp16 operands: with eight
+// to sixteen layers the 2^-9 rounding of bf16 intermediates alone puts about 1e-2 rms (5e-2 worst
+// case) on the scores, fp16's 2^-12 keeps them ten times closer; weights of magnitude >= 2^-14 are
+// represented exactly either way.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const bf16_t *__restrict__ in, half_t *__restrict__ out, int64_t n8) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+    const bf16x8 v = ((const bf16x8 *)in)[i];
+    f16x8 o;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = to_f16_sat((float)v[k]);
+    ((f16x8 *)out)[i] = o;
+  }
+}
+
+void launch_bf16_to_f16(const void *in, void *out, int64_t n, hipStream_t s) {
+  if (n <= 0) return;
+  const int64_t n8 = n / 8;   // every converted matrix has a multiple of 8 elements (d % 64 == 0)
+  int grid = (int)((n8 + 255) / 256 > 2048 ? 2048 : (n8 + 255) / 256);
+  bf16_to_f16_kernel<<<grid, 256, 0, s>>>((const bf16_t *)in, (half_t *)out, n8);
+}
+
+// ---------------------------------------------------------------------------------------------
 // G = (LayerNorm_d(O) * gamma + beta) * U.  One wavefront per row, statistics in fp32 by wavefront
 // reduction (mean first, then the centred second moment: biased variance).
 // ---------------------------------------------------------------------------------------------
-template <typename T, int MAXV>
+template <typename T, typename TW, int MAXV>   // T: activations (O, U, G); TW: stored weights (gamma, beta)
 __global__ __launch_bounds__(256) void ln_gate_kernel(const T *__restrict__ O, const T *__restrict__ U,
-                                                      const T *__restrict__ gamma, const T *__restrict__ beta,
+                                                      const TW *__restrict__ gamma, const TW *__restrict__ beta,
                                                       T *__restrict__ G, const RowBlock *__restrict__ blocks,
                                                       const int32_t *__restrict__ blk_list, int blk_first, int d,
                                                       float eps) {
@@ -101,11 +124,11 @@ __global__ __launch_bounds__(256) void ln_gate_kernel(const T *__restrict__ O, c
   }
 }
 
-template <typename T>
+template <typename T, typename TW>
 static void ln_gate_dispatch(const void *O, const void *U, const void *g, const void *b, void *G,
                              const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first, int d, float eps, hipStream_t s) {
   const int grid = n_blk * 16;
-#define LN_CASE(MV) ln_gate_kernel<T, MV><<<grid, 256, 0, s>>>((const T *)O, (const T *)U, (const T *)g, (const T *)b, (T *)G, blocks, blk_list, blk_first, d, eps)
+#define LN_CASE(MV) ln_gate_kernel<T, TW, MV><<<grid, 256, 0, s>>>((const T *)O, (const T *)U, (const TW *)g, (const TW *)b, (T *)G, blocks, blk_list, blk_first, d, eps)
   if (d <= 64) LN_CASE(1);
   else if (d <= 128) LN_CASE(2);
   else if (d <= 256) LN_CASE(4);
@@ -118,8 +141,8 @@ static void ln_gate_dispatch(const void *O, const void *U, const void *g, const 
 void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, const void *beta, void *G,
                     const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first, int d, float eps, hipStream_t s) {
   if (n_blk <= 0) return;
-  if (dtype == FLAME_GR_BF16) ln_gate_dispatch<bf16_t>(O, U, gamma, beta, G, blocks, blk_list, n_blk, blk_first, d, eps, s);
-  else ln_gate_dispatch<float>(O, U, gamma, beta, G, blocks, blk_list, n_blk, blk_first, d, eps, s);
+  if (dtype == FLAME_GR_BF16) ln_gate_dispatch<half_t, bf16_t>(O, U, gamma, beta, G, blocks, blk_list, n_blk, blk_first, d, eps, s);
+  else ln_gate_dispatch<float, float>(O, U, gamma, beta, G, blocks, blk_list, n_blk, blk_first, d, eps, s);
 }
 
 // ---------------------------------------------------------------------------------------------
