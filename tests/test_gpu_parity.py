@@ -2,7 +2,7 @@
 
 Error measure for scores (logits cross zero, so a plain relative error is unbounded there):
     err = max_j |g_j - o_j| / max(|o_j|, rms(o))
-Bars: 1e-4 for the fp32 path, 2e-2 for the bf16 path.  Intermediate tensors are compared with
+Bars: 1e-4 for the fp32 path, 2e-2 for the bf16-storage (MFMA) path.  Intermediate tensors are compared with
 max |g - o| / rms(o) per tensor so that a residual-dominated score cannot hide a broken branch.
 Integer outputs (offsets, mask, buckets) must match bit for bit.
 """
@@ -18,16 +18,14 @@ pytestmark = pytest.mark.gpu
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 # The "hot" stress inputs are ten times the benchmark's scale (embeddings N(0,1), bias table N(0,1)),
 # so every SiLU works in its curved region and each layer's branch is as large as the residual.  The
-# bf16 path stores X, UVQK, P, O and the gated LayerNorm output in bf16 (2^-9 relative each); with the
-# branch no longer a small perturbation those roundings reach the scores undamped: about 1e-2 rms,
-# 2-3e-2 for the worst of a few hundred scores.  The benchmark workloads keep the 2e-2 bar.
-TOL_HOT = {"f32": 1e-4, "bf16": 5e-2}
-# Intermediate tensors are compared in the max norm relative to the tensor's rms.  In the bf16 path
-# every stored element carries a rounding of 2^-9 relative to its own size, the largest elements
-# are 4-6 rms, and by the second layer three to four such roundings have compounded (X -> UVQK ->
-# P -> O), which puts the honest worst element at a few 1e-2; a wrong bucket, mask or head index
-# shows up at order 1.
-STAGE_TOL = {"f32": 2e-4, "bf16": 8e-2}
+# MFMA path stores its intermediates in fp16 (2^-12 relative per rounding); a handful of roundings per
+# layer leaves the scores within a few 1e-3 even then, so the hot inputs keep the benchmark's bar.
+TOL_HOT = {"f32": 1e-4, "bf16": 2e-2}
+# Intermediate tensors are compared in the max norm relative to the tensor's rms: every stored fp16
+# element carries 2^-12 of its own size, the largest elements are 4-6 rms and two or three roundings
+# have compounded by the second layer: a few 1e-3 honestly; a wrong bucket, mask or head index shows
+# up at order 1.
+STAGE_TOL = {"f32": 2e-4, "bf16": 1.5e-2}
 
 
 @pytest.fixture(scope="module")
