@@ -11,7 +11,10 @@ LIB = os.path.join(HERE, "libflame_gr.so")
 SOURCES = ["api.cpp", "plan.cpp", "misc.hip", "kernels_f32.hip", "gemm_mfma.hip", "attn_mfma.hip"]
 # packed fp32 VALU instructions are switched off on purpose (build flags)
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
-         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+         # keep MFMA accumulators in ordinary VGPRs: the epilogues and the attention SiLU read them
+         # with VALU instructions, and accumulation registers would need a copy each way
+         "-mllvm", "-amdgpu-mfma-vgpr-form"]
 
 
 def build(verbose: bool = True, jobs: int = 6) -> str:

@@ -2,7 +2,8 @@
 //
 // For every query row r of a request and every head:
 //     O_r = sum over allowed keys c of silu(<Q_r, K_c> + bias[p_r - p_c]) V_c
-// (Q already carries the scale alpha).  History rows look at keys 0..r, candidate rows look at the
+// Q arrives multiplied by alpha*log2(e), the bias table by log2(e) and V by ln(2), so the logits are
+// directly exp2 arguments: silu costs exp2, add, rcp, mul and the scale factors cancel in O.  History rows look at keys 0..r, candidate rows look at the
 // whole history and at themselves: the customised mask of Section 3.2 that lets all candidates of
 // a request be scored in one pass.  No score matrix is materialised: like a flash-attention tile
 // loop, but the pointwise SiLU needs neither running maximum nor rescaling.
@@ -30,20 +31,21 @@ constexpr int QT = kAttnQTileBf16;  // query rows per workgroup (4 wavefronts x 
 static_assert(QT == 128, "4 wavefronts of 32 query rows");
 constexpr int KT = 64;       // keys per tile
 constexpr int PAD = 8;       // fp16 elements of LDS row padding
-constexpr int BW = 192;      // bias window per key tile: distances (q_first - k0 - 63) .. (q_first + 127 - k0)
+constexpr int BW = 192;      // bias window per key tile, stored by decreasing distance:
+                             // slot u holds bias[q_first + 127 - k0 - u], u = 0..191
 
 __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
   return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
 }
 
-// eight attention weights -> fp16 B-operand fragment; saturating so that a huge weight cannot become inf
+// eight attention weights -> fp16 B-operand fragment (v_cvt_pk_f16_f32, round to nearest even).
+// A weight beyond the fp16 range becomes inf; the output store saturates, so nothing non-finite is
+// ever written to the workspace.
 __device__ __forceinline__ f16x8 pack8(const float *v) {
   f16x8 r;
 #pragma unroll
   for (int i = 0; i < 8; ++i) r[i] = (half_t)v[i];
-  const half_t big = (half_t)65504.f;
-  const f16x8 hi = {big, big, big, big, big, big, big, big};
-  return __builtin_elementwise_min(r, hi);
+  return r;
 }
 
 template <int DH>
@@ -59,7 +61,9 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
 
   const int head = blockIdx.x % H;
   const AttnItem it = items[blockIdx.x / H];
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // wavefront index as a scalar: every branch on it is then a uniform (scalar) branch
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lhalf = lane >> 5;
 
   const int64_t plane = ws_rows * d;
@@ -111,7 +115,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
     oV[i] = rr * (KT + PAD) + cc * 8;
   }
   const int bias_t = tid < BW ? tid : BW - 1;
-  const int delta0 = q_first - (KT - 1) + bias_t;       // distance of window slot bias_t for tile 0
+  const int delta0 = q_first + (QT - 1) - bias_t;       // distance held by window slot bias_t for tile 0
   uint4 rk[NCH], rv[NCH];
   float rbias;
 #define ATTN_LOAD_TILE(T)                                                                   \
@@ -140,8 +144,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
   }
   __syncthreads();
 
-  // index of my row's distance inside the bias window, for key 0 of the tile
-  const int bias_base = (it.is_cand ? 0 : my_q_local) + (KT - 1);
+  // window slot of (my row, key 0 of the tile); keys further right sit at increasing slots
+  const int bias_base = (QT - 1) - (it.is_cand ? 0 : my_q_local) + 8 * lhalf;
 
   for (int t = 0; t < n_tiles; ++t) {
     const int buf = t & 1;
@@ -154,10 +158,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
 #pragma unroll
       for (int j = 0; j < 2; ++j)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int kv_local = 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-          sacc[j][e] = sBias[buf][bias_base - kv_local];
-        }
+        for (int e = 0; e < 16; ++e) sacc[j][e] = sBias[buf][bias_base + 32 * j + 16 * (e >> 3) + (e & 7)];
 #pragma unroll
       for (int s = 0; s < KS; ++s)
 #pragma unroll
@@ -172,7 +173,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
       for (int j = 0; j < 2; ++j) {
         float p[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) p[e] = silu_fast(sacc[j][e]);
+        for (int e = 0; e < 16; ++e) p[e] = silu_log2_domain(sacc[j][e]);
         if (need_mask) {
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
@@ -215,7 +216,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
-      p[e] = (kv_local == l32 && row_valid) ? silu_fast(sacc[e]) : 0.f;
+      p[e] = (kv_local == l32 && row_valid) ? silu_log2_domain(sacc[e]) : 0.f;
     }
     f16x8 fp[2] = {pack8(p), pack8(p + 8)};
 #pragma unroll

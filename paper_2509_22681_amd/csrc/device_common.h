@@ -39,10 +39,21 @@ __device__ __forceinline__ float silu_f32(float x) {
   return x / (1.0f + __expf(-x));
 }
 
-// Faster variant for the attention inner loop: hardware exp2 and reciprocal (about 1 ulp each).
+// Faster variant: hardware exp2 and reciprocal (about 1 ulp each), same limits.
 __device__ __forceinline__ float silu_fast(float x) {
   float e = __builtin_amdgcn_exp2f(x * -1.4426950408889634f);
   return x * __builtin_amdgcn_rcpf(1.0f + e);
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+// SiLU of an argument that arrives pre-multiplied by log2(e): returns log2(e) * silu(x) for
+// y = log2(e) * x, in four instructions (exp2, add, rcp, mul).  The attention kernel keeps its
+// logits in this scaled form (the scale is folded into Q and into the bias table) and the factor
+// 1/log2(e) is folded into V.
+__device__ __forceinline__ float silu_log2_domain(float y) {
+  return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-y));
 }
 
 // Number of history keys a query row may look at (the mask of the single-user-multiple-items

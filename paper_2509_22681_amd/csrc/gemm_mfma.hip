@@ -28,8 +28,8 @@ template <int BN, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(
     const half_t *__restrict__ A, const half_t *__restrict__ W, const bf16_t *__restrict__ bias,
     half_t *__restrict__ planes, float *__restrict__ X, half_t *__restrict__ Xh,
-    const int32_t *__restrict__ blk_list, int blk_first, int n_blk, int K, int d, int64_t ws_rows,
-    PlaneSel sel, float alpha) {
+    const int32_t *__restrict__ blk_list, int blk_first, int n_blk, int n_row_tiles, int n_col_tiles, int K, int d,
+    int64_t ws_rows, PlaneSel sel, float alpha) {
   constexpr int WN = BN / 2;            // wavefront patch width
   constexpr int NB = WN / 32;           // 32-wide MFMA blocks per wavefront in n
   __shared__ __attribute__((aligned(16))) half_t sA[2][BM][LDS_LD];
@@ -39,21 +39,40 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lhalf = lane >> 5;
 
+  // Workgroup id -> (row tile, column tile).  Consecutive workgroup ids go round-robin over the 8
+  // XCDs, each with its own L2: XCD x takes the row tiles congruent to x mod 8 and walks through all
+  // column tiles of one row tile before the next, so an activation tile is fetched from HBM once
+  // and then served from that XCD's L2, while the (small) weight matrix stays resident in all L2s.
+  int row_tile, col_tile;
+  {
+    constexpr int NXCD = 8;
+    const int wg = blockIdx.x, xcd = wg % NXCD, j = wg / NXCD;
+    const int full = (n_row_tiles / NXCD) * NXCD;       // row tiles that split evenly over the XCDs
+    const int rt = (j / n_col_tiles) * NXCD + xcd;
+    if (rt < full) {
+      row_tile = rt;
+      col_tile = j % n_col_tiles;
+    } else {                                            // the tail is dealt out in plain order
+      const int t = wg - full * n_col_tiles;
+      row_tile = full + t / n_col_tiles;
+      col_tile = t % n_col_tiles;
+    }
+  }
   // column tile -> (plane, offset inside the plane)
   int plane = 0, n_in_plane = 0, n0;
   if (EPI == 0) {
     const int tiles_per_plane = d / BN;
-    plane = sel.id[blockIdx.y / tiles_per_plane];
-    n_in_plane = (blockIdx.y % tiles_per_plane) * BN;
+    plane = sel.id[col_tile / tiles_per_plane];
+    n_in_plane = (col_tile % tiles_per_plane) * BN;
     n0 = plane * d + n_in_plane;
   } else {
-    n0 = blockIdx.y * BN;
+    n0 = col_tile * BN;
   }
   // the two 64-row blocks of this row tile (-1: absent)
   int blk[2];
 #pragma unroll
   for (int r = 0; r < 2; ++r) {
-    const int t = blockIdx.x * 2 + r;
+    const int t = row_tile * 2 + r;
     blk[r] = t < n_blk ? (blk_list ? blk_list[t] : blk_first + t) : -1;
   }
   const int blk_safe1 = blk[1] >= 0 ? blk[1] : blk[0];
@@ -153,11 +172,13 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
         if (!transposed) {
           const int n = n_in_plane + nb0 + l32;
           const float bv = to_f32(bias[plane * d + n]);
-          const float sc = plane == 2 ? alpha : 1.0f;
+          // Q leaves this kernel multiplied by alpha * log2(e): the attention logits are then
+          // directly the arguments of exp2 (V carries the inverse factor ln 2).
+          const float sc = plane == 2 ? alpha * kLog2e : 1.0f;
 #pragma unroll
           for (int e = 0; e < 16; ++e) {
             const int m = 8 * (e >> 2) + 4 * lhalf + (e & 3);
-            P[(row_base + m) * d + n] = to_f16_sat(silu_f32(acc[i][j][e] + bv) * sc);
+            P[(row_base + m) * d + n] = to_f16_sat(silu_fast(acc[i][j][e] + bv) * sc);
           }
         } else {
           const int64_t m = row_base + l32;
@@ -165,7 +186,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
           for (int e = 0; e < 16; ++e) {
             const int n = n_in_plane + nb0 + 8 * (e >> 2) + 4 * lhalf + (e & 3);
             const float bv = to_f32(bias[plane * d + n]);
-            P[(int64_t)n * ws_rows + m] = to_f16_sat(silu_f32(acc[i][j][e] + bv));
+            P[(int64_t)n * ws_rows + m] = to_f16_sat(silu_fast(acc[i][j][e] + bv) * kLn2);
           }
         }
       } else {
@@ -193,13 +214,13 @@ void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *pla
     if (plane_mask & (1 << p)) sel.id[sel.n++] = p;
   const int row_tiles = (n_blk + 1) / 2;
   if (sh.d % 128 == 0) {
-    dim3 grid(row_tiles, sel.n * (sh.d / 128));
-    gemm_bf16_kernel<128, 0><<<grid, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1, (half_t *)planes,
-                                                  nullptr, nullptr, blk_list, blk_first, n_blk, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
+    const int col_tiles = sel.n * (sh.d / 128);
+    gemm_bf16_kernel<128, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1, (half_t *)planes,
+                                                  nullptr, nullptr, blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
   } else {
-    dim3 grid(row_tiles, sel.n * (sh.d / 64));
-    gemm_bf16_kernel<64, 0><<<grid, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1, (half_t *)planes,
-                                                 nullptr, nullptr, blk_list, blk_first, n_blk, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
+    const int col_tiles = sel.n * (sh.d / 64);
+    gemm_bf16_kernel<64, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1, (half_t *)planes,
+                                                 nullptr, nullptr, blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
   }
 }
 
@@ -209,13 +230,13 @@ void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *
   PlaneSel sel{};
   const int row_tiles = (n_blk + 1) / 2;
   if (sh.d % 128 == 0) {
-    dim3 grid(row_tiles, sh.d / 128);
-    gemm_bf16_kernel<128, 1><<<grid, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X, (half_t *)Xh,
-                                                  blk_list, blk_first, n_blk, sh.d, sh.d, sh.ws_rows, sel, 1.0f);
+    const int col_tiles = sh.d / 128;
+    gemm_bf16_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X, (half_t *)Xh,
+                                                  blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, 1.0f);
   } else {
-    dim3 grid(row_tiles, sh.d / 64);
-    gemm_bf16_kernel<64, 1><<<grid, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X, (half_t *)Xh,
-                                                 blk_list, blk_first, n_blk, sh.d, sh.d, sh.ws_rows, sel, 1.0f);
+    const int col_tiles = sh.d / 64;
+    gemm_bf16_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X, (half_t *)Xh,
+                                                 blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, 1.0f);
   }
 }
 

@@ -20,9 +20,10 @@ void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_e
                      const void *cand, float *X, void *Xh, int d, hipStream_t s);
 // out[i] = fp16(in[i]) for n bf16 elements (n % 8 == 0)
 void launch_bf16_to_f16(const void *in, void *out, int64_t n, hipStream_t s);
-// bias[lh][delta] = rab[lh][bucket_tab[delta]] for all layers and heads.
+// bias[lh][delta] = scale * rab[lh][bucket_tab[delta]] for all layers and heads (scale = log2(e) in
+// the MFMA path, whose logits live in the exp2 domain; 1 in the fp32 path).
 void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh,
-                        int n_buckets, int D, hipStream_t s);
+                        int n_buckets, int D, float scale, hipStream_t s);
 // G = (LayerNorm(O) * gamma + beta) * U, one row at a time (element type of O, U, G = dtype);
 // padding rows of a block get G = 0 so that they stay finite through the layers.
 void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, const void *beta,

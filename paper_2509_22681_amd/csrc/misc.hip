@@ -42,16 +42,16 @@ void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_e
 // bias[lh][delta] = rab[lh][bucket(delta)]: the attention kernels index the bias by distance.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void expand_bias_kernel(const float *__restrict__ rab, const int32_t *__restrict__ tab,
-                                                          float *__restrict__ bias, int nb, int D) {
+                                                          float *__restrict__ bias, int nb, int D, float scale) {
   const int lh = blockIdx.y;
   for (int t = blockIdx.x * 256 + threadIdx.x; t < D; t += gridDim.x * 256)
-    bias[(int64_t)lh * D + t] = rab[(int64_t)lh * nb + tab[t]];
+    bias[(int64_t)lh * D + t] = rab[(int64_t)lh * nb + tab[t]] * scale;
 }
 
 void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh, int n_buckets,
-                        int D, hipStream_t s) {
+                        int D, float scale, hipStream_t s) {
   dim3 grid((D + 255) / 256 > 64 ? 64 : (D + 255) / 256, n_lh);
-  expand_bias_kernel<<<grid, 256, 0, s>>>(rab, bucket_tab, bias, n_buckets, D);
+  expand_bias_kernel<<<grid, 256, 0, s>>>(rab, bucket_tab, bias, n_buckets, D, scale);
 }
 
 // ---------------------------------------------------------------------------------------------
