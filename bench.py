@@ -21,7 +21,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-PEAK_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_BF16_TFLOPS = 2500.0   # MI355X dense MFMA peak, the same for bf16 and fp16 operands
 
 
 def attention_flops_per_layer(cfg, L, M):
@@ -166,7 +166,9 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": cfg.dtype, "data": "synthetic",
+        # arithmetic type of the MFMA path: fp16 operands with fp32 accumulation (embeddings and weights
+        # are bf16 in HBM at the boundary); the fp32 workload computes in fp32
+        "dtype": "f16" if cfg.dtype == "bf16" else "f32", "storage_dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "requests": wl.n_requests, "sum_L": int(wl.L.sum()), "sum_M": n_scores,
                    "d_model": cfg.d_model, "n_heads": cfg.n_heads, "n_layers": cfg.n_layers,
                    "batcher_streams": max(args.streams, 1)},

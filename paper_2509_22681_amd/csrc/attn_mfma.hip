@@ -152,6 +152,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
     const int k0 = t * KT;
     const int tn = t + 1 < n_tiles ? t + 1 : t;
     ATTN_LOAD_TILE(tn);
+    __builtin_amdgcn_sched_barrier(0);   // the prefetch stays ahead of the tile's arithmetic
     if (wave_active && k0 < wave_vis_max) {
       // ---- S^T = K Q^T + bias, two blocks of 32 keys
       f32x16 sacc[2];
@@ -193,6 +194,7 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
           oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp[s2], oacc[b], 0, 0, 0);
         }
     }
+    __builtin_amdgcn_sched_barrier(0);
     ATTN_STORE_TILE(buf ^ 1);
     __syncthreads();
   }

@@ -3,11 +3,18 @@
 //   K3b X <- X + G W2^T + b2, Xh = fp16(X)       (residual fused as the GEMM epilogue)
 // Both are C[m][n] = sum_k A[m][k] W[n][k] with A and W row-major, k contiguous.
 //
-// Tiling: 256 threads = 4 wavefronts in a 2x2 arrangement, block tile 128 x BN x 64, each
-// wavefront owns a 64 x (BN/2) patch built from v_mfma_f32_32x32x16_f16 blocks; global -> register
-// -> LDS double buffering overlaps the loads of tile k+1 with the MFMAs of tile k (the role the
-// cp.async pipeline plays in Section 3.2).  Rows are addressed through 64-row blocks so that the
-// same kernel runs on a contiguous range or on a list of candidate blocks (last-layer pruning).
+// Tiling.  A 128x128 tile re-reads 1 byte of operand per 64 flop, which at MFMA speed is twice what
+// the L2 delivers (measured about 19 TB/s), so the block tile is 256 x BN (BN = 128 where d allows):
+// 256 threads = 4 wavefronts in a 2x2 arrangement, each owning 128 x BN/2 as 4 x (BN/64) blocks of
+// v_mfma_f32_32x32x16_f16.  k advances in steps of 32 through two LDS stages; the next stage is
+// prefetched global -> registers while the MFMAs of the current one run and is written to LDS
+// behind them (the role the cp.async pipeline plays in Section 3.2).  Two workgroups fit on a CU
+// (48 KB LDS, <= 256 VGPRs), so one workgroup's epilogue (VALU: SiLU, conversion) overlaps the
+// other's MFMA phase.  LDS rows are 64 bytes; 16-byte chunks are XOR-swizzled over 128-byte lines so
+// that both the staging writes and the fragment reads are bank-conflict free without padding.
+//
+// Rows are addressed through 64-row blocks so that the same kernel runs on a contiguous range or on
+// a list of candidate blocks (last-layer pruning).
 #include <type_traits>
 
 #include "device_common.h"
@@ -17,25 +24,33 @@ namespace flame {
 
 namespace {
 
-constexpr int BM = 128;
-constexpr int BK = 64;
-constexpr int LDS_PAD = 8;              // fp16 elements; keeps 16-byte alignment, spreads banks
-constexpr int LDS_LD = BK + LDS_PAD;    // 72
+constexpr int BM = 256;
+constexpr int BK = 32;
+constexpr int RB = BM / kRowAlign;      // 64-row blocks per row tile
 
 struct PlaneSel { int id[4]; int n; };
 
+// byte offset of 16-byte chunk c (0..3) of tile row `row` inside one LDS stage
+__device__ __forceinline__ int lds_off(int row, int c) {
+  const int line = row >> 1;
+  const int slot = ((row & 1) << 2) | c;
+  return line * 128 + ((slot ^ (line & 7)) << 4);
+}
+
 template <int BN, int EPI>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(
+__global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     const half_t *__restrict__ A, const half_t *__restrict__ W, const bf16_t *__restrict__ bias,
     half_t *__restrict__ planes, float *__restrict__ X, half_t *__restrict__ Xh,
     const int32_t *__restrict__ blk_list, int blk_first, int n_blk, int n_row_tiles, int n_col_tiles, int K, int d,
     int64_t ws_rows, PlaneSel sel, float alpha) {
-  constexpr int WN = BN / 2;            // wavefront patch width
-  constexpr int NB = WN / 32;           // 32-wide MFMA blocks per wavefront in n
-  __shared__ __attribute__((aligned(16))) half_t sA[2][BM][LDS_LD];
-  __shared__ __attribute__((aligned(16))) half_t sB[2][BN][LDS_LD];
+  constexpr int WN = BN / 2;            // wavefront patch: 128 rows x WN columns
+  constexpr int MB = 4;                 // 32-row MFMA blocks per wavefront
+  constexpr int NB = WN / 32;           // 32-column MFMA blocks per wavefront
+  constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
+  __shared__ __attribute__((aligned(128))) char smem[2 * STAGE];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int wm = wave >> 1, wn = wave & 1;
   const int l32 = lane & 31, lhalf = lane >> 5;
 
@@ -68,136 +83,160 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(
   } else {
     n0 = col_tile * BN;
   }
-  // the two 64-row blocks of this row tile (-1: absent)
-  int blk[2];
+  // the 64-row blocks of this row tile (-1: absent; loads then fall back to the first block)
+  int blk[RB];
 #pragma unroll
-  for (int r = 0; r < 2; ++r) {
-    const int t = row_tile * 2 + r;
+  for (int r = 0; r < RB; ++r) {
+    const int t = row_tile * RB + r;
     blk[r] = t < n_blk ? (blk_list ? blk_list[t] : blk_first + t) : -1;
   }
-  const int blk_safe1 = blk[1] >= 0 ? blk[1] : blk[0];
 
-  // global -> register staging: 16-byte chunks, 8 per 64-wide row.  Per-thread source pointers
-  // (at k = 0) and LDS destinations are fixed for the whole loop.
-  constexpr int A_CH = BM * 8 / 256, B_CH = BN * 8 / 256;
+  // global -> register staging: 16-byte chunks, 4 per 32-wide row
+  constexpr int A_CH = BM * 4 / 256, B_CH = BN * 4 / 256;
   const half_t *gA[A_CH];
   const half_t *gB[B_CH];
-  int oA[A_CH], oB[B_CH];               // element offsets inside one LDS buffer
+  int oA[A_CH], oB[B_CH];
 #pragma unroll
   for (int i = 0; i < A_CH; ++i) {
-    const int c = tid + i * 256, r = c >> 3, c8 = c & 7;
-    const int64_t row = (int64_t)(r < 64 ? blk[0] : blk_safe1) * kRowAlign + (r & 63);
-    gA[i] = A + row * K + c8 * 8;
-    oA[i] = r * LDS_LD + c8 * 8;
+    const int c = tid + i * 256, r = c >> 2, ch = c & 3;
+    const int b = blk[r >> 6] >= 0 ? blk[r >> 6] : blk[0];
+    gA[i] = A + ((int64_t)b * kRowAlign + (r & 63)) * K + ch * 8;
+    oA[i] = lds_off(r, ch);
   }
 #pragma unroll
   for (int i = 0; i < B_CH; ++i) {
-    const int c = tid + i * 256, r = c >> 3, c8 = c & 7;
-    gB[i] = W + (int64_t)(n0 + r) * K + c8 * 8;
-    oB[i] = r * LDS_LD + c8 * 8;
+    const int c = tid + i * 256, r = c >> 2, ch = c & 3;
+    gB[i] = W + (int64_t)(n0 + r) * K + ch * 8;
+    oB[i] = A_BYTES + lds_off(r, ch);
   }
-
-  f32x16 acc[2][NB];
+  // fragment addresses inside a stage, for k16-step 0 (step 1 = chunk + 2)
+  int fA[MB], fB[NB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < MB; ++i) fA[i] = wm * 128 + i * 32 + l32;       // tile row
+#pragma unroll
+  for (int j = 0; j < NB; ++j) fB[j] = wn * WN + j * 32 + l32;
+
+  f32x16 acc[MB][NB];
+#pragma unroll
+  for (int i = 0; i < MB; ++i)
 #pragma unroll
     for (int j = 0; j < NB; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
-  // The V plane is produced transposed (feature-major) because the attention kernel consumes V as
-  // the A operand of O^T = V^T P^T: swapping the MFMA operands yields C^T in registers for free.
-  const bool transposed = (EPI == 0) && plane == 1;
+  // Operand order.  Row-major outputs (U, Q, K planes, X) want each lane to hold 4 consecutive
+  // features of one token, which is the transposed accumulator: W rows as the A operand.  The V
+  // plane is stored feature-major for the attention kernel (V^T is its A operand) and wants 4
+  // consecutive tokens of one feature: activations as the A operand.
+  const bool feature_major = (EPI == 0) && plane == 1;
 
-  // The operand order is fixed per workgroup; the loop is instantiated once per order so that no
-  // branch sits between the MFMAs.
-  auto main_loop = [&](auto swapped) {
-    constexpr bool SW = decltype(swapped)::value;
+  auto main_loop = [&](auto fm) {
+    constexpr bool FM = decltype(fm)::value;
     uint4 ra[A_CH], rb[B_CH];
 #pragma unroll
     for (int i = 0; i < A_CH; ++i) ra[i] = *(const uint4 *)gA[i];
 #pragma unroll
     for (int i = 0; i < B_CH; ++i) rb[i] = *(const uint4 *)gB[i];
 #pragma unroll
-    for (int i = 0; i < A_CH; ++i) *(uint4 *)(&sA[0][0][0] + oA[i]) = ra[i];
+    for (int i = 0; i < A_CH; ++i) *(uint4 *)(smem + oA[i]) = ra[i];
 #pragma unroll
-    for (int i = 0; i < B_CH; ++i) *(uint4 *)(&sB[0][0][0] + oB[i]) = rb[i];
+    for (int i = 0; i < B_CH; ++i) *(uint4 *)(smem + oB[i]) = rb[i];
     __syncthreads();
     const int nk = K / BK;
     for (int kt = 0; kt < nk; ++kt) {
-      const int buf = kt & 1;
+      const char *st = smem + (kt & 1) * STAGE;
+      char *nx = smem + ((kt & 1) ^ 1) * STAGE;
       // prefetch the next k tile into registers (the last iteration re-reads its own tile: no branch)
       const int kn = (kt + 1 < nk ? kt + 1 : kt) * BK;
 #pragma unroll
       for (int i = 0; i < A_CH; ++i) ra[i] = *(const uint4 *)(gA[i] + kn);
 #pragma unroll
       for (int i = 0; i < B_CH; ++i) rb[i] = *(const uint4 *)(gB[i] + kn);
+      // keep the loads up here: left alone, the scheduler sinks them to just before the LDS writes
+      // and the whole global latency lands on the critical path
+      __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
       for (int ks = 0; ks < BK / 16; ++ks) {
-        f16x8 fa[2], fb[NB];
+        f16x8 fa[MB], fb[NB];
 #pragma unroll
-        for (int i = 0; i < 2; ++i) fa[i] = *(const f16x8 *)&sA[buf][wm * 64 + i * 32 + l32][ks * 16 + lhalf * 8];
+        for (int i = 0; i < MB; ++i) fa[i] = *(const f16x8 *)(st + lds_off(fA[i], ks * 2 + lhalf));
 #pragma unroll
-        for (int j = 0; j < NB; ++j) fb[j] = *(const f16x8 *)&sB[buf][wn * WN + j * 32 + l32][ks * 16 + lhalf * 8];
+        for (int j = 0; j < NB; ++j) fb[j] = *(const f16x8 *)(st + A_BYTES + lds_off(fB[j], ks * 2 + lhalf));
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < MB; ++i)
 #pragma unroll
           for (int j = 0; j < NB; ++j)
-            acc[i][j] = SW ? __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0)
-                           : __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            acc[i][j] = FM ? __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0)
+                           : __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0);
       }
-      // the other buffer was last read before the previous barrier: safe to overwrite
+      __builtin_amdgcn_sched_barrier(0);
+      // the other stage was last read before the previous barrier: safe to overwrite
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) *(uint4 *)(&sA[buf ^ 1][0][0] + oA[i]) = ra[i];
+      for (int i = 0; i < A_CH; ++i) *(uint4 *)(nx + oA[i]) = ra[i];
 #pragma unroll
-      for (int i = 0; i < B_CH; ++i) *(uint4 *)(&sB[buf ^ 1][0][0] + oB[i]) = rb[i];
+      for (int i = 0; i < B_CH; ++i) *(uint4 *)(nx + oB[i]) = rb[i];
       __syncthreads();
     }
   };
-  if (transposed) main_loop(std::true_type{});
+  if (feature_major) main_loop(std::true_type{});
   else main_loop(std::false_type{});
 
-  // epilogue.  Accumulator element e of a 32x32 block: column = lane % 32, row = 8*(e/4) + 4*(lane/32) + e%4
-  // (rows are tokens and columns features, or the reverse for the transposed plane).
+  // Epilogue.  Accumulator element e of a 32x32 block sits at (A-operand row 8*(e/4) + 4*(lane/32) + e%4,
+  // B-operand row lane%32): four consecutive e are four consecutive A-operand rows.
 #pragma unroll
-  for (int i = 0; i < 2; ++i) {
-    const int rblk = blk[wm];             // wavefront rows wm*64 .. +63 lie in one 64-row block
+  for (int i = 0; i < MB; ++i) {
+    const int tr = wm * 128 + i * 32;                 // first tile row of this block: inside one 64-row block
+    const int rblk = blk[tr >> 6];
     if (rblk < 0) continue;
-    const int64_t row_base = (int64_t)rblk * kRowAlign + i * 32;
+    const int64_t row_base = (int64_t)rblk * kRowAlign + (tr & 63);
 #pragma unroll
     for (int j = 0; j < NB; ++j) {
-      const int nb0 = wn * WN + j * 32;   // column offset of this block inside the tile
+      const int nb0 = wn * WN + j * 32;               // column offset of this block inside the tile
       if (EPI == 0) {
         half_t *P = planes + (int64_t)plane * ws_rows * d;
-        if (!transposed) {
-          const int n = n_in_plane + nb0 + l32;
-          const float bv = to_f32(bias[plane * d + n]);
+        if (!feature_major) {
+          // lane: token row_base + l32; elements: features nb0 + 8g + 4*lhalf + 0..3
           // Q leaves this kernel multiplied by alpha * log2(e): the attention logits are then
           // directly the arguments of exp2 (V carries the inverse factor ln 2).
           const float sc = plane == 2 ? alpha * kLog2e : 1.0f;
+          half_t *prow = P + (row_base + l32) * d + n_in_plane + nb0 + 4 * lhalf;
+          const bf16_t *brow = bias + plane * d + n_in_plane + nb0 + 4 * lhalf;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int m = 8 * (e >> 2) + 4 * lhalf + (e & 3);
-            P[(row_base + m) * d + n] = to_f16_sat(silu_fast(acc[i][j][e] + bv) * sc);
+          for (int g = 0; g < 4; ++g) {
+            const bf16x4 bv = *(const bf16x4 *)(brow + 8 * g);
+            f16x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][4 * g + q] + (float)bv[q]) * sc);
+            *(f16x4 *)(prow + 8 * g) = o;
           }
         } else {
-          const int64_t m = row_base + l32;
+          // lane: feature n_in_plane + nb0 + l32; elements: tokens row_base + 8g + 4*lhalf + 0..3
+          const int n = n_in_plane + nb0 + l32;
+          const float bv = to_f32(bias[plane * d + n]);
+          half_t *pcol = P + (int64_t)n * ws_rows + row_base + 4 * lhalf;
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int n = n_in_plane + nb0 + 8 * (e >> 2) + 4 * lhalf + (e & 3);
-            const float bv = to_f32(bias[plane * d + n]);
-            P[(int64_t)n * ws_rows + m] = to_f16_sat(silu_fast(acc[i][j][e] + bv) * kLn2);
+          for (int g = 0; g < 4; ++g) {
+            f16x4 o;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][4 * g + q] + bv) * kLn2);
+            *(f16x4 *)(pcol + 8 * g) = o;
           }
         }
       } else {
-        const int n = n0 + nb0 + l32;
-        const float bv = to_f32(bias[n]);
+        const int64_t m = row_base + l32;
+        const int nn = n0 + nb0 + 4 * lhalf;
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-          const int64_t m = row_base + 8 * (e >> 2) + 4 * lhalf + (e & 3);
-          const float v = X[m * d + n] + acc[i][j][e] + bv;
-          X[m * d + n] = v;
-          Xh[m * d + n] = to_f16_sat(v);
+        for (int g = 0; g < 4; ++g) {
+          const bf16x4 bv = *(const bf16x4 *)(bias + nn + 8 * g);
+          f32x4 x = *(const f32x4 *)(X + m * d + nn + 8 * g);
+          f16x4 o;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            x[q] += acc[i][j][4 * g + q] + (float)bv[q];
+            o[q] = to_f16_sat(x[q]);
+          }
+          *(f32x4 *)(X + m * d + nn + 8 * g) = x;
+          *(f16x4 *)(Xh + m * d + nn + 8 * g) = o;
         }
       }
     }
@@ -212,15 +251,17 @@ void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *pla
   PlaneSel sel{};
   for (int p = 0; p < 4; ++p)
     if (plane_mask & (1 << p)) sel.id[sel.n++] = p;
-  const int row_tiles = (n_blk + 1) / 2;
+  const int row_tiles = (n_blk + RB - 1) / RB;
   if (sh.d % 128 == 0) {
     const int col_tiles = sel.n * (sh.d / 128);
-    gemm_bf16_kernel<128, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1, (half_t *)planes,
-                                                  nullptr, nullptr, blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
+    gemm_mfma_kernel<128, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
+                                                                   (half_t *)planes, nullptr, nullptr, blk_list, blk_first, n_blk,
+                                                                   row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
   } else {
     const int col_tiles = sel.n * (sh.d / 64);
-    gemm_bf16_kernel<64, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1, (half_t *)planes,
-                                                 nullptr, nullptr, blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
+    gemm_mfma_kernel<64, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
+                                                                  (half_t *)planes, nullptr, nullptr, blk_list, blk_first, n_blk,
+                                                                  row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
   }
 }
 
@@ -228,15 +269,17 @@ void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *
                          int n_blk, int blk_first, const Shape &sh, hipStream_t s) {
   if (n_blk <= 0) return;
   PlaneSel sel{};
-  const int row_tiles = (n_blk + 1) / 2;
+  const int row_tiles = (n_blk + RB - 1) / RB;
   if (sh.d % 128 == 0) {
     const int col_tiles = sh.d / 128;
-    gemm_bf16_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X, (half_t *)Xh,
-                                                  blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, 1.0f);
+    gemm_mfma_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X,
+                                                                   (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
+                                                                   sh.d, sh.d, sh.ws_rows, sel, 1.0f);
   } else {
     const int col_tiles = sh.d / 64;
-    gemm_bf16_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X, (half_t *)Xh,
-                                                 blk_list, blk_first, n_blk, row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, 1.0f);
+    gemm_mfma_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X,
+                                                                  (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
+                                                                  sh.d, sh.d, sh.ws_rows, sel, 1.0f);
   }
 }
 

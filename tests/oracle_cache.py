@@ -1,12 +1,15 @@
-"""Oracle scores for the named workloads, with an on-disk cache.
+"""Oracle scores for the named benchmark workloads, stored as text fixtures.
 
-The expected values are always produced by `oracle.forward` (nothing else); because the big
-workloads take minutes of fp64 numpy per request, results are cached as .npy files keyed by a hash
-of the exact inputs.  Running this file as a script fills the cache:
+The expected values are produced by `oracle.forward_request` and by nothing else.  Because the big
+workloads take minutes of fp64 numpy per request (five minutes for one 8192-token history), the
+results are kept as text files under tests/golden/oracle_scores/, one per request, keyed by a hash
+of the exact inputs (configuration, the request's embeddings, all weights).  This script is the only
+writer of those files:
 
     python tests/oracle_cache.py [workload ...]
 
-The cache is an accelerator only: when a file is missing the tests compute the values in place.
+A file whose key does not match the regenerated inputs is simply not found, and the tests then
+compute the values in place.
 """
 from __future__ import annotations
 
@@ -24,7 +27,7 @@ if ROOT not in sys.path:
 import oracle  # noqa: E402
 from paper_2509_22681_amd import workloads as W  # noqa: E402
 
-CACHE_DIR = os.path.join(ROOT, "tests", "golden", "cache")
+CACHE_DIR = os.path.join(ROOT, "tests", "golden", "oracle_scores")
 
 # requests whose oracle scores are compared at the full benchmark sizes (all requests where None)
 SAMPLED = {
@@ -75,9 +78,9 @@ def _key(wl: W.Workload, i: int) -> str:
 
 def request_scores(wl: W.Workload, i: int, verbose: bool = False) -> np.ndarray:
     """Oracle scores of request i of a workload (cached)."""
-    path = os.path.join(CACHE_DIR, f"{wl.name}_req{i}_{_key(wl, i)}.npy")
+    path = os.path.join(CACHE_DIR, f"{wl.name}_req{i}_{_key(wl, i)}.txt")
     if os.path.exists(path):
-        return np.load(path)
+        return np.loadtxt(path, dtype=np.float64, ndmin=1)
     t = time.time()
     ho, co = wl.history_offsets, wl.cand_offsets
     s = oracle.forward_request(wl.cfg.to_dict(), wl.weights, wl.history_emb[ho[i]:ho[i + 1]],
@@ -87,8 +90,8 @@ def request_scores(wl: W.Workload, i: int, verbose: bool = False) -> np.ndarray:
               f"{time.time() - t:.1f}s", flush=True)
     try:
         os.makedirs(CACHE_DIR, exist_ok=True)
-        tmp = path + f".tmp{os.getpid()}.npy"
-        np.save(tmp, s)
+        tmp = path + f".tmp{os.getpid()}"
+        np.savetxt(tmp, s, fmt="%.17g")
         os.replace(tmp, path)
     except OSError:
         pass
