@@ -54,7 +54,7 @@ typedef enum { FLAME_GR_F32 = 0, FLAME_GR_BF16 = 1 } flame_gr_dtype;
 /* Model shape and capacity.  Fixed for the life of a handle. */
 typedef struct {
   int32_t n_layers;      /* >= 1 */
-  int32_t d_model;       /* d; multiple of n_heads.  bf16: d % 64 == 0 and d/n_heads in {32,64,128} */
+  int32_t d_model;       /* d; multiple of n_heads.  bf16: d % 64 == 0 and d/n_heads in {32,64} */
   int32_t n_heads;       /* H */
   int32_t n_buckets;     /* relative-position buckets: power of two, >= 2 */
   int32_t max_rel_dist;  /* D: power of two >= n_buckets/2; distances >= D share the last bucket */

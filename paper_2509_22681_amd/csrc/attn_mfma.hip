@@ -3,13 +3,16 @@
 // For every query row r of a request and every head:
 //     O_r = sum over allowed keys c of silu(<Q_r, K_c> + bias[p_r - p_c]) V_c
 // Q arrives multiplied by alpha*log2(e), the bias table by log2(e) and V by ln(2), so the logits are
-// directly exp2 arguments: silu costs exp2, add, rcp, mul and the scale factors cancel in O.  History rows look at keys 0..r, candidate rows look at the
-// whole history and at themselves: the customised mask of Section 3.2 that lets all candidates of
-// a request be scored in one pass.  No score matrix is materialised: like a flash-attention tile
-// loop, but the pointwise SiLU needs neither running maximum nor rescaling.
+// directly exp2 arguments and the scale factors cancel in O.  History rows look at keys 0..r,
+// candidate rows look at the whole history and at themselves: the customised mask of Section 3.2
+// that lets all candidates of a request be scored in one pass.  No score matrix is materialised:
+// like a flash-attention tile loop, but the pointwise SiLU needs neither running maximum nor
+// rescaling.
 //
-// Work decomposition: one workgroup = (query tile of 128 rows, head); 4 wavefronts, 32 query rows
-// each; keys are walked in tiles of 64 staged through LDS (double buffered).
+// Work decomposition: one workgroup = (query tile of 256 rows, head); 4 wavefronts, 64 query rows
+// each (two 32-row MFMA blocks that share every K and V fragment read from LDS: fragment traffic, not
+// MFMA issue, is what bounds this loop on a CU with 128 B/clk of LDS); keys are walked in tiles of 64
+// staged through LDS (double buffered, next tile prefetched into registers).
 //
 // Register-level formulation: the products are computed transposed,
 //     S^T[kv][q] = K Q^T      (A operand = K rows, B operand = Q rows)
@@ -20,6 +23,15 @@
 // into MFMA row m makes accumulator elements 8s..8s+7 of a lane hold keys 16s+8*(lane/32)+0..7, which
 // is exactly the k order of a 16-deep B operand.  V is stored feature-major by the projection
 // kernel, so V^T tiles are plain row loads.
+//
+// SiLU: two routes to the same fp16 weights.  If every logit of a wavefront's 64x64 patch satisfies
+// |x| <= 2 and no mask is needed, a packed fp16 polynomial (five v_pk_* per two weights, within two
+// fp16 ulps); otherwise the exact exp2/rcp form in fp32 with the mask applied.
+//
+// Bias: each key tile brings a window of the per-distance table (by decreasing distance, fp32) into
+// LDS; a lane's 8 consecutive entries per accumulator half-block are read straight into the
+// accumulator registers, so the bias add costs LDS bandwidth but no VALU instruction (on this
+// chip VALU and MFMA work of one SIMD largely serialise, so every VALU instruction saved counts).
 #include "device_common.h"
 #include "kernels.h"
 
@@ -27,12 +39,27 @@ namespace flame {
 
 namespace {
 
-constexpr int QT = kAttnQTileBf16;  // query rows per workgroup (4 wavefronts x 32)
-static_assert(QT == 128, "4 wavefronts of 32 query rows");
-constexpr int KT = 64;       // keys per tile
-constexpr int PAD = 8;       // fp16 elements of LDS row padding
-constexpr int BW = 192;      // bias window per key tile, stored by decreasing distance:
-                             // slot u holds bias[q_first + 127 - k0 - u], u = 0..191
+constexpr int QT = kAttnQTileBf16;  // query rows per workgroup (4 wavefronts x 64)
+static_assert(QT == 256, "4 wavefronts of 64 query rows");
+constexpr int KT = 64;              // keys per tile
+constexpr int PAD = 8;              // fp16 elements of LDS row padding
+constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..318
+
+// Packed fp16 SiLU for small arguments, exp2 domain: for y = log2(e) x with |x| <= 2,
+//   log2(e) silu(x) = 0.5 y + t (b1 + b3 t + b5 t^2),  t = y^2,
+// where (b1, b3, b5) = (a1 ln2, a3 ln2^3, a5 ln2^5) and (a1, a3, a5) is the weighted least-squares fit of
+// (silu(x) - x/2)/x^2 on [-2, 2] (relative-error weights).  Evaluated in fp16 the result is within
+// 2.8e-3 (6e-4 rms) of the exact value, against 4.9e-4 for rounding the exact value to fp16.
+constexpr float kPolyA1 = 0.24916259f, kPolyA3 = -0.01916112f, kPolyA5 = 0.00112581f;
+constexpr float kPolyT2 = (2.0f * kLog2e) * (2.0f * kLog2e);     // bound on t = y^2
+__device__ __forceinline__ f16x2 silu_poly_pk(f16x2 y, f16x2 t) {
+  constexpr float b1 = kPolyA1 * kLn2, b3 = kPolyA3 * kLn2 * kLn2 * kLn2, b5 = kPolyA5 * kLn2 * kLn2 * kLn2 * kLn2 * kLn2;
+  const f16x2 c5 = {(half_t)b5, (half_t)b5}, c3 = {(half_t)b3, (half_t)b3}, c1 = {(half_t)b1, (half_t)b1};
+  const f16x2 hf = {(half_t)0.5f, (half_t)0.5f};
+  f16x2 p = __builtin_elementwise_fma(c5, t, c3);
+  p = __builtin_elementwise_fma(p, t, c1);
+  return __builtin_elementwise_fma(t, p, hf * y);
+}
 
 __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
   return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
@@ -49,9 +76,9 @@ __device__ __forceinline__ f16x8 pack8(const float *v) {
 }
 
 template <int DH>
-__global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict__ planes, const float *__restrict__ bias_lh,
-                                                        half_t *__restrict__ O, const AttnItem *__restrict__ items,
-                                                        int H, int d, int D, int64_t ws_rows) {
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restrict__ planes, const float *__restrict__ bias_lh,
+                                                           half_t *__restrict__ O, const AttnItem *__restrict__ items,
+                                                           int H, int d, int D, int64_t ws_rows) {
   constexpr int KS = DH / 16;          // k-steps of the Q K^T product
   constexpr int DB = DH / 32;          // 32-row blocks of O^T
   constexpr int NCH = DH / 32;         // 16-byte chunks per thread for one K (or V^T) tile
@@ -72,28 +99,32 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
   const half_t *Kp = planes + 3 * plane + head * DH;
   const float *bias = bias_lh + (int64_t)head * D;
 
-  // this wavefront's 32 query rows
-  const int q_local0 = wave * 32;
+  // this wavefront's 64 query rows = two 32-row blocks qb = 0, 1
+  const int q_local0 = wave * 64;
   const bool wave_active = q_local0 < it.n_q;
-  const int my_q_local = q_local0 + l32;
-  const bool row_valid = my_q_local < it.n_q;
-  const int64_t my_row = it.q_row + (row_valid ? my_q_local : it.n_q - 1);   // clamped for loads
-  // position of my query row; number of history keys it may see
-  const int q_index = it.is_cand ? it.L : it.q_pos + my_q_local;
-  const int n_vis = visible_history(it.is_cand, q_index, it.L);
+  int my_q_local[2], n_vis[2];
+  bool row_valid[2];
+  f16x8 fq[2][KS];                     // Q fragments (B operand of S^T): row = my query, k = 16*s + 8*lhalf + 0..7
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    my_q_local[qb] = q_local0 + 32 * qb + l32;
+    row_valid[qb] = my_q_local[qb] < it.n_q;
+    const int64_t row = it.q_row + (row_valid[qb] ? my_q_local[qb] : it.n_q - 1);   // clamped for loads
+    const int q_index = it.is_cand ? it.L : it.q_pos + my_q_local[qb];
+    n_vis[qb] = visible_history(it.is_cand, q_index, it.L);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) fq[qb][s] = *(const f16x8 *)(Qp + row * d + s * 16 + lhalf * 8);
+  }
   const int wave_vis_min = it.is_cand ? it.L : it.q_pos + q_local0 + 1;
-  const int wave_vis_max = it.is_cand ? it.L : it.q_pos + q_local0 + 32;
+  const int wave_vis_max = it.is_cand ? it.L : it.q_pos + q_local0 + 64;
 
-  // Q fragments (B operand of S^T): row = my query, k = 16*s + 8*lhalf + 0..7
-  f16x8 fq[KS];
+  f32x16 oacc[2][DB];
 #pragma unroll
-  for (int s = 0; s < KS; ++s) fq[s] = *(const f16x8 *)(Qp + my_row * d + s * 16 + lhalf * 8);
-
-  f32x16 oacc[DB];
+  for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-  for (int b = 0; b < DB; ++b)
+    for (int b = 0; b < DB; ++b)
 #pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
+      for (int e = 0; e < 16; ++e) oacc[qb][b][e] = 0.f;
 
   const int n_tiles = (it.n_kv + KT - 1) / KT;
   const int q_first = it.is_cand ? it.L : it.q_pos;     // position of query row 0 of the workgroup tile
@@ -114,10 +145,10 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
     gV[i] = Vt + (int64_t)rr * ws_rows + it.kv_row + cc * 8;
     oV[i] = rr * (KT + PAD) + cc * 8;
   }
-  const int bias_t = tid < BW ? tid : BW - 1;
-  const int delta0 = q_first + (QT - 1) - bias_t;       // distance held by window slot bias_t for tile 0
+  // bias window: thread t stages slots t and (t < BW-256) t + 256
+  const int delta0 = q_first + (QT - 1) - tid;          // distance held by window slot tid for tile 0
   uint4 rk[NCH], rv[NCH];
-  float rbias;
+  float rb0, rb1;
 #define ATTN_LOAD_TILE(T)                                                                   \
   {                                                                                         \
     const int k0_ = (T) * KT;                                                               \
@@ -126,8 +157,11 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
       rv[i] = *(const uint4 *)(gV[i] + k0_);                                                \
     }                                                                                       \
     int dl_ = delta0 - k0_;                                                                 \
+    int dh_ = dl_ - 256;                                                                    \
     dl_ = dl_ < 0 ? 0 : (dl_ > D - 1 ? D - 1 : dl_);                                        \
-    rbias = bias[dl_];                                                                      \
+    dh_ = dh_ < 0 ? 0 : (dh_ > D - 1 ? D - 1 : dh_);                                        \
+    rb0 = bias[dl_];                                                                        \
+    rb1 = bias[dh_];                                                                        \
   }
 #define ATTN_STORE_TILE(BUF)                                                                \
   {                                                                                         \
@@ -135,7 +169,8 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
       *(uint4 *)(&sK[BUF][0][0] + oK[i]) = rk[i];                                           \
       *(uint4 *)(&sVt[BUF][0][0] + oV[i]) = rv[i];                                          \
     }                                                                                       \
-    sBias[BUF][bias_t] = rbias;                                                             \
+    sBias[BUF][tid] = rb0;                                                                  \
+    if (tid < BW - 256) sBias[BUF][tid + 256] = rb1;                                        \
   }
 
   if (n_tiles > 0) {
@@ -144,8 +179,12 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
   }
   __syncthreads();
 
-  // window slot of (my row, key 0 of the tile); keys further right sit at increasing slots
-  const int bias_base = (QT - 1) - (it.is_cand ? 0 : my_q_local) + 8 * lhalf;
+  // Window slot of (my row of block qb, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's
+  // index in the workgroup tile (0 for candidate rows: they all sit at the same distance from a
+  // key); keys further right sit at increasing slots.
+  int bias_idx[2];
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) bias_idx[qb] = (QT - 1) - (it.is_cand ? 0 : my_q_local[qb]) + 8 * lhalf;
 
   for (int t = 0; t < n_tiles; ++t) {
     const int buf = t & 1;
@@ -154,45 +193,103 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
     ATTN_LOAD_TILE(tn);
     __builtin_amdgcn_sched_barrier(0);   // the prefetch stays ahead of the tile's arithmetic
     if (wave_active && k0 < wave_vis_max) {
-      // ---- S^T = K Q^T + bias, two blocks of 32 keys
-      f32x16 sacc[2];
+      // ---- S^T = K Q^T: blocks [qb][j], j = 32-key half of the tile; K fragments shared by both qb.
+      // Fragment reads run one group ahead of the MFMAs that use them (and the first V^T group is
+      // fetched behind the last K group), so LDS latency hides behind matrix work instead of being
+      // paid once per group.
+      f32x16 sacc[2][2];
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+      for (int qb = 0; qb < 2; ++qb)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) sacc[j][e] = sBias[buf][bias_base + 32 * j + 16 * (e >> 3) + (e & 7)];
+        for (int j = 0; j < 2; ++j)
 #pragma unroll
-      for (int s = 0; s < KS; ++s)
+          for (int e = 0; e < 16; ++e) sacc[qb][j][e] = sBias[buf][bias_idx[qb] + 32 * j + 16 * (e >> 3) + (e & 7)];
+      f16x8 fk[2][2], fv[2][DB];
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          const f16x8 fk = *(const f16x8 *)&sK[buf][32 * j + pi32(l32)][s * 16 + lhalf * 8];
-          sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sacc[j], 0, 0, 0);
+      for (int j = 0; j < 2; ++j) fk[0][j] = *(const f16x8 *)&sK[buf][32 * j + pi32(l32)][lhalf * 8];
+#pragma unroll
+      for (int s = 0; s < KS; ++s) {
+        if (s + 1 < KS) {
+#pragma unroll
+          for (int j = 0; j < 2; ++j) fk[(s + 1) & 1][j] = *(const f16x8 *)&sK[buf][32 * j + pi32(l32)][(s + 1) * 16 + lhalf * 8];
+        } else {
+#pragma unroll
+          for (int b = 0; b < DB; ++b) fv[0][b] = *(const f16x8 *)&sVt[buf][32 * b + l32][lhalf * 8];
         }
-      // ---- P^T = silu(S^T), masked where the tile reaches past what a row may see
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+            sacc[qb][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk[s & 1][j], fq[qb][s], sacc[qb][j], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      // ---- P^T = silu(S^T) (the bias is already in the accumulators)
       const bool need_mask = k0 + KT > wave_vis_min;
-      f16x8 fp[4];
+      f16x8 fp[2][4];
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        float p[16];
+      for (int qb = 0; qb < 2; ++qb) {
+        bool fast = false;
+        if (!need_mask) {
+          f16x2 yh[2][8], th[2][8];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) p[e] = silu_log2_domain(sacc[j][e]);
-        if (need_mask) {
+          for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) {
-            const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-            p[e] = kv < n_vis ? p[e] : 0.f;
+            for (int i = 0; i < 8; ++i) {
+              yh[j][i] = f16x2{(half_t)sacc[qb][j][2 * i], (half_t)sacc[qb][j][2 * i + 1]};
+              th[j][i] = yh[j][i] * yh[j][i];
+            }
+          f16x2 m = th[0][0];
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int i = 0; i < 8; ++i) m = __builtin_elementwise_max(m, th[j][i]);
+          const bool bad = !((float)m[0] <= kPolyT2 && (float)m[1] <= kPolyT2);     // NaN counts as bad
+          fast = __builtin_amdgcn_ballot_w64(bad) == 0;
+          if (fast) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                const f16x2 w = silu_poly_pk(yh[j][i], th[j][i]);
+                fp[qb][2 * j + (i >> 2)][2 * (i & 3)] = w[0];
+                fp[qb][2 * j + (i >> 2)][2 * (i & 3) + 1] = w[1];
+              }
           }
         }
-        fp[2 * j] = pack8(p);
-        fp[2 * j + 1] = pack8(p + 8);
-      }
-      // ---- O^T += V^T P^T
+        if (!fast) {
 #pragma unroll
-      for (int s2 = 0; s2 < 4; ++s2)
+          for (int j = 0; j < 2; ++j) {
+            float p[16];
 #pragma unroll
-        for (int b = 0; b < DB; ++b) {
-          const f16x8 fv = *(const f16x8 *)&sVt[buf][32 * b + l32][s2 * 16 + lhalf * 8];
-          oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp[s2], oacc[b], 0, 0, 0);
+            for (int e = 0; e < 16; ++e) p[e] = silu_log2_domain(sacc[qb][j][e]);
+            if (need_mask) {
+#pragma unroll
+              for (int e = 0; e < 16; ++e) {
+                const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
+                p[e] = kv < n_vis[qb] ? p[e] : 0.f;
+              }
+            }
+            fp[qb][2 * j] = pack8(p);
+            fp[qb][2 * j + 1] = pack8(p + 8);
+          }
         }
+      }
+      // ---- O^T += V^T P^T; V^T fragments shared by both qb, read one group ahead
+#pragma unroll
+      for (int s2 = 0; s2 < 4; ++s2) {
+        if (s2 + 1 < 4) {
+#pragma unroll
+          for (int b = 0; b < DB; ++b) fv[(s2 + 1) & 1][b] = *(const f16x8 *)&sVt[buf][32 * b + l32][(s2 + 1) * 16 + lhalf * 8];
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int b = 0; b < DB; ++b)
+#pragma unroll
+          for (int qb = 0; qb < 2; ++qb)
+            oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv[s2 & 1][b], fp[qb][s2], oacc[qb][b], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
     __builtin_amdgcn_sched_barrier(0);
     ATTN_STORE_TILE(buf ^ 1);
@@ -201,45 +298,50 @@ __global__ __launch_bounds__(256) void attn_bf16_kernel(const half_t *__restrict
 #undef ATTN_LOAD_TILE
 #undef ATTN_STORE_TILE
 
-  // ---- candidates: the row itself is one more key, at distance 0.  Each wavefront multiplies its
-  // 32 candidate rows against themselves and keeps the diagonal.
+  // ---- candidates: the row itself is one more key, at distance 0.  Each 32-row block multiplies
+  // its candidate rows against themselves and keeps the diagonal.
   if (it.is_cand && wave_active) {
-    const int64_t base_row = it.q_row + q_local0;        // multiple of 32 inside the padded workspace
-    f32x16 sacc;
     const float b0 = bias[0];
 #pragma unroll
-    for (int e = 0; e < 16; ++e) sacc[e] = b0;
+    for (int qb = 0; qb < 2; ++qb) {
+      const int64_t base_row = it.q_row + q_local0 + 32 * qb;   // multiple of 32 inside the padded workspace
+      f32x16 sacc;
 #pragma unroll
-    for (int s = 0; s < KS; ++s) {
-      const f16x8 fk = *(const f16x8 *)(Kp + (base_row + pi32(l32)) * d + s * 16 + lhalf * 8);
-      sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sacc, 0, 0, 0);
-    }
-    float p[16];
+      for (int e = 0; e < 16; ++e) sacc[e] = b0;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
-      const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
-      p[e] = (kv_local == l32 && row_valid) ? silu_log2_domain(sacc[e]) : 0.f;
-    }
-    f16x8 fp[2] = {pack8(p), pack8(p + 8)};
-#pragma unroll
-    for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-      for (int b = 0; b < DB; ++b) {
-        const f16x8 fv = *(const f16x8 *)(Vt + (int64_t)(32 * b + l32) * ws_rows + base_row + s2 * 16 + lhalf * 8);
-        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fp[s2], oacc[b], 0, 0, 0);
+      for (int s = 0; s < KS; ++s) {
+        const f16x8 fk = *(const f16x8 *)(Kp + (base_row + pi32(l32)) * d + s * 16 + lhalf * 8);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[qb][s], sacc, 0, 0, 0);
       }
+      float p[16];
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
+        p[e] = (kv_local == l32 && row_valid[qb]) ? silu_log2_domain(sacc[e]) : 0.f;
+      }
+      const f16x8 fps[2] = {pack8(p), pack8(p + 8)};
+#pragma unroll
+      for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+        for (int b = 0; b < DB; ++b) {
+          const f16x8 fv = *(const f16x8 *)(Vt + (int64_t)(32 * b + l32) * ws_rows + base_row + s2 * 16 + lhalf * 8);
+          oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fps[s2], oacc[qb][b], 0, 0, 0);
+        }
+    }
   }
 
   // ---- write O[q][head*DH + dd]; accumulator element e of block b: dd = 32b + 8*(e/4) + 4*lhalf + e%4
-  if (row_valid) {
-    half_t *orow = O + (it.q_row + my_q_local) * (int64_t)d + head * DH;
+#pragma unroll
+  for (int qb = 0; qb < 2; ++qb) {
+    if (!row_valid[qb]) continue;
+    half_t *orow = O + (it.q_row + my_q_local[qb]) * (int64_t)d + head * DH;
 #pragma unroll
     for (int b = 0; b < DB; ++b)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         f16x4 v;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[b][4 * g + i]);
+        for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[qb][b][4 * g + i]);
         *(f16x4 *)(orow + 32 * b + 8 * g + 4 * lhalf) = v;
       }
   }
@@ -251,10 +353,9 @@ void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const A
                       const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   const int grid = n_items * sh.H;
-#define ATTN_CASE(DHV) attn_bf16_kernel<DHV><<<grid, 256, 0, s>>>((const half_t *)planes, bias_lh, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
+#define ATTN_CASE(DHV) attn_mfma_kernel<DHV><<<grid, 256, 0, s>>>((const half_t *)planes, bias_lh, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
   if (sh.dh == 32) ATTN_CASE(32);
-  else if (sh.dh == 64) ATTN_CASE(64);
-  else ATTN_CASE(128);
+  else ATTN_CASE(64);
 #undef ATTN_CASE
 }
 

@@ -58,7 +58,7 @@ void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const A
 void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
-constexpr int kAttnQTileBf16 = 128;  // query rows per attention work item, bf16 path
+constexpr int kAttnQTileBf16 = 256;  // query rows per attention work item, MFMA path
 constexpr int kAttnQTileF32 = 64;    // fp32 path
 
 }  // namespace flame

@@ -27,8 +27,8 @@ int validate_config(const flame_gr_config &c, std::string &err) {
   if (c.n_streams < 0 || c.n_streams > 16) return bad("n_streams must be in [0, 16]");
   if (c.dtype == FLAME_GR_BF16) {
     int dh = c.d_model / c.n_heads;
-    if (c.d_model % 64 || !(dh == 32 || dh == 64 || dh == 128)) {
-      err = "bf16 path needs d_model % 64 == 0 and head width 32, 64 or 128";
+    if (c.d_model % 64 || !(dh == 32 || dh == 64)) {
+      err = "bf16 path needs d_model % 64 == 0 and head width 32 or 64";
       return FLAME_GR_UNSUPPORTED;
     }
   } else if (c.d_model / c.n_heads > 256) {

@@ -92,8 +92,8 @@ STRESS = {
     "S2": dict(L=[0, 1, 300], M=[2, 0, 5], d=64, H=2, nb=16, D=256),
     # lengths that are multiples of no tile size
     "S3": dict(L=[700], M=[130], d=128, H=2, nb=16, D=1024),
-    # several ragged requests, head width 128
-    "S4": dict(L=[65, 127, 129, 3], M=[1, 63, 65, 200], d=128, H=1, nb=32, D=128),
+    # several ragged requests around the tile sizes
+    "S4": dict(L=[65, 127, 129, 3, 257, 300], M=[1, 63, 65, 200, 255, 257], d=128, H=2, nb=32, D=128),
 }
 
 

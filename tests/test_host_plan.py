@@ -141,7 +141,8 @@ def test_config_validation_codes():
     ho, co = np.array([0, 4], np.int32), np.array([0, 2], np.int32)
     for kw, code in [(dict(n_layers=0), -1), (dict(d_model=65), -1), (dict(n_buckets=12), -1),
                      (dict(max_rel_dist=1000), -1), (dict(dtype=7), -1), (dict(n_streams=99), -1),
-                     (dict(d_model=96, n_heads=2), -5), (dict(d_model=64, n_heads=4), -5)]:
+                     (dict(d_model=96, n_heads=2), -5), (dict(d_model=64, n_heads=4), -5),
+                     (dict(d_model=128, n_heads=1), -5)]:
         with pytest.raises(B.FlameGRError) as e:
             B.flame_gr_host_plan(_cfg(**kw), ho, co)
         assert e.value.code == code, kw
