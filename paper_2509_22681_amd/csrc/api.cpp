@@ -46,7 +46,7 @@ struct flame_gr {
   // workspaces (device)
   float *X = nullptr;
   void *Xb = nullptr, *planes = nullptr, *O = nullptr, *G = nullptr;   // Xb: fp16 copy of X (MFMA path)
-  void *W1h = nullptr, *W2h = nullptr;                                   // fp16 copies of the projection matrices
+  void *W1h = nullptr, *W2h = nullptr, *W2p = nullptr;                   // fp16 copies of the projection matrices (W2p: fragment-major)
   float *bias = nullptr;
   int32_t *bucket_tab = nullptr;
   // plan staging
@@ -107,7 +107,7 @@ float half_bits_to_float(uint16_t b) {
 void free_all(flame_gr *h) {
   (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->O); (void)hipFree(h->G);
   (void)hipFree(h->bias); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
-  (void)hipFree(h->W1h); (void)hipFree(h->W2h);
+  (void)hipFree(h->W1h); (void)hipFree(h->W2h); (void)hipFree(h->W2p);
   (void)hipFree(h->cap_planes); (void)hipFree(h->cap_O); (void)hipFree(h->cap_X);
   for (int i = 0; i < kStageSlots; ++i) {
     if (h->stage_host[i]) (void)hipHostFree(h->stage_host[i]);
@@ -187,16 +187,18 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
       if (dt == FLAME_GR_BF16) launch_attn_bf16(h->planes, bias_l, h->O, it, n_it, sh, s);
       else launch_attn_f32((const float *)h->planes, bias_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
     }
-    {
-      Timed t(h, KIND_LNGATE, s);
-      if (last) launch_ln_gate(dt, h->O, h->planes, lg, lb, h->G, blocks, cl, n_cblk, 0, d, sh.eps, s);
-      else launch_ln_gate(dt, h->O, h->planes, lg, lb, h->G, blocks, nullptr, n_blk, G.blk_begin, d, sh.eps, s);
-    }
-    {
+    const int32_t *bl = last ? cl : nullptr;
+    const int nb = last ? n_cblk : n_blk;
+    const int bf = last ? 0 : G.blk_begin;
+    if (dt == FLAME_GR_BF16 && k3_fused_supported(d)) {
       Timed t(h, KIND_OUTPROJ, s);
-      const int32_t *bl = last ? cl : nullptr;
-      const int nb = last ? n_cblk : n_blk;
-      const int bf = last ? 0 : G.blk_begin;
+      launch_k3_fused(h->O, h->planes, lg, lb, (const char *)h->W2p + (size_t)l * d * d * e, b2, h->X, h->Xb, blocks, bl, nb, bf, sh, s);
+    } else {
+      {
+        Timed t(h, KIND_LNGATE, s);
+        launch_ln_gate(dt, h->O, h->planes, lg, lb, h->G, blocks, bl, nb, bf, d, sh.eps, s);
+      }
+      Timed t(h, KIND_OUTPROJ, s);
       if (dt == FLAME_GR_BF16) launch_outproj_bf16(h->G, w2, b2, h->X, h->Xb, bl, nb, bf, sh, s);
       else launch_outproj_f32((const float *)h->G, (const float *)w2, (const float *)b2, h->X, bl, nb, bf, sh, s);
     }
@@ -271,6 +273,7 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
     CR(hipMalloc(&h->Xb, rows * d * e));
     CR(hipMalloc(&h->W1h, (size_t)cfg.n_layers * 4 * d * d * e));
     CR(hipMalloc(&h->W2h, (size_t)cfg.n_layers * d * d * e));
+    CR(hipMalloc(&h->W2p, (size_t)cfg.n_layers * d * d * e));
   }
   CR(hipMalloc(&h->bias, (size_t)cfg.n_layers * cfg.n_heads * cfg.max_rel_dist * sizeof(float)));
   CR(hipMalloc(&h->bucket_tab, (size_t)cfg.max_rel_dist * sizeof(int32_t)));
@@ -372,7 +375,8 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
       // the caller owns the weights and may have changed them: convert on every forward
       const int64_t dd = (int64_t)h->sh.d * h->sh.d;
       launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dd, s0);
-      launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dd, s0);
+      if (k3_fused_supported(h->sh.d)) launch_pack_w2(w->w2, h->W2p, h->sh.d, h->sh.n_layers, s0);
+      else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dd, s0);
     }
     launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
                        h->cfg.dtype == FLAME_GR_BF16 ? 1.4426950408889634f : 1.0f, s0);

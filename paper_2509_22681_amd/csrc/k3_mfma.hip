@@ -1,0 +1,224 @@
+// K3 of the GR block, fused: X <- X + (LayerNorm_d(O) * U) W2^T + b2, Xh = fp16(X).
+//
+// LayerNorm, the U gate, the output projection and the residual run in one kernel (the fusion of
+// layer normalisation with the following linear projection that Section 3.2 describes), so the
+// gated activations never travel through HBM.  The kernel is HBM-bound by construction (per row it
+// must read O and U and read-modify-write X: 14 bytes per element against 2*d flops), so the
+// design aims at streaming, not at MFMA utilisation:
+//   * one workgroup = one 64-row block of the workspace, all d output features (d <= 512 per pass);
+//   * phase 1: each wavefront normalises 16 rows (one row per wavefront-wide 16-byte load, statistics
+//     by wavefront reduction in fp32: mean, then centred second moment) and writes the gated fp16 rows
+//     into LDS, 16-byte chunks XOR-swizzled so that the MFMA operand reads are conflict free;
+//   * phase 2: each wavefront owns d/4 output features; the W2 operand comes straight from L2 in a
+//     fragment-major packed layout (one coalesced 1 KB read per MFMA operand, prepared once per forward
+//     by pack_w2_kernel), so LDS holds only the activations and two workgroups fit on a CU;
+//   * phase 3: residual add in fp32, fp16 copy for the next layer's projection.
+#include "device_common.h"
+#include "kernels.h"
+
+namespace flame {
+
+namespace {
+
+// W2p[ks][cb][lane][0..7] = W2[32*cb + lane%32][16*ks + 8*(lane/32) + 0..7]  (bf16 -> fp16)
+__global__ __launch_bounds__(256) void pack_w2_kernel(const bf16_t *__restrict__ W2, half_t *__restrict__ W2p, int d, int n_layers) {
+  const int64_t per_layer = (int64_t)d * d / 8;            // 16-byte chunks
+  const int64_t total = per_layer * n_layers;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    const int64_t l = i / per_layer, c = i % per_layer;
+    const int lane = (int)(c & 63);
+    const int64_t t = c >> 6;
+    const int cb = (int)(t % (d / 32)), ks = (int)(t / (d / 32));
+    const bf16x8 v = *(const bf16x8 *)(W2 + l * d * d + (int64_t)(32 * cb + (lane & 31)) * d + 16 * ks + 8 * (lane >> 5));
+    f16x8 o;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) o[k] = to_f16_sat((float)v[k]);
+    *(f16x8 *)(W2p + (l * per_layer + c) * 8) = o;
+  }
+}
+
+// NBW: 32-feature blocks per wavefront (d = 128 * NBW)
+template <int NBW>
+__global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restrict__ O, const half_t *__restrict__ U,
+                                                          const bf16_t *__restrict__ gamma, const bf16_t *__restrict__ beta,
+                                                          const half_t *__restrict__ W2p, const bf16_t *__restrict__ b2,
+                                                          float *__restrict__ X, half_t *__restrict__ Xh,
+                                                          const RowBlock *__restrict__ blocks, const int32_t *__restrict__ blk_list,
+                                                          int blk_first, float eps) {
+  constexpr int d = 128 * NBW;
+  constexpr int NCHUNK = d / 8;                  // 16-byte chunks per row
+  constexpr int CPL = (NCHUNK + 63) / 64;        // chunks per lane in phase 1
+  extern __shared__ __attribute__((aligned(16))) char smem[];   // sG: 64 rows x d fp16, swizzled
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int l32 = lane & 31, lhalf = lane >> 5;
+  const int blk = blk_list ? blk_list[blockIdx.x] : blk_first + blockIdx.x;
+  const int n_valid = blocks[blk].n_valid;
+  const int64_t row0 = (int64_t)blk * kRowAlign;
+
+  // ---- phase 1: G = (LN(O) * gamma + beta) * U -> LDS
+  float g[CPL][8], bt[CPL][8];
+#pragma unroll
+  for (int c = 0; c < CPL; ++c) {
+    const int ch = lane + 64 * c;
+    if (ch < NCHUNK) {
+      const bf16x8 gv = *(const bf16x8 *)(gamma + ch * 8), bv = *(const bf16x8 *)(beta + ch * 8);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) { g[c][k] = (float)gv[k]; bt[c][k] = (float)bv[k]; }
+    }
+  }
+  // Rows are taken four at a time, and the loads of the next four are issued before the current
+  // four are normalised: with one row in flight per wavefront the kernel would run at the latency,
+  // not the bandwidth, of HBM.
+  constexpr int RB4 = 4;
+  f16x8 ov[2][RB4][CPL], uv[2][RB4][CPL];
+  auto issue = [&](int set, int batch) {
+#pragma unroll
+    for (int q = 0; q < RB4; ++q)
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) {
+        const int ch = lane + 64 * c;
+        if (ch < NCHUNK) {
+          const int64_t off = (row0 + wave * 16 + batch * RB4 + q) * d + ch * 8;
+          ov[set][q][c] = *(const f16x8 *)(O + off);
+          uv[set][q][c] = *(const f16x8 *)(U + off);
+        }
+      }
+  };
+  issue(0, 0);
+#pragma unroll
+  for (int batch = 0; batch < 16 / RB4; ++batch) {
+    const int set = batch & 1;
+    if (batch + 1 < 16 / RB4) issue(set ^ 1, batch + 1);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int q = 0; q < RB4; ++q) {
+      const int r = wave * 16 + batch * RB4 + q;
+      float v[CPL][8];
+      float sum = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPL; ++c)
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          v[c][k] = lane + 64 * c < NCHUNK ? (float)ov[set][q][c][k] : 0.f;
+          sum += v[c][k];
+        }
+      const float mu = wave_sum(sum) * (1.0f / d);
+      float sq = 0.f;
+#pragma unroll
+      for (int c = 0; c < CPL; ++c)
+        if (lane + 64 * c < NCHUNK) {
+#pragma unroll
+          for (int k = 0; k < 8; ++k) { const float t = v[c][k] - mu; sq += t * t; }
+        }
+      const float rstd = rsqrtf(wave_sum(sq) * (1.0f / d) + eps);
+      const bool pad = r >= n_valid;               // padding rows carry a zero branch so that they stay finite
+#pragma unroll
+      for (int c = 0; c < CPL; ++c) {
+        const int ch = lane + 64 * c;
+        if (ch < NCHUNK) {
+          f16x8 o;
+#pragma unroll
+          for (int k = 0; k < 8; ++k)
+            o[k] = pad ? (half_t)0.f : to_f16_sat(((v[c][k] - mu) * rstd * g[c][k] + bt[c][k]) * (float)uv[set][q][c][k]);
+          *(f16x8 *)(smem + r * (d * 2) + ((ch ^ (r & 7)) << 4)) = o;
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  __syncthreads();
+
+  // ---- phase 2: acc[token][feature] over k; features of this wavefront: wave*32*NBW .. +32*NBW-1
+  f32x16 acc[2][NBW];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  constexpr int NKS = d / 16;
+  const half_t *wp = W2p + ((int64_t)(wave * NBW) * 64 + lane) * 8;      // + (ks * (d/32) + j) * 512
+  f16x8 fw[2][NBW], fa[2][2];
+#pragma unroll
+  for (int j = 0; j < NBW; ++j) fw[0][j] = *(const f16x8 *)(wp + (int64_t)j * 512);
+#pragma unroll
+  for (int i = 0; i < 2; ++i) {
+    const int r = 32 * i + l32;
+    fa[0][i] = *(const f16x8 *)(smem + r * (d * 2) + ((lhalf ^ (r & 7)) << 4));
+  }
+#pragma unroll 4
+  for (int ks = 0; ks < NKS; ++ks) {
+    const int cur = ks & 1, nxt = cur ^ 1;
+    const int kn = ks + 1 < NKS ? ks + 1 : ks;
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) fw[nxt][j] = *(const f16x8 *)(wp + ((int64_t)kn * (d / 32) + j) * 512);
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int r = 32 * i + l32;
+      fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ (r & 7)) << 4));
+    }
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < NBW; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
+  }
+
+  // ---- phase 3: lane = token 32*i + l32; elements = features 32*(wave*NBW + j) + 8g + 4*lhalf + 0..3.
+  // The residual rows of the next (i, j) block are requested before the current block is finished.
+  f32x4 xr[2][4];
+  auto load_x = [&](int set, int i, int j) {
+    const int64_t m = row0 + 32 * i + l32;
+    const int nn = 32 * (wave * NBW + j) + 4 * lhalf;
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) xr[set][gq] = *(const f32x4 *)(X + m * d + nn + 8 * gq);
+  };
+  load_x(0, 0, 0);
+#pragma unroll
+  for (int ij = 0; ij < 2 * NBW; ++ij) {
+    const int i = ij / NBW, j = ij % NBW, set = ij & 1;
+    if (ij + 1 < 2 * NBW) load_x(set ^ 1, (ij + 1) / NBW, (ij + 1) % NBW);
+    const int64_t m = row0 + 32 * i + l32;
+    const int nn = 32 * (wave * NBW + j) + 4 * lhalf;
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq) {
+      const bf16x4 bv = *(const bf16x4 *)(b2 + nn + 8 * gq);
+      f32x4 x = xr[set][gq];
+      f16x4 o;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        x[q] += acc[i][j][4 * gq + q] + (float)bv[q];
+        o[q] = to_f16_sat(x[q]);
+      }
+      *(f32x4 *)(X + m * d + nn + 8 * gq) = x;
+      *(f16x4 *)(Xh + m * d + nn + 8 * gq) = o;
+    }
+  }
+}
+
+}  // namespace
+
+bool k3_fused_supported(int d) { return d == 128 || d == 256 || d == 512; }
+
+void launch_pack_w2(const void *W2, void *W2p, int d, int n_layers, hipStream_t s) {
+  const int64_t total = (int64_t)d * d / 8 * n_layers;
+  int grid = (int)((total + 255) / 256 > 2048 ? 2048 : (total + 255) / 256);
+  pack_w2_kernel<<<grid, 256, 0, s>>>((const bf16_t *)W2, (half_t *)W2p, d, n_layers);
+}
+
+void launch_k3_fused(const void *O, const void *U, const void *gamma, const void *beta, const void *W2p_layer, const void *b2,
+                     float *X, void *Xh, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first,
+                     const Shape &sh, hipStream_t s) {
+  if (n_blk <= 0) return;
+  const size_t lds = (size_t)kRowAlign * sh.d * 2;
+#define K3_CASE(NB) k3_fused_kernel<NB><<<n_blk, 256, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
+    (const half_t *)W2p_layer, (const bf16_t *)b2, X, (half_t *)Xh, blocks, blk_list, blk_first, sh.eps)
+  if (sh.d == 512) K3_CASE(4);
+  else if (sh.d == 256) K3_CASE(2);
+  else K3_CASE(1);
+#undef K3_CASE
+}
+
+}  // namespace flame
