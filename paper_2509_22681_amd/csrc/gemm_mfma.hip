@@ -248,6 +248,10 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
                       int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s) {
   if (n_blk <= 0 || !(plane_mask & 0xF)) return;
+  if (uvqk256_supported(sh.d)) {
+    launch_uvqk256(Xh, W1h, b1, planes, blk_list, n_blk, blk_first, plane_mask, sh, s);
+    return;
+  }
   PlaneSel sel{};
   for (int p = 0; p < 4; ++p)
     if (plane_mask & (1 << p)) sel.id[sel.n++] = p;

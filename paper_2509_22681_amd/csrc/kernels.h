@@ -58,6 +58,12 @@ void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const A
 void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
+// K1 on 256 x 256 tiles for d % 256 == 0 (gemm256_mfma.hip); same contract as launch_uvqk_bf16, which
+// dispatches to it.
+bool uvqk256_supported(int d);
+void launch_uvqk256(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list, int n_blk,
+                    int blk_first, int plane_mask, const Shape &sh, hipStream_t s);
+
 // K3 fused (k3_mfma.hip): LayerNorm * U gate + output projection + residual in one kernel, for
 // d in {128, 256, 512}; W2p is the fragment-major packed fp16 copy of W2 written by launch_pack_w2.
 bool k3_fused_supported(int d);
