@@ -6,12 +6,19 @@
 // Tiling.  A 128x128 tile re-reads 1 byte of operand per 64 flop, which at MFMA speed is twice what
 // the L2 delivers (measured about 19 TB/s), so the block tile is 256 x BN (BN = 128 where d allows):
 // 256 threads = 4 wavefronts in a 2x2 arrangement, each owning 128 x BN/2 as 4 x (BN/64) blocks of
-// v_mfma_f32_32x32x16_f16.  k advances in steps of 32 through two LDS stages; the next stage is
-// prefetched global -> registers while the MFMAs of the current one run and is written to LDS
-// behind them (the role the cp.async pipeline plays in Section 3.2).  Two workgroups fit on a CU
-// (48 KB LDS, <= 256 VGPRs), so one workgroup's epilogue (VALU: SiLU, conversion) overlaps the
-// other's MFMA phase.  LDS rows are 64 bytes; 16-byte chunks are XOR-swizzled over 128-byte lines so
-// that both the staging writes and the fragment reads are bank-conflict free without padding.
+// v_mfma_f32_32x32x16_f16.  Two workgroups share a CU: with K = d as short as 512 the fixed cost of a
+// tile (pipeline fill, epilogue) is a third of its time and only another resident workgroup hides it
+// (a 256 x 256 tile at one workgroup per CU measured slower for exactly that reason).
+//
+// Pipeline (the role the cp.async pipeline plays in Section 3.2): k advances in steps of 32 through a
+// ring of three LDS stages filled by LDS-DMA loads (global_load_lds_dwordx4: no staging registers,
+// lane i of an instruction lands at base + 16 i).  Iteration kt waits for its own DMA of tile kt, passes
+// one barrier (tile kt complete for everybody, tile kt-1 vacated by everybody), requests tile kt+2
+// into the vacated stage - two iterations of flight time - and multiplies tile kt; the fragment reads
+// of the second 16-deep step are issued behind the first MFMAs of the first step, so that they run
+// under matrix work and nothing waits on them early.  LDS rows are 64 bytes; 16-byte chunks are
+// XOR-swizzled over 128-byte lines (each DMA lane fetches the chunk that belongs in its slot), which
+// makes the fragment reads bank-conflict free without padding.
 //
 // Rows are addressed through 64-row blocks so that the same kernel runs on a contiguous range or on
 // a list of candidate blocks (last-layer pruning).
@@ -47,7 +54,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   constexpr int MB = 4;                 // 32-row MFMA blocks per wavefront
   constexpr int NB = WN / 32;           // 32-column MFMA blocks per wavefront
   constexpr int A_BYTES = BM * BK * 2, B_BYTES = BN * BK * 2, STAGE = A_BYTES + B_BYTES;
-  __shared__ __attribute__((aligned(128))) char smem[2 * STAGE];
+  constexpr int NSTAGE = 3;
+  __shared__ __attribute__((aligned(128))) char smem[NSTAGE * STAGE];
 
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -91,30 +99,28 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     blk[r] = t < n_blk ? (blk_list ? blk_list[t] : blk_first + t) : -1;
   }
 
-  // global -> register staging: 16-byte chunks, 4 per 32-wide row
-  constexpr int A_CH = BM * 4 / 256, B_CH = BN * 4 / 256;
-  const half_t *gA[A_CH];
-  const half_t *gB[B_CH];
-  int oA[A_CH], oB[B_CH];
+  // LDS-DMA sources.  One instruction of a wavefront fills 1 KB = 8 lines = 16 tile rows; lane p owns
+  // physical slot p & 7 of line p >> 3 and must fetch the chunk the swizzle maps there:
+  // slot = (p & 7) ^ (line & 7), row = 2 * line + (slot >> 2), chunk = slot & 3.  Instruction q of wavefront
+  // w covers tile rows 16 * (4 q + w) .. + 15 (A: q = 0..3, one 64-row block each; B: q < BN / 64).
+  constexpr int A_Q = BM / 64, B_Q = BN / 64;
+  const int dl = lane >> 3, dslot = (lane & 7) ^ dl;
+  const int rloc = 16 * wave + 2 * dl + (dslot >> 2), dch = dslot & 3;
+  int64_t aoff[A_Q];
 #pragma unroll
-  for (int i = 0; i < A_CH; ++i) {
-    const int c = tid + i * 256, r = c >> 2, ch = c & 3;
-    const int b = blk[r >> 6] >= 0 ? blk[r >> 6] : blk[0];
-    gA[i] = A + ((int64_t)b * kRowAlign + (r & 63)) * K + ch * 8;
-    oA[i] = lds_off(r, ch);
+  for (int q = 0; q < A_Q; ++q) {
+    const int b = blk[q] >= 0 ? blk[q] : blk[0];
+    aoff[q] = ((int64_t)b * kRowAlign + rloc) * K + dch * 8;
   }
+  const half_t *Wn0 = W + (int64_t)n0 * K;
+  const int boff = rloc * K + dch * 8;
+  // fragment byte offsets inside an operand for the two 16-deep steps; 32-row blocks are 2048 bytes apart
+  int f0[2], g0[2];
 #pragma unroll
-  for (int i = 0; i < B_CH; ++i) {
-    const int c = tid + i * 256, r = c >> 2, ch = c & 3;
-    gB[i] = W + (int64_t)(n0 + r) * K + ch * 8;
-    oB[i] = A_BYTES + lds_off(r, ch);
+  for (int ks = 0; ks < 2; ++ks) {
+    f0[ks] = lds_off(wm * 128 + l32, ks * 2 + lhalf);
+    g0[ks] = A_BYTES + lds_off(wn * WN + l32, ks * 2 + lhalf);
   }
-  // fragment addresses inside a stage, for k16-step 0 (step 1 = chunk + 2)
-  int fA[MB], fB[NB];
-#pragma unroll
-  for (int i = 0; i < MB; ++i) fA[i] = wm * 128 + i * 32 + l32;       // tile row
-#pragma unroll
-  for (int j = 0; j < NB; ++j) fB[j] = wn * WN + j * 32 + l32;
 
   f32x16 acc[MB][NB];
 #pragma unroll
@@ -130,53 +136,64 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   // consecutive tokens of one feature: activations as the A operand.
   const bool feature_major = (EPI == 0) && plane == 1;
 
+  typedef __attribute__((address_space(1))) const void gvoid;
+  typedef __attribute__((address_space(3))) void lvoid;
   auto main_loop = [&](auto fm) {
     constexpr bool FM = decltype(fm)::value;
-    uint4 ra[A_CH], rb[B_CH];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) ra[i] = *(const uint4 *)gA[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) rb[i] = *(const uint4 *)gB[i];
-#pragma unroll
-    for (int i = 0; i < A_CH; ++i) *(uint4 *)(smem + oA[i]) = ra[i];
-#pragma unroll
-    for (int i = 0; i < B_CH; ++i) *(uint4 *)(smem + oB[i]) = rb[i];
-    __syncthreads();
     const int nk = K / BK;
+    auto request = [&](int tile, int stage) {            // A_Q + B_Q DMA instructions per wavefront
+      const int kk = (tile < nk ? tile : nk - 1) * BK;
+#pragma unroll
+      for (int q = 0; q < A_Q; ++q)
+        __builtin_amdgcn_global_load_lds((gvoid *)(A + aoff[q] + kk), (lvoid *)(smem + stage * STAGE + (4 * q + wave) * 1024), 16, 0, 0);
+#pragma unroll
+      for (int q = 0; q < B_Q; ++q)
+        __builtin_amdgcn_global_load_lds((gvoid *)(Wn0 + (size_t)q * 64 * K + boff + kk),
+                                         (lvoid *)(smem + stage * STAGE + A_BYTES + (4 * q + wave) * 1024), 16, 0, 0);
+    };
+#define GEMM_MFMA(S, i, j)                                                                              \
+  acc[i][j] = FM ? __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[S][i], fb[S][j], acc[i][j], 0, 0, 0)         \
+                 : __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[S][j], fa[S][i], acc[i][j], 0, 0, 0)
+    request(0, 0);
+    request(1, 1);
+    f16x8 fa[2][MB], fb[2][NB];
+    int st = 0;
     for (int kt = 0; kt < nk; ++kt) {
-      const char *st = smem + (kt & 1) * STAGE;
-      char *nx = smem + ((kt & 1) ^ 1) * STAGE;
-      // prefetch the next k tile into registers (the last iteration re-reads its own tile: no branch)
-      const int kn = (kt + 1 < nk ? kt + 1 : kt) * BK;
+      // tile kt has landed for this wavefront once at most the requests of tile kt+1 are outstanding
+      if (A_Q + B_Q == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
+      else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+      __builtin_amdgcn_s_barrier();
+      const int st2 = st + 2 >= NSTAGE ? st + 2 - NSTAGE : st + 2;
+      request(kt + 2, st2);
+      const char *sp = smem + st * STAGE;
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) ra[i] = *(const uint4 *)(gA[i] + kn);
+      for (int i = 0; i < MB; ++i) fa[0][i] = *(const f16x8 *)(sp + f0[0] + i * 2048);
 #pragma unroll
-      for (int i = 0; i < B_CH; ++i) rb[i] = *(const uint4 *)(gB[i] + kn);
-      // keep the loads up here: left alone, the scheduler sinks them to just before the LDS writes
-      // and the whole global latency lands on the critical path
+      for (int j = 0; j < NB; ++j) fb[0][j] = *(const f16x8 *)(sp + g0[0] + j * 2048);
+      __builtin_amdgcn_sched_barrier(0);
+      GEMM_MFMA(0, 0, 0);
+      GEMM_MFMA(0, 1, 0);
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-      for (int ks = 0; ks < BK / 16; ++ks) {
-        f16x8 fa[MB], fb[NB];
+      for (int i = 0; i < MB; ++i) fa[1][i] = *(const f16x8 *)(sp + f0[1] + i * 2048);
 #pragma unroll
-        for (int i = 0; i < MB; ++i) fa[i] = *(const f16x8 *)(st + lds_off(fA[i], ks * 2 + lhalf));
-#pragma unroll
-        for (int j = 0; j < NB; ++j) fb[j] = *(const f16x8 *)(st + A_BYTES + lds_off(fB[j], ks * 2 + lhalf));
-#pragma unroll
-        for (int i = 0; i < MB; ++i)
-#pragma unroll
-          for (int j = 0; j < NB; ++j)
-            acc[i][j] = FM ? __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[i], fb[j], acc[i][j], 0, 0, 0)
-                           : __builtin_amdgcn_mfma_f32_32x32x16_f16(fb[j], fa[i], acc[i][j], 0, 0, 0);
-      }
+      for (int j = 0; j < NB; ++j) fb[1][j] = *(const f16x8 *)(sp + g0[1] + j * 2048);
       __builtin_amdgcn_sched_barrier(0);
-      // the other stage was last read before the previous barrier: safe to overwrite
+      GEMM_MFMA(0, 2, 0);
+      GEMM_MFMA(0, 3, 0);
 #pragma unroll
-      for (int i = 0; i < A_CH; ++i) *(uint4 *)(nx + oA[i]) = ra[i];
+      for (int j = 1; j < NB; ++j)
 #pragma unroll
-      for (int i = 0; i < B_CH; ++i) *(uint4 *)(nx + oB[i]) = rb[i];
-      __syncthreads();
+        for (int i = 0; i < MB; ++i) GEMM_MFMA(0, i, j);
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int i = 0; i < MB; ++i) GEMM_MFMA(1, i, j);
+      __builtin_amdgcn_sched_barrier(0);
+      st = st + 1 >= NSTAGE ? 0 : st + 1;
     }
+#undef GEMM_MFMA
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the clamped tail requests must not outlive the workgroup's LDS
   };
   if (feature_major) main_loop(std::true_type{});
   else main_loop(std::false_type{});
