@@ -8,16 +8,14 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflame_gr.so")
-SOURCES = ["api.cpp", "plan.cpp", "misc.hip", "kernels_f32.hip", "gemm_mfma.hip", "gemm256_mfma.hip", "attn_mfma.hip", "k3_mfma.hip"]
+SOURCES = ["api.cpp", "plan.cpp", "misc.hip", "kernels_f32.hip", "gemm_mfma.hip", "attn_mfma.hip", "k3_mfma.hip"]
 # packed fp32 VALU instructions are switched off on purpose (build flags)
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          ]
 # keep MFMA accumulators in ordinary VGPRs: the epilogues and the attention SiLU read them with VALU
-# instructions, and accumulation registers would need a copy each way.  Not for the 256x256 GEMM, whose
-# 256 accumulators per lane only fit in the accumulation half of the register file.
+# instructions, and accumulation registers would need a copy each way
 VGPR_FORM = ["-mllvm", "-amdgpu-mfma-vgpr-form"]
-NO_VGPR_FORM = {"gemm256_mfma.hip"}
 
 
 def build(verbose: bool = True, jobs: int = 6) -> str:
@@ -29,8 +27,7 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     for src in SOURCES:
         obj = os.path.join(objdir, src + ".o")
         objs.append(obj)
-        extra = [] if src in NO_VGPR_FORM else VGPR_FORM
-        cmd = [hipcc, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [hipcc, *FLAGS, *VGPR_FORM, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
         procs.append((src, cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         while sum(p.poll() is None for _, _, p in procs) >= jobs:
             procs[0][2].wait()

@@ -373,10 +373,10 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
     Timed t(h, KIND_BIAS, s0);
     if (h->cfg.dtype == FLAME_GR_BF16) {
       // the caller owns the weights and may have changed them: convert on every forward
-      const int64_t dd = (int64_t)h->sh.d * h->sh.d;
-      launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dd, s0);
-      if (k3_fused_supported(h->sh.d)) launch_pack_w2(w->w2, h->W2p, h->sh.d, h->sh.n_layers, s0);
-      else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dd, s0);
+      const int dm = h->sh.d;
+      launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dm, dm, true, s0);
+      if (k3_fused_supported(dm)) launch_pack_w2(w->w2, h->W2p, dm, h->sh.n_layers, s0);
+      else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dm, dm, true, s0);
     }
     launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
                        h->cfg.dtype == FLAME_GR_BF16 ? 1.4426950408889634f : 1.0f, s0);

@@ -56,6 +56,15 @@ __device__ __forceinline__ float silu_log2_domain(float y) {
   return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-y));
 }
 
+// "k-tile blocked" layout of the fp16 GEMM operands (the activation copy Xh and the converted weight
+// matrices): inside every block of 64 rows the 32-wide k slices follow one another,
+// [row / 64][k / 32][row % 64][k % 32], so the 64 rows x 32 k slice a GEMM k-tile needs is 4 KB of
+// contiguous memory and is fetched as whole 128-byte lines.  (Row-major rows of d elements would hand
+// the L1 two 64-byte requests per line, and the number of requests in flight is what bounds it.)
+__device__ __forceinline__ int64_t blocked_index(int64_t row, int k, int K) {
+  return (row >> 6) * 64 * K + (int64_t)(k >> 5) * 2048 + (row & 63) * 32 + (k & 31);
+}
+
 // Number of history keys a query row may look at (the mask of the single-user-multiple-items
 // scoring pass): a history row at index q sees keys 0..q, a candidate row sees all L.
 __device__ __forceinline__ int visible_history(int is_cand, int q_index, int L) {

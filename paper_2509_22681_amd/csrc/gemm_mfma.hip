@@ -37,19 +37,29 @@ constexpr int RB = BM / kRowAlign;      // 64-row blocks per row tile
 
 struct PlaneSel { int id[4]; int n; };
 
-// byte offset of 16-byte chunk c (0..3) of tile row `row` inside one LDS stage
+// byte offset of 16-byte chunk c (0..3) of tile row `row` inside one LDS operand.  Two 64-byte rows share
+// a 128-byte line; the slot inside the line is XORed with a key made of row bits 1, 2 ^ 4 and 3.  Both
+// fragment row orders used below (identity: row bits 0..2 vary over 8 consecutive lanes; sigma32: row
+// bits 0, 1, 4 vary) then send 8 consecutive lanes to 8 different slots.
+__device__ __forceinline__ int lds_key(int line) { return (line & 5) | ((line ^ (line >> 2)) & 2); }
 __device__ __forceinline__ int lds_off(int row, int c) {
   const int line = row >> 1;
   const int slot = ((row & 1) << 2) | c;
-  return line * 128 + ((slot ^ (line & 7)) << 4);
+  return line * 128 + ((slot ^ lds_key(line)) << 4);
 }
+// Row order of the MFMA A operand.  Accumulator element e of lane (l32, lhalf) belongs to A-operand
+// row 8*(e/4) + 4*lhalf + e%4.  Feeding tile row sigma32(m) = 16*bit2(m) + 4*(m/8) + m%4 into A-operand
+// row m turns that into tile row 16*lhalf + e: a lane then owns 16 consecutive outputs (features of
+// one token, or tokens of one feature for the feature-major plane) and stores them as two 16-byte
+// words, two lanes covering a contiguous 64 bytes.
+__device__ __forceinline__ int sigma32(int m) { return ((m & 4) << 2) | ((m >> 3) << 2) | (m & 3); }
 
 template <int BN, int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     const half_t *__restrict__ A, const half_t *__restrict__ W, const bf16_t *__restrict__ bias,
     half_t *__restrict__ planes, float *__restrict__ X, half_t *__restrict__ Xh,
     const int32_t *__restrict__ blk_list, int blk_first, int n_blk, int n_row_tiles, int n_col_tiles, int K, int d,
-    int64_t ws_rows, PlaneSel sel, float alpha) {
+    int64_t ws_rows, PlaneSel sel, float alpha, bool a_blocked) {
   constexpr int WN = BN / 2;            // wavefront patch: 128 rows x WN columns
   constexpr int MB = 4;                 // 32-row MFMA blocks per wavefront
   constexpr int NB = WN / 32;           // 32-column MFMA blocks per wavefront
@@ -101,27 +111,22 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 
   // LDS-DMA sources.  One instruction of a wavefront fills 1 KB = 8 lines = 16 tile rows; lane p owns
   // physical slot p & 7 of line p >> 3 and must fetch the chunk the swizzle maps there:
-  // slot = (p & 7) ^ (line & 7), row = 2 * line + (slot >> 2), chunk = slot & 3.  Instruction q of wavefront
+  // slot = (p & 7) ^ key(line), row = 2 * line + (slot >> 2), chunk = slot & 3.  Instruction q of wavefront
   // w covers tile rows 16 * (4 q + w) .. + 15 (A: q = 0..3, one 64-row block each; B: q < BN / 64).
   constexpr int A_Q = BM / 64, B_Q = BN / 64;
-  const int dl = lane >> 3, dslot = (lane & 7) ^ dl;
+  const int dl = lane >> 3, dslot = (lane & 7) ^ lds_key(8 * wave + dl);
   const int rloc = 16 * wave + 2 * dl + (dslot >> 2), dch = dslot & 3;
+  // W is k-tile blocked (64 rows x 32 k = 2048 contiguous elements, whole 128-byte lines per request);
+  // A is blocked too when it is the activation copy Xh, row-major when it is G.
   int64_t aoff[A_Q];
 #pragma unroll
   for (int q = 0; q < A_Q; ++q) {
     const int b = blk[q] >= 0 ? blk[q] : blk[0];
-    aoff[q] = ((int64_t)b * kRowAlign + rloc) * K + dch * 8;
+    aoff[q] = a_blocked ? (int64_t)b * kRowAlign * K + rloc * 32 + dch * 8 : ((int64_t)b * kRowAlign + rloc) * K + dch * 8;
   }
-  const half_t *Wn0 = W + (int64_t)n0 * K;
-  const int boff = rloc * K + dch * 8;
-  // fragment byte offsets inside an operand for the two 16-deep steps; 32-row blocks are 2048 bytes apart
-  int f0[2], g0[2];
-#pragma unroll
-  for (int ks = 0; ks < 2; ++ks) {
-    f0[ks] = lds_off(wm * 128 + l32, ks * 2 + lhalf);
-    g0[ks] = A_BYTES + lds_off(wn * WN + l32, ks * 2 + lhalf);
-  }
-
+  const int a_kstep = a_blocked ? 64 * BK : BK;
+  const half_t *Wn0 = W + (int64_t)n0 * K;            // n0 % 64 == 0: a block boundary
+  const int boff = rloc * 32 + dch * 8;
   f32x16 acc[MB][NB];
 #pragma unroll
   for (int i = 0; i < MB; ++i)
@@ -135,6 +140,17 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   // plane is stored feature-major for the attention kernel (V^T is its A operand) and wants 4
   // consecutive tokens of one feature: activations as the A operand.
   const bool feature_major = (EPI == 0) && plane == 1;
+  // fragment byte offsets inside a stage for the two 16-deep steps (32-row blocks are 2048 bytes apart);
+  // the operand that plays A is read in sigma32 row order
+  int f0[2], g0[2];
+  {
+    const int ra = feature_major ? sigma32(l32) : l32, rb = feature_major ? l32 : sigma32(l32);
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks) {
+      f0[ks] = lds_off(wm * 128 + ra, ks * 2 + lhalf);
+      g0[ks] = A_BYTES + lds_off(wn * WN + rb, ks * 2 + lhalf);
+    }
+  }
 
   typedef __attribute__((address_space(1))) const void gvoid;
   typedef __attribute__((address_space(3))) void lvoid;
@@ -142,13 +158,13 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     constexpr bool FM = decltype(fm)::value;
     const int nk = K / BK;
     auto request = [&](int tile, int stage) {            // A_Q + B_Q DMA instructions per wavefront
-      const int kk = (tile < nk ? tile : nk - 1) * BK;
+      const int kt_ = tile < nk ? tile : nk - 1;
 #pragma unroll
       for (int q = 0; q < A_Q; ++q)
-        __builtin_amdgcn_global_load_lds((gvoid *)(A + aoff[q] + kk), (lvoid *)(smem + stage * STAGE + (4 * q + wave) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gvoid *)(A + aoff[q] + kt_ * a_kstep), (lvoid *)(smem + stage * STAGE + (4 * q + wave) * 1024), 16, 0, 0);
 #pragma unroll
       for (int q = 0; q < B_Q; ++q)
-        __builtin_amdgcn_global_load_lds((gvoid *)(Wn0 + (size_t)q * 64 * K + boff + kk),
+        __builtin_amdgcn_global_load_lds((gvoid *)(Wn0 + (size_t)q * 64 * K + boff + kt_ * (64 * BK)),
                                          (lvoid *)(smem + stage * STAGE + A_BYTES + (4 * q + wave) * 1024), 16, 0, 0);
     };
 #define GEMM_MFMA(S, i, j)                                                                              \
@@ -198,8 +214,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   if (feature_major) main_loop(std::true_type{});
   else main_loop(std::false_type{});
 
-  // Epilogue.  Accumulator element e of a 32x32 block sits at (A-operand row 8*(e/4) + 4*(lane/32) + e%4,
-  // B-operand row lane%32): four consecutive e are four consecutive A-operand rows.
+  // Epilogue.  With the sigma32 row order accumulator element e of a 32x32 block sits at (A-operand
+  // tile row 16*lhalf + e, B-operand tile row l32).
 #pragma unroll
   for (int i = 0; i < MB; ++i) {
     const int tr = wm * 128 + i * 32;                 // first tile row of this block: inside one 64-row block
@@ -212,48 +228,51 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
       if (EPI == 0) {
         half_t *P = planes + (int64_t)plane * ws_rows * d;
         if (!feature_major) {
-          // lane: token row_base + l32; elements: features nb0 + 8g + 4*lhalf + 0..3
+          // lane: token row_base + l32; elements: features nb0 + 16*lhalf + 0..15
           // Q leaves this kernel multiplied by alpha * log2(e): the attention logits are then
           // directly the arguments of exp2 (V carries the inverse factor ln 2).
           const float sc = plane == 2 ? alpha * kLog2e : 1.0f;
-          half_t *prow = P + (row_base + l32) * d + n_in_plane + nb0 + 4 * lhalf;
-          const bf16_t *brow = bias + plane * d + n_in_plane + nb0 + 4 * lhalf;
+          half_t *prow = P + (row_base + l32) * d + n_in_plane + nb0 + 16 * lhalf;
+          const bf16_t *brow = bias + plane * d + n_in_plane + nb0 + 16 * lhalf;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            const bf16x4 bv = *(const bf16x4 *)(brow + 8 * g);
-            f16x4 o;
+          for (int g = 0; g < 2; ++g) {
+            const bf16x8 bv = *(const bf16x8 *)(brow + 8 * g);
+            f16x8 o;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][4 * g + q] + (float)bv[q]) * sc);
-            *(f16x4 *)(prow + 8 * g) = o;
+            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + (float)bv[q]) * sc);
+            *(f16x8 *)(prow + 8 * g) = o;
           }
         } else {
-          // lane: feature n_in_plane + nb0 + l32; elements: tokens row_base + 8g + 4*lhalf + 0..3
+          // lane: feature n_in_plane + nb0 + l32; elements: tokens row_base + 16*lhalf + 0..15
           const int n = n_in_plane + nb0 + l32;
           const float bv = to_f32(bias[plane * d + n]);
-          half_t *pcol = P + (int64_t)n * ws_rows + row_base + 4 * lhalf;
+          half_t *pcol = P + (int64_t)n * ws_rows + row_base + 16 * lhalf;
 #pragma unroll
-          for (int g = 0; g < 4; ++g) {
-            f16x4 o;
+          for (int g = 0; g < 2; ++g) {
+            f16x8 o;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][4 * g + q] + bv) * kLn2);
-            *(f16x4 *)(pcol + 8 * g) = o;
+            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + bv) * kLn2);
+            *(f16x8 *)(pcol + 8 * g) = o;
           }
         }
       } else {
         const int64_t m = row_base + l32;
-        const int nn = n0 + nb0 + 4 * lhalf;
+        const int nn = n0 + nb0 + 16 * lhalf;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          const bf16x4 bv = *(const bf16x4 *)(bias + nn + 8 * g);
-          f32x4 x = *(const f32x4 *)(X + m * d + nn + 8 * g);
-          f16x4 o;
+        for (int g = 0; g < 2; ++g) {
+          const bf16x8 bv = *(const bf16x8 *)(bias + nn + 8 * g);
+          f32x4 x0 = *(const f32x4 *)(X + m * d + nn + 8 * g), x1 = *(const f32x4 *)(X + m * d + nn + 8 * g + 4);
+          f16x8 o;
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
-            x[q] += acc[i][j][4 * g + q] + (float)bv[q];
-            o[q] = to_f16_sat(x[q]);
+            x0[q] += acc[i][j][8 * g + q] + (float)bv[q];
+            x1[q] += acc[i][j][8 * g + 4 + q] + (float)bv[4 + q];
+            o[q] = to_f16_sat(x0[q]);
+            o[4 + q] = to_f16_sat(x1[q]);
           }
-          *(f32x4 *)(X + m * d + nn + 8 * g) = x;
-          *(f16x4 *)(Xh + m * d + nn + 8 * g) = o;
+          *(f32x4 *)(X + m * d + nn + 8 * g) = x0;
+          *(f32x4 *)(X + m * d + nn + 8 * g + 4) = x1;
+          *(f16x8 *)(Xh + blocked_index(m, nn + 8 * g, d)) = o;
         }
       }
     }
@@ -265,10 +284,6 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
                       int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s) {
   if (n_blk <= 0 || !(plane_mask & 0xF)) return;
-  if (uvqk256_supported(sh.d)) {
-    launch_uvqk256(Xh, W1h, b1, planes, blk_list, n_blk, blk_first, plane_mask, sh, s);
-    return;
-  }
   PlaneSel sel{};
   for (int p = 0; p < 4; ++p)
     if (plane_mask & (1 << p)) sel.id[sel.n++] = p;
@@ -277,12 +292,12 @@ void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *pla
     const int col_tiles = sel.n * (sh.d / 128);
     gemm_mfma_kernel<128, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
                                                                    (half_t *)planes, nullptr, nullptr, blk_list, blk_first, n_blk,
-                                                                   row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
+                                                                   row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha, true);
   } else {
     const int col_tiles = sel.n * (sh.d / 64);
     gemm_mfma_kernel<64, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
                                                                   (half_t *)planes, nullptr, nullptr, blk_list, blk_first, n_blk,
-                                                                  row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha);
+                                                                  row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha, true);
   }
 }
 
@@ -295,12 +310,12 @@ void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *
     const int col_tiles = sh.d / 128;
     gemm_mfma_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X,
                                                                    (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
-                                                                   sh.d, sh.d, sh.ws_rows, sel, 1.0f);
+                                                                   sh.d, sh.d, sh.ws_rows, sel, 1.0f, false);
   } else {
     const int col_tiles = sh.d / 64;
     gemm_mfma_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X,
                                                                   (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
-                                                                  sh.d, sh.d, sh.ws_rows, sel, 1.0f);
+                                                                  sh.d, sh.d, sh.ws_rows, sel, 1.0f, false);
   }
 }
 

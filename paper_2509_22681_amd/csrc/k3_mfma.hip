@@ -193,7 +193,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
         o[q] = to_f16_sat(x[q]);
       }
       *(f32x4 *)(X + m * d + nn + 8 * gq) = x;
-      *(f16x4 *)(Xh + m * d + nn + 8 * gq) = o;
+      *(f16x4 *)(Xh + blocked_index(m, nn + 8 * gq, d)) = o;
     }
   }
 }

@@ -15,11 +15,12 @@ struct Shape {
 };
 
 // ---- shared small kernels (misc.hip) --------------------------------------------------------
-// X[rows of blocks) <- embeddings (fp32 copy, and an fp16 copy Xh in the MFMA path); padding rows zeroed.
+// X[rows of blocks) <- embeddings (fp32 copy, and a k-tile blocked fp16 copy Xh in the MFMA path); padding rows zeroed.
 void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
                      const void *cand, float *X, void *Xh, int d, hipStream_t s);
-// out[i] = fp16(in[i]) for n bf16 elements (n % 8 == 0)
-void launch_bf16_to_f16(const void *in, void *out, int64_t n, hipStream_t s);
+// fp16 copy of a bf16 matrix of `rows` rows of K elements (K % 8 == 0); blocked: written in the k-tile
+// blocked layout of the GEMM operands (rows % 64 == 0, K % 32 == 0), else element for element
+void launch_bf16_to_f16(const void *in, void *out, int64_t rows, int K, bool blocked, hipStream_t s);
 // bias[lh][delta] = scale * rab[lh][bucket_tab[delta]] for all layers and heads (scale = log2(e) in
 // the MFMA path, whose logits live in the exp2 domain; 1 in the fp32 path).
 void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh,
@@ -48,6 +49,7 @@ void launch_outproj_f32(const float *G, const float *W2, const float *b2, float 
 
 // ---- bf16-storage path (gemm_mfma.hip, attn_mfma.hip): fp16 MFMA kernels, fp32 accumulation --------
 // Activations (Xh, planes, O, G) and the converted matrices W1h/W2h are fp16; biases stay bf16.
+// Xh, W1h and W2h are k-tile blocked (device_common.h: blocked_index); planes, O and G are row-major.
 // U, Q, K planes row-major [row][d]; the V plane is written transposed, Vt[n][row] (row stride ws_rows).
 // plane_mask bit p set = compute plane p (U=1, V=2, Q=4, K=8).
 void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
@@ -57,12 +59,6 @@ void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const A
 // X[row] += G W2h^T + b2, and Xh[row] = fp16(X[row])
 void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
-
-// K1 on 256 x 256 tiles for d % 256 == 0 (gemm256_mfma.hip); same contract as launch_uvqk_bf16, which
-// dispatches to it.
-bool uvqk256_supported(int d);
-void launch_uvqk256(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list, int n_blk,
-                    int blk_first, int plane_mask, const Shape &sh, hipStream_t s);
 
 // K3 fused (k3_mfma.hip): LayerNorm * U gate + output projection + residual in one kernel, for
 // d in {128, 256, 512}; W2p is the fragment-major packed fp16 copy of W2 written by launch_pack_w2.

@@ -9,6 +9,7 @@ namespace flame {
 // Assembly: the token matrix of a request is its history rows followed by its candidate rows
 // (Section 2.1: candidates are appended after the behaviour sequence).  One workgroup per 64-row
 // block of the padded workspace; rows past n_valid are zero so that they stay finite downstream.
+// X is row-major fp32; the fp16 copy Xh (MFMA path) is k-tile blocked.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restrict__ blocks, int blk_begin,
@@ -24,7 +25,7 @@ __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restric
     float v = 0.f;
     if (i < nv) v = to_f32(src[(int64_t)rb.src_row * d + i]);
     X[dst0 + i] = v;
-    if (Xh) Xh[dst0 + i] = to_f16_sat(v);
+    if (Xh) Xh[blocked_index((int64_t)b * kRowAlign + i / d, i % d, d)] = to_f16_sat(v);
   }
 }
 
@@ -60,21 +61,23 @@ void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias
 // case) on the scores, fp16's 2^-12 keeps them ten times closer; weights of magnitude >= 2^-14 are
 // represented exactly either way.
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const bf16_t *__restrict__ in, half_t *__restrict__ out, int64_t n8) {
+__global__ __launch_bounds__(256) void bf16_to_f16_kernel(const bf16_t *__restrict__ in, half_t *__restrict__ out, int64_t n8,
+                                                          int K, bool blocked) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
     const bf16x8 v = ((const bf16x8 *)in)[i];
     f16x8 o;
 #pragma unroll
     for (int k = 0; k < 8; ++k) o[k] = to_f16_sat((float)v[k]);
-    ((f16x8 *)out)[i] = o;
+    const int64_t e = i * 8;                              // 8 consecutive k of one row stay together
+    *(f16x8 *)(out + (blocked ? blocked_index(e / K, (int)(e % K), K) : e)) = o;
   }
 }
 
-void launch_bf16_to_f16(const void *in, void *out, int64_t n, hipStream_t s) {
-  if (n <= 0) return;
-  const int64_t n8 = n / 8;   // every converted matrix has a multiple of 8 elements (d % 64 == 0)
+void launch_bf16_to_f16(const void *in, void *out, int64_t rows, int K, bool blocked, hipStream_t s) {
+  const int64_t n8 = rows * K / 8;   // K % 64 == 0 in the MFMA path
+  if (n8 <= 0) return;
   int grid = (int)((n8 + 255) / 256 > 2048 ? 2048 : (n8 + 255) / 256);
-  bf16_to_f16_kernel<<<grid, 256, 0, s>>>((const bf16_t *)in, (half_t *)out, n8);
+  bf16_to_f16_kernel<<<grid, 256, 0, s>>>((const bf16_t *)in, (half_t *)out, n8, K, blocked);
 }
 
 // ---------------------------------------------------------------------------------------------
