@@ -216,48 +216,89 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 
   // Epilogue.  With the sigma32 row order accumulator element e of a 32x32 block sits at (A-operand
   // tile row 16*lhalf + e, B-operand tile row l32).
+  const int b0 = wm ? blk[2] : blk[0], b1 = wm ? blk[3] : blk[1];    // the two 64-row blocks of this wavefront's 128 rows
+  if (EPI == 0) {
+    // Only two lanes share an output row in the accumulator layout, so direct stores would reach the
+    // L2 as 32-byte pieces, and the write path is then bound by the number of requests.  The
+    // wavefront's patch goes through LDS instead (the operand ring is free by now; each wavefront
+    // owns a private slice of it, chunks XOR-swizzled by row) and leaves as 16 bytes per lane with
+    // whole 128-byte lines per output row.
+    __builtin_amdgcn_s_barrier();                     // every wavefront has finished reading the ring
+    char *pb = smem + wave * (128 * WN * 2);
+    half_t *P = planes + (int64_t)plane * ws_rows * d;
+    if (!feature_major) {
+      // patch[128 tokens][WN features]; lane holds token 32i + l32, features 32j + 16*lhalf + 0..15.
+      // Q leaves this kernel multiplied by alpha * log2(e): the attention logits are then
+      // directly the arguments of exp2 (V carries the inverse factor ln 2).
+      constexpr int CPR = WN / 8;                     // 16-byte chunks per patch row
+      const float sc = plane == 2 ? alpha * kLog2e : 1.0f;
+      const bf16_t *brow = bias + plane * d + n_in_plane + wn * WN + 16 * lhalf;
 #pragma unroll
-  for (int i = 0; i < MB; ++i) {
-    const int tr = wm * 128 + i * 32;                 // first tile row of this block: inside one 64-row block
-    const int rblk = blk[tr >> 6];
-    if (rblk < 0) continue;
-    const int64_t row_base = (int64_t)rblk * kRowAlign + (tr & 63);
+      for (int j = 0; j < NB; ++j) {
+        const bf16x8 bv0 = *(const bf16x8 *)(brow + 32 * j), bv1 = *(const bf16x8 *)(brow + 32 * j + 8);
 #pragma unroll
-    for (int j = 0; j < NB; ++j) {
-      const int nb0 = wn * WN + j * 32;               // column offset of this block inside the tile
-      if (EPI == 0) {
-        half_t *P = planes + (int64_t)plane * ws_rows * d;
-        if (!feature_major) {
-          // lane: token row_base + l32; elements: features nb0 + 16*lhalf + 0..15
-          // Q leaves this kernel multiplied by alpha * log2(e): the attention logits are then
-          // directly the arguments of exp2 (V carries the inverse factor ln 2).
-          const float sc = plane == 2 ? alpha * kLog2e : 1.0f;
-          half_t *prow = P + (row_base + l32) * d + n_in_plane + nb0 + 16 * lhalf;
-          const bf16_t *brow = bias + plane * d + n_in_plane + nb0 + 16 * lhalf;
+        for (int i = 0; i < MB; ++i) {
+          const int row = 32 * i + l32;
 #pragma unroll
           for (int g = 0; g < 2; ++g) {
-            const bf16x8 bv = *(const bf16x8 *)(brow + 8 * g);
             f16x8 o;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + (float)bv[q]) * sc);
-            *(f16x8 *)(prow + 8 * g) = o;
+            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + (float)(g ? bv1[q] : bv0[q])) * sc);
+            const int c = 4 * j + 2 * lhalf + g;
+            *(f16x8 *)(pb + row * (WN * 2) + ((c ^ (row & (CPR - 1))) << 4)) = o;
           }
-        } else {
-          // lane: feature n_in_plane + nb0 + l32; elements: tokens row_base + 16*lhalf + 0..15
-          const int n = n_in_plane + nb0 + l32;
-          const float bv = to_f32(bias[plane * d + n]);
-          half_t *pcol = P + (int64_t)n * ws_rows + row_base + 16 * lhalf;
+        }
+      }
+      constexpr int RPI = 64 / CPR;                   // patch rows per store instruction
+      const int rl = lane / CPR, c = lane % CPR;
+      half_t *pcol = P + n_in_plane + wn * WN + c * 8;
+#pragma unroll
+      for (int it = 0; it < 128 / RPI; ++it) {
+        const int row = it * RPI + rl;
+        const f16x8 v = *(const f16x8 *)(pb + row * (WN * 2) + ((c ^ (row & (CPR - 1))) << 4));
+        const int rblk = row >= 64 ? b1 : b0;
+        if (rblk >= 0) *(f16x8 *)(pcol + ((int64_t)rblk * kRowAlign + (row & 63)) * d) = v;
+      }
+    } else {
+      // patch[WN features][128 tokens]; lane holds feature 32j + l32, tokens 32i + 16*lhalf + 0..15
+      const bf16_t *bcol = bias + plane * d + n_in_plane + wn * WN + l32;
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const float bv = to_f32(bcol[32 * j]);
+        const int fr = 32 * j + l32;
+#pragma unroll
+        for (int i = 0; i < MB; ++i) {
 #pragma unroll
           for (int g = 0; g < 2; ++g) {
             f16x8 o;
 #pragma unroll
             for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + bv) * kLn2);
-            *(f16x8 *)(pcol + 8 * g) = o;
+            const int c = 4 * i + 2 * lhalf + g;
+            *(f16x8 *)(pb + fr * 256 + (((c & 8) | ((c ^ fr) & 7)) << 4)) = o;
           }
         }
-      } else {
-        const int64_t m = row_base + l32;
-        const int nn = n0 + nb0 + 16 * lhalf;
+      }
+      const int rl = lane >> 4, c = lane & 15;
+      const int rblk = c >= 8 ? b1 : b0;
+      half_t *prow = P + (int64_t)(n_in_plane + wn * WN) * ws_rows + (int64_t)rblk * kRowAlign + (c & 7) * 8;
+      if (rblk >= 0) {
+#pragma unroll
+        for (int it = 0; it < WN / 4; ++it) {
+          const int fr = it * 4 + rl;
+          const f16x8 v = *(const f16x8 *)(pb + fr * 256 + (((c & 8) | ((c ^ fr) & 7)) << 4));
+          *(f16x8 *)(prow + (int64_t)fr * ws_rows) = v;
+        }
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < MB; ++i) {
+      const int rblk = i >= 2 ? b1 : b0;              // 32-row block i lies inside one 64-row block
+      if (rblk < 0) continue;
+      const int64_t m = (int64_t)rblk * kRowAlign + (i & 1) * 32 + l32;
+#pragma unroll
+      for (int j = 0; j < NB; ++j) {
+        const int nn = n0 + wn * WN + j * 32 + 16 * lhalf;
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
           const bf16x8 bv = *(const bf16x8 *)(bias + nn + 8 * g);
