@@ -12,7 +12,8 @@
 //   * phase 2: each wavefront owns d/4 output features; the W2 operand comes straight from L2 in a
 //     fragment-major packed layout (one coalesced 1 KB read per MFMA operand, prepared once per forward
 //     by pack_w2_kernel), so LDS holds only the activations and two workgroups fit on a CU;
-//   * phase 3: residual add in fp32, fp16 copy for the next layer's projection.
+//   * phase 3: residual add in fp32 and fp16 copy for the next layer's projection, after a transposition
+//     of the accumulators through LDS so that X is read and written in whole lines.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -166,34 +167,55 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
   }
 
-  // ---- phase 3: lane = token 32*i + l32; elements = features 32*(wave*NBW + j) + 8g + 4*lhalf + 0..3.
-  // The residual rows of the next (i, j) block are requested before the current block is finished.
-  f32x4 xr[2][4];
-  auto load_x = [&](int set, int i, int j) {
-    const int64_t m = row0 + 32 * i + l32;
-    const int nn = 32 * (wave * NBW + j) + 4 * lhalf;
+  // ---- phase 3: residual.  In the accumulators a lane holds one token and scattered features, and only
+  // two lanes share a row, so direct X accesses would be 32-byte pieces (the memory path is bound by the
+  // number of requests, not only by bytes).  Each wavefront passes its 32 x (32 NBW) patch through a
+  // private slice of the now free LDS (16-byte chunks XOR-swizzled by row) and then walks it row by
+  // row: 16 bytes per lane, whole lines of X, 64-byte runs of the blocked fp16 copy.
+  __syncthreads();                                  // every wavefront has finished reading G
+  constexpr int WF = 32 * NBW;                      // features per wavefront
+  constexpr int CPR = WF / 4;                       // 16-byte fp32 chunks per patch row
+  constexpr int RPI = 64 / CPR;                     // patch rows per instruction
+  constexpr int NIT = 32 / RPI;
+  char *pb = smem + wave * (32 * WF * 4);
+  const int rl = lane / CPR, cc = lane % CPR;
+  const int n = wave * WF + 4 * cc;                 // this lane's 4 features in the read-out
+  f32x4 bvf;
+  {
+    const bf16x4 bv = *(const bf16x4 *)(b2 + n);
 #pragma unroll
-    for (int gq = 0; gq < 4; ++gq) xr[set][gq] = *(const f32x4 *)(X + m * d + nn + 8 * gq);
-  };
-  load_x(0, 0, 0);
+    for (int q = 0; q < 4; ++q) bvf[q] = (float)bv[q];
+  }
+  constexpr int XB = NIT < 8 ? NIT : 8;             // residual rows requested ahead
+  f32x4 xr[XB];
 #pragma unroll
-  for (int ij = 0; ij < 2 * NBW; ++ij) {
-    const int i = ij / NBW, j = ij % NBW, set = ij & 1;
-    if (ij + 1 < 2 * NBW) load_x(set ^ 1, (ij + 1) / NBW, (ij + 1) % NBW);
-    const int64_t m = row0 + 32 * i + l32;
-    const int nn = 32 * (wave * NBW + j) + 4 * lhalf;
+  for (int i = 0; i < 2; ++i) {
+    float *xrow = X + (row0 + 32 * i + rl) * d + n;
 #pragma unroll
-    for (int gq = 0; gq < 4; ++gq) {
-      const bf16x4 bv = *(const bf16x4 *)(b2 + nn + 8 * gq);
-      f32x4 x = xr[set][gq];
+    for (int t = 0; t < XB; ++t) xr[t] = *(const f32x4 *)(xrow + (int64_t)t * RPI * d);
+#pragma unroll
+    for (int j = 0; j < NBW; ++j)
+#pragma unroll
+      for (int gq = 0; gq < 4; ++gq) {
+        const int c = 8 * j + 2 * gq + lhalf;
+        const f32x4 v = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
+        *(f32x4 *)(pb + l32 * (WF * 4) + ((c ^ (l32 & 7)) << 4)) = v;
+      }
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+      const int row = it * RPI + rl;
+      const f32x4 v = *(const f32x4 *)(pb + row * (WF * 4) + ((cc ^ (row & 7)) << 4));
+      f32x4 x = xr[it % XB];
+      if (it + XB < NIT) xr[it % XB] = *(const f32x4 *)(xrow + (int64_t)(it + XB) * RPI * d);
       f16x4 o;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        x[q] += acc[i][j][4 * gq + q] + (float)bv[q];
+        x[q] += v[q] + bvf[q];
         o[q] = to_f16_sat(x[q]);
       }
-      *(f32x4 *)(X + m * d + nn + 8 * gq) = x;
-      *(f16x4 *)(Xh + blocked_index(m, nn + 8 * gq, d)) = o;
+      const int64_t m = row0 + 32 * i + row;
+      *(f32x4 *)(X + m * d + n) = x;
+      *(f16x4 *)(Xh + blocked_index(m, n, d)) = o;
     }
   }
 }
