@@ -82,9 +82,19 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   constexpr int KS = DH / 16;          // k-steps of the Q K^T product
   constexpr int DB = DH / 32;          // 32-row blocks of O^T
   constexpr int NCH = DH / 32;         // 16-byte chunks per thread for one K (or V^T) tile
-  __shared__ __attribute__((aligned(16))) half_t sK[2][KT][DH + PAD];
-  __shared__ __attribute__((aligned(16))) half_t sVt[2][DH][KT + PAD];
-  __shared__ float sBias[2][BW];
+  struct Tiles {
+    half_t sK[2][KT][DH + PAD];
+    half_t sVt[2][DH][KT + PAD];
+    float sBias[2][BW];
+  };
+  // the output patches of the four wavefronts reuse the tile buffers once the key loop is over
+  __shared__ __attribute__((aligned(16))) union {
+    Tiles t;
+    char patch[4][64 * DH * 2];
+  } lds;
+  auto &sK = lds.t.sK;
+  auto &sVt = lds.t.sVt;
+  auto &sBias = lds.t.sBias;
 
   const int head = blockIdx.x % H;
   const AttnItem it = items[blockIdx.x / H];
@@ -330,20 +340,38 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
     }
   }
 
-  // ---- write O[q][head*DH + dd]; accumulator element e of block b: dd = 32b + 8*(e/4) + 4*lhalf + e%4
+  // ---- write O[q][head*DH + dd]; accumulator element e of block b: dd = 32b + 8*(e/4) + 4*lhalf + e%4.
+  // Only two lanes share a query row there (16 contiguous bytes per row and store instruction, and the
+  // write path is bound by the number of requests), so each wavefront transposes its 64 x DH patch
+  // through LDS (16-byte chunks XOR-swizzled by row; every wavefront is past the last barrier of the key
+  // loop, nobody reads the tile buffers any more) and stores 16 bytes per lane, a whole head row of
+  // 2*DH bytes per group of lanes.
+  {
+    constexpr int CPR = DH / 8;                       // 16-byte chunks per patch row
+    constexpr int RPI = 64 / CPR;                     // patch rows per store instruction
+    char *pb = lds.patch[wave];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    if (!row_valid[qb]) continue;
-    half_t *orow = O + (it.q_row + my_q_local[qb]) * (int64_t)d + head * DH;
+    for (int qb = 0; qb < 2; ++qb) {
+      const int row = 32 * qb + l32;
 #pragma unroll
-    for (int b = 0; b < DB; ++b)
+      for (int b = 0; b < DB; ++b)
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        f16x4 v;
+        for (int g = 0; g < 4; ++g) {
+          f16x4 v;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[qb][b][4 * g + i]);
-        *(f16x4 *)(orow + 32 * b + 8 * g + 4 * lhalf) = v;
-      }
+          for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[qb][b][4 * g + i]);
+          const int c = 4 * b + g;
+          *(f16x4 *)(pb + row * (DH * 2) + ((c ^ (row & (CPR - 1))) << 4) + 8 * lhalf) = v;
+        }
+    }
+    const int rl = lane / CPR, c = lane % CPR;
+    half_t *obase = O + (int64_t)it.q_row * d + head * DH + c * 8;
+#pragma unroll
+    for (int t = 0; t < 64 / RPI; ++t) {
+      const int row = t * RPI + rl;
+      const f16x8 v = *(const f16x8 *)(pb + row * (DH * 2) + ((c ^ (row & (CPR - 1))) << 4));
+      if (q_local0 + row < it.n_q) *(f16x8 *)(obase + (int64_t)(q_local0 + row) * d) = v;
+    }
   }
 }
 
