@@ -379,7 +379,7 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
       else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dm, dm, true, s0);
     }
     launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
-                       h->cfg.dtype == FLAME_GR_BF16 ? 1.4426950408889634f : 1.0f, s0);
+                       h->cfg.dtype == FLAME_GR_BF16 ? 0.5f : 1.0f, s0);
   }
   if (h->n_groups == 1) {
     run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0);
@@ -503,9 +503,8 @@ int flame_gr_debug_stage(flame_gr_t *h, int32_t which, float *host_out) {
                       : which == 4 ? h->cap_O : (const void *)h->cap_X;
     HIP_TRY(h, hipMemcpy(raw.data(), src, raw.size(), hipMemcpyDeviceToHost));
   }
-  // the MFMA path stores Q times alpha*log2(e) and V times ln(2): report the plain tensors
-  const float unscale = !bf ? 1.0f : which == 2 ? 1.0f / (h->sh.alpha * 1.4426950408889634f)
-                            : which == 1 ? 1.4426950408889634f : 1.0f;
+  // the MFMA path stores Q times alpha/2: report the plain tensor
+  const float unscale = bf && which == 2 ? 2.0f / h->sh.alpha : 1.0f;
   auto get = [&](size_t row, size_t k) -> float {
     if (esz == 4) return ((const float *)raw.data())[row * d + k];
     const uint16_t *p = (const uint16_t *)raw.data();

@@ -2,8 +2,8 @@
 //
 // For every query row r of a request and every head:
 //     O_r = sum over allowed keys c of silu(<Q_r, K_c> + bias[p_r - p_c]) V_c
-// Q arrives multiplied by alpha*log2(e), the bias table by log2(e) and V by ln(2), so the logits are
-// directly exp2 arguments and the scale factors cancel in O.  History rows look at keys 0..r,
+// Q arrives multiplied by alpha/2 and the bias table by 1/2, so the kernel sees halved logits s = x/2
+// (both factors are powers of two for the usual alpha: no rounding).  History rows look at keys 0..r,
 // candidate rows look at the whole history and at themselves: the customised mask of Section 3.2
 // that lets all candidates of a request be scored in one pass.  No score matrix is materialised:
 // like a flash-attention tile loop, but the pointwise SiLU needs neither running maximum nor
@@ -25,8 +25,8 @@
 // kernel, so V^T tiles are plain row loads.
 //
 // SiLU: two routes to the same fp16 weights.  If every logit of a wavefront's 64x64 patch satisfies
-// |x| <= 2 and no mask is needed, a packed fp16 polynomial (five v_pk_* per two weights, within two
-// fp16 ulps); otherwise the exact exp2/rcp form in fp32 with the mask applied.
+// |x| <= 2 and no mask is needed, a polynomial whose correction term runs in packed fp16 (within one
+// fp16 ulp of the exact weight); otherwise the exact exp2/rcp form in fp32 with the mask applied.
 //
 // Bias: each key tile brings a window of the per-distance table (by decreasing distance, fp32) into
 // LDS; a lane's 8 consecutive entries per accumulator half-block are read straight into the
@@ -45,20 +45,20 @@ constexpr int KT = 64;              // keys per tile
 constexpr int PAD = 8;              // fp16 elements of LDS row padding
 constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..318
 
-// Packed fp16 SiLU for small arguments, exp2 domain: for y = log2(e) x with |x| <= 2,
-//   log2(e) silu(x) = 0.5 y + t (b1 + b3 t + b5 t^2),  t = y^2,
-// where (b1, b3, b5) = (a1 ln2, a3 ln2^3, a5 ln2^5) and (a1, a3, a5) is the weighted least-squares fit of
-// (silu(x) - x/2)/x^2 on [-2, 2] (relative-error weights).  Evaluated in fp16 the result is within
-// 2.8e-3 (6e-4 rms) of the exact value, against 4.9e-4 for rounding the exact value to fp16.
+// SiLU for small arguments.  silu(x) - x/2 is even: silu(x) = x/2 + x^2 r(x^2) with
+// r(u) ~ a1 + a3 u + a5 u^2 (weighted least-squares fit of (silu(x) - x/2)/x^2 on [-2, 2], approximation
+// error below 5.3e-4 at |x| = 2 and below 1e-4 for |x| <= 1.5).  On the halved logit s = x/2, with t = s^2:
+//   silu(x) = s + q,   q = t (4 a1 + 16 a3 t + 64 a5 t^2).
+// t and the bracket are evaluated in packed fp16 (one multiply and two fused multiply-adds per pair of
+// weights); the last step is a mixed-precision fused multiply-add per weight, fp16 t times fp16 bracket
+// plus the fp32 logit itself, rounded to fp16 once, like the weight of the exact route.
 constexpr float kPolyA1 = 0.24916259f, kPolyA3 = -0.01916112f, kPolyA5 = 0.00112581f;
-constexpr float kPolyT2 = (2.0f * kLog2e) * (2.0f * kLog2e);     // bound on t = y^2
-__device__ __forceinline__ f16x2 silu_poly_pk(f16x2 y, f16x2 t) {
-  constexpr float b1 = kPolyA1 * kLn2, b3 = kPolyA3 * kLn2 * kLn2 * kLn2, b5 = kPolyA5 * kLn2 * kLn2 * kLn2 * kLn2 * kLn2;
+constexpr float kPolyT2 = 1.0f;                                  // bound on t = s^2  (|x| <= 2)
+__device__ __forceinline__ f16x2 silu_corr_poly_pk(f16x2 t) {      // 4 a1 + 16 a3 t + 64 a5 t^2
+  constexpr float b1 = 4.0f * kPolyA1, b3 = 16.0f * kPolyA3, b5 = 64.0f * kPolyA5;
   const f16x2 c5 = {(half_t)b5, (half_t)b5}, c3 = {(half_t)b3, (half_t)b3}, c1 = {(half_t)b1, (half_t)b1};
-  const f16x2 hf = {(half_t)0.5f, (half_t)0.5f};
   f16x2 p = __builtin_elementwise_fma(c5, t, c3);
-  p = __builtin_elementwise_fma(p, t, c1);
-  return __builtin_elementwise_fma(t, p, hf * y);
+  return __builtin_elementwise_fma(p, t, c1);
 }
 
 __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
@@ -209,11 +209,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
       // paid once per group.
       f32x16 sacc[2][2];
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb)
+      for (int qb = 0; qb < 2; ++qb) {
+        // one address register per block, the 32 reads use immediate offsets (the empty asm keeps the
+        // compiler from folding the array's LDS offset into every read as a separate add)
+        typedef const __attribute__((address_space(3))) float *lds_cfloat;
+        lds_cfloat bp = (lds_cfloat)(&sBias[buf][0]) + bias_idx[qb];
+        asm volatile("" : "+v"(bp));
 #pragma unroll
         for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sacc[qb][j][e] = sBias[buf][bias_idx[qb] + 32 * j + 16 * (e >> 3) + (e & 7)];
+          for (int e = 0; e < 16; ++e) sacc[qb][j][e] = bp[32 * j + 16 * (e >> 3) + (e & 7)];
+      }
       f16x8 fk[2][2], fv[2][DB];
 #pragma unroll
       for (int j = 0; j < 2; ++j) fk[0][j] = *(const f16x8 *)&sK[buf][32 * j + pi32(l32)][lhalf * 8];
@@ -261,9 +267,11 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
             for (int j = 0; j < 2; ++j)
 #pragma unroll
               for (int i = 0; i < 8; ++i) {
-                const f16x2 w = silu_poly_pk(yh[j][i], th[j][i]);
-                fp[qb][2 * j + (i >> 2)][2 * (i & 3)] = w[0];
-                fp[qb][2 * j + (i >> 2)][2 * (i & 3) + 1] = w[1];
+                const f16x2 r = silu_corr_poly_pk(th[j][i]);
+                const float w0 = __builtin_fmaf((float)th[j][i][0], (float)r[0], sacc[qb][j][2 * i]);
+                const float w1 = __builtin_fmaf((float)th[j][i][1], (float)r[1], sacc[qb][j][2 * i + 1]);
+                fp[qb][2 * j + (i >> 2)][2 * (i & 3)] = (half_t)w0;
+                fp[qb][2 * j + (i >> 2)][2 * (i & 3) + 1] = (half_t)w1;
               }
           }
         }
@@ -272,7 +280,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
           for (int j = 0; j < 2; ++j) {
             float p[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) p[e] = silu_log2_domain(sacc[qb][j][e]);
+            for (int e = 0; e < 16; ++e) p[e] = silu_half_domain(sacc[qb][j][e]);
             if (need_mask) {
 #pragma unroll
               for (int e = 0; e < 16; ++e) {
@@ -327,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
 #pragma unroll
       for (int e = 0; e < 16; ++e) {
         const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
-        p[e] = (kv_local == l32 && row_valid[qb]) ? silu_log2_domain(sacc[e]) : 0.f;
+        p[e] = (kv_local == l32 && row_valid[qb]) ? silu_half_domain(sacc[e]) : 0.f;
       }
       const f16x8 fps[2] = {pack8(p), pack8(p + 8)};
 #pragma unroll
@@ -350,6 +358,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
     constexpr int CPR = DH / 8;                       // 16-byte chunks per patch row
     constexpr int RPI = 64 / CPR;                     // patch rows per store instruction
     char *pb = lds.patch[wave];
+    auto pkey = [](int row) { return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };   // spreads 16 rows over 256 bytes
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
       const int row = 32 * qb + l32;
@@ -361,7 +370,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
 #pragma unroll
           for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[qb][b][4 * g + i]);
           const int c = 4 * b + g;
-          *(f16x4 *)(pb + row * (DH * 2) + ((c ^ (row & (CPR - 1))) << 4) + 8 * lhalf) = v;
+          *(f16x4 *)(pb + row * (DH * 2) + ((c ^ pkey(row)) << 4) + 8 * lhalf) = v;
         }
     }
     const int rl = lane / CPR, c = lane % CPR;
@@ -369,7 +378,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
 #pragma unroll
     for (int t = 0; t < 64 / RPI; ++t) {
       const int row = t * RPI + rl;
-      const f16x8 v = *(const f16x8 *)(pb + row * (DH * 2) + ((c ^ (row & (CPR - 1))) << 4));
+      const f16x8 v = *(const f16x8 *)(pb + row * (DH * 2) + ((c ^ pkey(row)) << 4));
       if (q_local0 + row < it.n_q) *(f16x8 *)(obase + (int64_t)(q_local0 + row) * d) = v;
     }
   }

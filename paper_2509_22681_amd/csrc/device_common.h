@@ -48,12 +48,11 @@ __device__ __forceinline__ float silu_fast(float x) {
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-// SiLU of an argument that arrives pre-multiplied by log2(e): returns log2(e) * silu(x) for
-// y = log2(e) * x, in four instructions (exp2, add, rcp, mul).  The attention kernel keeps its
-// logits in this scaled form (the scale is folded into Q and into the bias table) and the factor
-// 1/log2(e) is folded into V.
-__device__ __forceinline__ float silu_log2_domain(float y) {
-  return y * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(-y));
+// SiLU of an argument that arrives halved: returns silu(x) for s = x / 2.  The attention kernel keeps
+// its logits in this form (the factor 1/2 is folded into Q and into the bias table, both exactly):
+// silu(x) = x/2 + x^2 r(x^2) then starts from the logit itself, see the polynomial route there.
+__device__ __forceinline__ float silu_half_domain(float s) {
+  return (2.0f * s) * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * (-2.0f * kLog2e)));
 }
 
 // "k-tile blocked" layout of the fp16 GEMM operands (the activation copy Xh and the converted weight

@@ -37,16 +37,22 @@ constexpr int RB = BM / kRowAlign;      // 64-row blocks per row tile
 
 struct PlaneSel { int id[4]; int n; };
 
-// byte offset of 16-byte chunk c (0..3) of tile row `row` inside one LDS operand.  Two 64-byte rows share
-// a 128-byte line; the slot inside the line is XORed with a key made of row bits 1, 2 ^ 4 and 3.  Both
-// fragment row orders used below (identity: row bits 0..2 vary over 8 consecutive lanes; sigma32: row
-// bits 0, 1, 4 vary) then send 8 consecutive lanes to 8 different slots.
-__device__ __forceinline__ int lds_key(int line) { return (line & 5) | ((line ^ (line >> 2)) & 2); }
+// byte offset of 16-byte chunk c (0..3) of tile row `row` inside one LDS operand.  The LDS serves 16
+// lanes x 16 bytes = 256 bytes per clock from 64 banks, so 16 consecutive lanes of a fragment read (16
+// rows, same chunk) must fall into 16 different 16-byte slots modulo 256 bytes.  Four 64-byte rows
+// share a 256-byte group: row bits 0..1 pick the quarter, and the chunk index is XORed with a 2-bit key
+// made of row bits 2 and 3 ^ 4.  Both fragment row orders used below (identity: row bits 0..3 vary
+// over 16 consecutive lanes; sigma32: row bits 0, 1, 2, 4 vary) then use every slot once.
+__device__ __forceinline__ int lds_key(int row) { return ((row >> 2) & 1) | ((((row >> 3) ^ (row >> 4)) & 1) << 1); }
 __device__ __forceinline__ int lds_off(int row, int c) {
-  const int line = row >> 1;
-  const int slot = ((row & 1) << 2) | c;
-  return line * 128 + ((slot ^ lds_key(line)) << 4);
+  return (row >> 2) * 256 + ((((row & 3) << 2) | (c ^ lds_key(row))) << 4);
 }
+// XOR key of the chunk index in an epilogue patch whose rows hold CPR 16-byte chunks (8: 128-byte rows,
+// two per 256-byte group; 4: 64-byte rows, four per group): 16 consecutive rows of one chunk column use
+// every slot of the 256 bytes once.
+template <int CPR>
+__device__ __forceinline__ int patch_key(int row) { return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; }
+
 // Row order of the MFMA A operand.  Accumulator element e of lane (l32, lhalf) belongs to A-operand
 // row 8*(e/4) + 4*lhalf + e%4.  Feeding tile row sigma32(m) = 16*bit2(m) + 4*(m/8) + m%4 into A-operand
 // row m turns that into tile row 16*lhalf + e: a lane then owns 16 consecutive outputs (features of
@@ -109,13 +115,13 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     blk[r] = t < n_blk ? (blk_list ? blk_list[t] : blk_first + t) : -1;
   }
 
-  // LDS-DMA sources.  One instruction of a wavefront fills 1 KB = 8 lines = 16 tile rows; lane p owns
-  // physical slot p & 7 of line p >> 3 and must fetch the chunk the swizzle maps there:
-  // slot = (p & 7) ^ key(line), row = 2 * line + (slot >> 2), chunk = slot & 3.  Instruction q of wavefront
-  // w covers tile rows 16 * (4 q + w) .. + 15 (A: q = 0..3, one 64-row block each; B: q < BN / 64).
+  // LDS-DMA sources.  One instruction of a wavefront fills 1 KB = four 256-byte groups = 16 tile rows;
+  // lane p owns physical slot p & 15 of group p >> 4 and must fetch the chunk the swizzle maps there:
+  // row = 4 * group + (slot >> 2), chunk = (slot & 3) ^ key(row).  Instruction q of wavefront w covers tile
+  // rows 16 * (4 q + w) .. + 15 (A: q = 0..3, one 64-row block each; B: q < BN / 64).
   constexpr int A_Q = BM / 64, B_Q = BN / 64;
-  const int dl = lane >> 3, dslot = (lane & 7) ^ lds_key(8 * wave + dl);
-  const int rloc = 16 * wave + 2 * dl + (dslot >> 2), dch = dslot & 3;
+  const int rloc = 16 * wave + 4 * (lane >> 4) + ((lane & 15) >> 2);
+  const int dch = (lane & 3) ^ lds_key(rloc);
   // W is k-tile blocked (64 rows x 32 k = 2048 contiguous elements, whole 128-byte lines per request);
   // A is blocked too when it is the activation copy Xh, row-major when it is G.
   int64_t aoff[A_Q];
@@ -221,17 +227,16 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     // Only two lanes share an output row in the accumulator layout, so direct stores would reach the
     // L2 as 32-byte pieces, and the write path is then bound by the number of requests.  The
     // wavefront's patch goes through LDS instead (the operand ring is free by now; each wavefront
-    // owns a private slice of it, chunks XOR-swizzled by row) and leaves as 16 bytes per lane with
+    // owns a private slice of it, chunks XOR-swizzled by row so that writes and reads are conflict free) and leaves as 16 bytes per lane with
     // whole 128-byte lines per output row.
     __builtin_amdgcn_s_barrier();                     // every wavefront has finished reading the ring
     char *pb = smem + wave * (128 * WN * 2);
     half_t *P = planes + (int64_t)plane * ws_rows * d;
     if (!feature_major) {
       // patch[128 tokens][WN features]; lane holds token 32i + l32, features 32j + 16*lhalf + 0..15.
-      // Q leaves this kernel multiplied by alpha * log2(e): the attention logits are then
-      // directly the arguments of exp2 (V carries the inverse factor ln 2).
+      // Q leaves this kernel multiplied by alpha / 2: the attention kernel works on halved logits.
       constexpr int CPR = WN / 8;                     // 16-byte chunks per patch row
-      const float sc = plane == 2 ? alpha * kLog2e : 1.0f;
+      const float sc = plane == 2 ? alpha * 0.5f : 1.0f;
       const bf16_t *brow = bias + plane * d + n_in_plane + wn * WN + 16 * lhalf;
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 #pragma unroll
             for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + (float)(g ? bv1[q] : bv0[q])) * sc);
             const int c = 4 * j + 2 * lhalf + g;
-            *(f16x8 *)(pb + row * (WN * 2) + ((c ^ (row & (CPR - 1))) << 4)) = o;
+            *(f16x8 *)(pb + row * (WN * 2) + ((c ^ patch_key<CPR>(row)) << 4)) = o;
           }
         }
       }
@@ -255,7 +260,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 #pragma unroll
       for (int it = 0; it < 128 / RPI; ++it) {
         const int row = it * RPI + rl;
-        const f16x8 v = *(const f16x8 *)(pb + row * (WN * 2) + ((c ^ (row & (CPR - 1))) << 4));
+        const f16x8 v = *(const f16x8 *)(pb + row * (WN * 2) + ((c ^ patch_key<CPR>(row)) << 4));
         const int rblk = row >= 64 ? b1 : b0;
         if (rblk >= 0) *(f16x8 *)(pcol + ((int64_t)rblk * kRowAlign + (row & 63)) * d) = v;
       }
@@ -272,9 +277,9 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
           for (int g = 0; g < 2; ++g) {
             f16x8 o;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + bv) * kLn2);
+            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + bv));
             const int c = 4 * i + 2 * lhalf + g;
-            *(f16x8 *)(pb + fr * 256 + (((c & 8) | ((c ^ fr) & 7)) << 4)) = o;
+            *(f16x8 *)(pb + fr * 256 + (((c ^ fr) & 15) << 4)) = o;
           }
         }
       }
@@ -285,7 +290,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 #pragma unroll
         for (int it = 0; it < WN / 4; ++it) {
           const int fr = it * 4 + rl;
-          const f16x8 v = *(const f16x8 *)(pb + fr * 256 + (((c & 8) | ((c ^ fr) & 7)) << 4));
+          const f16x8 v = *(const f16x8 *)(pb + fr * 256 + (((c ^ fr) & 15) << 4));
           *(f16x8 *)(prow + (int64_t)fr * ws_rows) = v;
         }
       }

@@ -8,7 +8,8 @@
 //   * one workgroup = one 64-row block of the workspace, all d output features (d <= 512 per pass);
 //   * phase 1: each wavefront normalises 16 rows (one row per wavefront-wide 16-byte load, statistics
 //     by wavefront reduction in fp32: mean, then centred second moment) and writes the gated fp16 rows
-//     into LDS, 16-byte chunks XOR-swizzled so that the MFMA operand reads are conflict free;
+//     into LDS, 16-byte chunks XOR-swizzled with the row's low four bits so that the MFMA operand reads are
+//     conflict free (the LDS serves 16 lanes x 16 bytes per clock from 64 banks);
 //   * phase 2: each wavefront owns d/4 output features; the W2 operand comes straight from L2 in a
 //     fragment-major packed layout (one coalesced 1 KB read per MFMA operand, prepared once per forward
 //     by pack_w2_kernel), so LDS holds only the activations and two workgroups fit on a CU;
@@ -123,7 +124,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
           for (int k = 0; k < 8; ++k)
             o[k] = pad ? (half_t)0.f : to_f16_sat(((v[c][k] - mu) * rstd * g[c][k] + bt[c][k]) * (float)uv[set][q][c][k]);
-          *(f16x8 *)(smem + r * (d * 2) + ((ch ^ (r & 7)) << 4)) = o;
+          *(f16x8 *)(smem + r * (d * 2) + ((ch ^ (r & 15)) << 4)) = o;
         }
       }
     }
@@ -147,7 +148,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int r = 32 * i + l32;
-    fa[0][i] = *(const f16x8 *)(smem + r * (d * 2) + ((lhalf ^ (r & 7)) << 4));
+    fa[0][i] = *(const f16x8 *)(smem + r * (d * 2) + ((lhalf ^ (r & 15)) << 4));
   }
 #pragma unroll 4
   for (int ks = 0; ks < NKS; ++ks) {
@@ -158,7 +159,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
     for (int i = 0; i < 2; ++i) {
       const int r = 32 * i + l32;
-      fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ (r & 7)) << 4));
+      fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ (r & 15)) << 4));
     }
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -178,6 +179,8 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
   constexpr int RPI = 64 / CPR;                     // patch rows per instruction
   constexpr int NIT = 32 / RPI;
   char *pb = smem + wave * (32 * WF * 4);
+  // chunk XOR key: 16 consecutive rows of one chunk column use each of the 16 slots of 256 bytes once
+  auto pkey = [](int row) { return CPR == 8 ? (row >> 1) & 7 : row & 15; };
   const int rl = lane / CPR, cc = lane % CPR;
   const int n = wave * WF + 4 * cc;                 // this lane's 4 features in the read-out
   f32x4 bvf;
@@ -199,12 +202,12 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
       for (int gq = 0; gq < 4; ++gq) {
         const int c = 8 * j + 2 * gq + lhalf;
         const f32x4 v = {acc[i][j][4 * gq], acc[i][j][4 * gq + 1], acc[i][j][4 * gq + 2], acc[i][j][4 * gq + 3]};
-        *(f32x4 *)(pb + l32 * (WF * 4) + ((c ^ (l32 & 7)) << 4)) = v;
+        *(f32x4 *)(pb + l32 * (WF * 4) + ((c ^ pkey(l32)) << 4)) = v;
       }
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int row = it * RPI + rl;
-      const f32x4 v = *(const f32x4 *)(pb + row * (WF * 4) + ((cc ^ (row & 7)) << 4));
+      const f32x4 v = *(const f32x4 *)(pb + row * (WF * 4) + ((cc ^ pkey(row)) << 4));
       f32x4 x = xr[it % XB];
       if (it + XB < NIT) xr[it % XB] = *(const f32x4 *)(xrow + (int64_t)(it + XB) * RPI * d);
       f16x4 o;

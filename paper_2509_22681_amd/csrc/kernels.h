@@ -21,8 +21,8 @@ void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_e
 // fp16 copy of a bf16 matrix of `rows` rows of K elements (K % 8 == 0); blocked: written in the k-tile
 // blocked layout of the GEMM operands (rows % 64 == 0, K % 32 == 0), else element for element
 void launch_bf16_to_f16(const void *in, void *out, int64_t rows, int K, bool blocked, hipStream_t s);
-// bias[lh][delta] = scale * rab[lh][bucket_tab[delta]] for all layers and heads (scale = log2(e) in
-// the MFMA path, whose logits live in the exp2 domain; 1 in the fp32 path).
+// bias[lh][delta] = scale * rab[lh][bucket_tab[delta]] for all layers and heads (scale = 1/2 in the
+// MFMA path, whose attention kernel works on halved logits; 1 in the fp32 path).
 void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias, int n_lh,
                         int n_buckets, int D, float scale, hipStream_t s);
 // G = (LayerNorm(O) * gamma + beta) * U, one row at a time (element type of O, U, G = dtype);
