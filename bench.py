@@ -33,6 +33,18 @@ def attention_flops_per_layer(cfg, L, M):
     return full, last
 
 
+def stored_traffic(workload):
+    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload (two
+    counter runs, FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), or None if there is
+    no such summary.  A stored measurement: counters cannot be read from inside this process."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_attn_hbm_traffic.json")
+    try:
+        with open(path) as f:
+            return float(json.load(f)["bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        return None
+
+
 def cpu_baseline(wl, budget_s=12.0):
     """Time the fp64 oracle on the cheapest requests of the workload until the budget is used, then
     scale to the whole batch by the cost model (algorithmic flops)."""
@@ -107,6 +119,9 @@ def main():
     ap.add_argument("--streams", type=int, default=0, help="internal stream groups of the batcher (0/1 = caller's stream)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
+    ap.add_argument("--calibration-copy-mib", type=int, default=0,
+                    help="before the timed region, run one plain device-to-device copy kernel of this many MiB "
+                         "(a kernel of known HBM traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU (requests are independent; more GPUs would each run this same "
@@ -125,6 +140,14 @@ def main():
     n_scores = int(wl.cand_offsets[-1])
     scores = torch.zeros(n_scores, device="cuda:0", dtype=torch.float32)
     h = B.flame_gr_create(B.config_for(wl, n_streams=args.streams))
+    if args.calibration_copy_mib > 0:
+        n = args.calibration_copy_mib * (1 << 20) // 4
+        src = torch.ones(n, device="cuda:0", dtype=torch.float32)
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)                    # one elementwise copy kernel: reads n*4 bytes, writes n*4 bytes
+        torch.cuda.synchronize()
+        del src, dst
     try:
         for _ in range(args.warmup):
             B.flame_gr_forward(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
@@ -177,9 +200,9 @@ def main():
         "pct_of_bf16_mfma_peak": 100.0 * flops_pruned / (dt / args.steps) / (PEAK_BF16_TFLOPS * 1e12),
         "ms_per_step_without_kernel_events": dt_plain / args.steps * 1e3,
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
-        "roofline": {"kernel": "attn_bf16_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
+        "roofline": {"kernel": "attn_mfma_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": None,
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(args.workload),
                      "avg_launch_ms": attn_avg_ms, "launches": attn_launches,
                      "algorithmic_flops_per_launch": attn_flops_per_launch},
     }

@@ -54,13 +54,6 @@ constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bi
 // plus the fp32 logit itself, rounded to fp16 once, like the weight of the exact route.
 constexpr float kPolyA1 = 0.24916259f, kPolyA3 = -0.01916112f, kPolyA5 = 0.00112581f;
 constexpr float kPolyT2 = 1.0f;                                  // bound on t = s^2  (|x| <= 2)
-__device__ __forceinline__ f16x2 silu_corr_poly_pk(f16x2 t) {      // 4 a1 + 16 a3 t + 64 a5 t^2
-  constexpr float b1 = 4.0f * kPolyA1, b3 = 16.0f * kPolyA3, b5 = 64.0f * kPolyA5;
-  const f16x2 c5 = {(half_t)b5, (half_t)b5}, c3 = {(half_t)b3, (half_t)b3}, c1 = {(half_t)b1, (half_t)b1};
-  f16x2 p = __builtin_elementwise_fma(c5, t, c3);
-  return __builtin_elementwise_fma(p, t, c1);
-}
-
 __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
   return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
 }
@@ -263,16 +256,26 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
           const bool bad = !((float)m[0] <= kPolyT2 && (float)m[1] <= kPolyT2);     // NaN counts as bad
           fast = __builtin_amdgcn_ballot_w64(bad) == 0;
           if (fast) {
+            // stage by stage over eight independent pairs, so that no instruction waits for the one before
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j) {
+              constexpr float b1 = 4.0f * kPolyA1, b3 = 16.0f * kPolyA3, b5 = 64.0f * kPolyA5;
+              const f16x2 c5 = {(half_t)b5, (half_t)b5}, c3 = {(half_t)b3, (half_t)b3}, c1 = {(half_t)b1, (half_t)b1};
+              f16x2 r[8];
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = __builtin_elementwise_fma(c5, th[j][i], c3);
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = __builtin_elementwise_fma(r[i], th[j][i], c1);
+              float w[16];
 #pragma unroll
               for (int i = 0; i < 8; ++i) {
-                const f16x2 r = silu_corr_poly_pk(th[j][i]);
-                const float w0 = __builtin_fmaf((float)th[j][i][0], (float)r[0], sacc[qb][j][2 * i]);
-                const float w1 = __builtin_fmaf((float)th[j][i][1], (float)r[1], sacc[qb][j][2 * i + 1]);
-                fp[qb][2 * j + (i >> 2)][2 * (i & 3)] = (half_t)w0;
-                fp[qb][2 * j + (i >> 2)][2 * (i & 3) + 1] = (half_t)w1;
+                w[2 * i] = __builtin_fmaf((float)th[j][i][0], (float)r[i][0], sacc[qb][j][2 * i]);
+                w[2 * i + 1] = __builtin_fmaf((float)th[j][i][1], (float)r[i][1], sacc[qb][j][2 * i + 1]);
               }
+              __builtin_amdgcn_sched_barrier(0);
+              fp[qb][2 * j] = pack8(w);
+              fp[qb][2 * j + 1] = pack8(w + 8);
+            }
           }
         }
         if (!fast) {
