@@ -24,9 +24,10 @@
 // is exactly the k order of a 16-deep B operand.  V is stored feature-major by the projection
 // kernel, so V^T tiles are plain row loads.
 //
-// SiLU: two routes to the same fp16 weights.  If every logit of a wavefront's 64x64 patch satisfies
-// |x| <= 2 and no mask is needed, a polynomial whose correction term runs in packed fp16 (within one
-// fp16 ulp of the exact weight); otherwise the exact exp2/rcp form in fp32 with the mask applied.
+// SiLU: two routes to the same fp16 weights.  If every logit of a wavefront's 32x64 block satisfies
+// |x| <= 2 (masked positions included), a polynomial whose correction term runs in packed fp16 (within one
+// fp16 ulp of the exact weight); otherwise the exact exp2/rcp form in fp32.  The mask is applied to the
+// fp32 weights of either route, on boundary tiles only.
 //
 // Bias: each key tile brings a window of the per-distance table (by decreasing distance, fp32) into
 // LDS; a lane's 8 consecutive entries per accumulator half-block are read straight into the
@@ -239,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
         bool fast = false;
-        if (!need_mask) {
+        {
           f16x2 yh[2][8], th[2][8];
 #pragma unroll
           for (int j = 0; j < 2; ++j)
@@ -271,6 +272,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
               for (int i = 0; i < 8; ++i) {
                 w[2 * i] = __builtin_fmaf((float)th[j][i][0], (float)r[i][0], sacc[qb][j][2 * i]);
                 w[2 * i + 1] = __builtin_fmaf((float)th[j][i][1], (float)r[i][1], sacc[qb][j][2 * i + 1]);
+              }
+              if (need_mask) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                  const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
+                  w[e] = kv < n_vis[qb] ? w[e] : 0.f;
+                }
               }
               __builtin_amdgcn_sched_barrier(0);
               fp[qb][2 * j] = pack8(w);
