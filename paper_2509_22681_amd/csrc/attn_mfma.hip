@@ -10,9 +10,13 @@
 // rescaling.
 //
 // Work decomposition: one workgroup = (query tile of 256 rows, head); 4 wavefronts, 64 query rows
-// each (two 32-row MFMA blocks that share every K and V fragment read from LDS: fragment traffic, not
-// MFMA issue, is what bounds this loop on a CU with 128 B/clk of LDS); keys are walked in tiles of 64
-// staged through LDS (double buffered, next tile prefetched into registers).
+// each (two 32-row MFMA blocks, processed one after the other).  Keys are walked in
+// tiles of 128, processed as two halves of 64.  A tile (K rows, V^T rows and the window of the bias
+// table it needs) is brought into one of two LDS stages by LDS-DMA loads (global_load_lds: no staging
+// registers, no LDS store instructions), requested one tile ahead right after the barrier that opens
+// the current tile: one barrier per 128 keys.  LDS rows are unpadded (a DMA instruction fills 1 KB of
+// consecutive LDS) and 16-byte chunks are XOR-swizzled so that 16 consecutive lanes of a fragment read
+// fall into 16 different slots of the 256 bytes the LDS serves per clock.
 //
 // Register-level formulation: the products are computed transposed,
 //     S^T[kv][q] = K Q^T      (A operand = K rows, B operand = Q rows)
@@ -42,9 +46,9 @@ namespace {
 
 constexpr int QT = kAttnQTileBf16;  // query rows per workgroup (4 wavefronts x 64)
 static_assert(QT == 256, "4 wavefronts of 64 query rows");
-constexpr int KT = 64;              // keys per tile
-constexpr int PAD = 8;              // fp16 elements of LDS row padding
-constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..318
+constexpr int KT = 128;             // keys per LDS stage
+constexpr int KH = 64;              // keys per half tile (one pass of the register-level loop)
+constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..382
 
 // SiLU for small arguments.  silu(x) - x/2 is even: silu(x) = x/2 + x^2 r(x^2) with
 // r(u) ~ a1 + a3 u + a5 u^2 (weighted least-squares fit of (silu(x) - x/2)/x^2 on [-2, 2], approximation
@@ -75,20 +79,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
                                                            int H, int d, int D, int64_t ws_rows) {
   constexpr int KS = DH / 16;          // k-steps of the Q K^T product
   constexpr int DB = DH / 32;          // 32-row blocks of O^T
-  constexpr int NCH = DH / 32;         // 16-byte chunks per thread for one K (or V^T) tile
-  struct Tiles {
-    half_t sK[2][KT][DH + PAD];
-    half_t sVt[2][DH][KT + PAD];
-    float sBias[2][BW];
-  };
-  // the output patches of the four wavefronts reuse the tile buffers once the key loop is over
-  __shared__ __attribute__((aligned(16))) union {
-    Tiles t;
-    char patch[4][64 * DH * 2];
-  } lds;
-  auto &sK = lds.t.sK;
-  auto &sVt = lds.t.sVt;
-  auto &sBias = lds.t.sBias;
+  constexpr int KCH = DH / 8;          // 16-byte chunks per K row (8 or 4)
+  constexpr int KSH = KCH == 8 ? 1 : 2;            // K rows per 256 bytes = 1 << KSH
+  constexpr int K_BYTES = KT * DH * 2;             // K tile [128 keys][DH]
+  constexpr int V_BYTES = DH * KT * 2;             // V^T tile [DH][128 keys]
+  constexpr int STAGE = K_BYTES + V_BYTES + BW * 4;
+  static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0 && STAGE % 256 == 0, "stage parts start on 256-byte boundaries");
+  static_assert(4 * 64 * DH * 2 <= 2 * STAGE, "output patches fit in the tile buffers");
+  // two stages; the output patches of the four wavefronts reuse them once the key loop is over
+  __shared__ __attribute__((aligned(256))) char lds[2 * STAGE];
 
   const int head = blockIdx.x % H;
   const AttnItem it = items[blockIdx.x / H];
@@ -133,55 +132,50 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   const int n_tiles = (it.n_kv + KT - 1) / KT;
   const int q_first = it.is_cand ? it.L : it.q_pos;     // position of query row 0 of the workgroup tile
 
-  // global -> register -> LDS staging of one key tile: per-thread source pointers at tile 0 and LDS
-  // destinations are fixed; every iteration prefetches unconditionally (the last one re-reads its
-  // own tile) so that the staging registers never live across a branch.
-  const half_t *gK[NCH];
-  const half_t *gV[NCH];
-  int oK[NCH], oV[NCH];
+  // ---- LDS-DMA sources.  One instruction of a wavefront fills 1 KB of LDS, lane p at byte 16 p.
+  // K tile: 1 KB = 64 / KCH rows; lane p owns physical chunk p % KCH of row p / KCH and fetches the logical
+  // chunk the swizzle maps there (chunk ^ key, key = row bits above the rows that share 256 bytes).
+  // V^T tile: 1 KB = 4 feature rows of 256 bytes; physical chunk p % 16 of row p / 16, key = row % 16.
+  // Instruction I = wave + 4 i of either tile belongs to this wavefront.
+  typedef __attribute__((address_space(1))) const void gvoid;
+  typedef __attribute__((address_space(3))) void lvoid;
+  constexpr int NKI = KCH / 2, NVI = DH / 16;         // instructions per wavefront and tile
+  // Instruction i of a wavefront covers rows 4 i * (64 / KCH) (K) or 16 i (V^T) further down; those steps leave
+  // the swizzle keys unchanged, so one lane pointer per tile kind plus scalar offsets is enough.  The lane
+  // pointers are recomputed at every request (a few dozen instructions per 128 keys) from an opaque copy of
+  // the lane index: kept across the key loop they would be spilled, and their reloads would have to wait for
+  // the requests issued just before.
+  // bias window: slot u = tid (all wavefronts) and u = 256 + tid (wavefronts 0 and 1), 4 bytes per lane
+  auto request_tile = [&](int t, int stage) {
+    char *sb = lds + stage * STAGE;
+    const int k0_ = t * KT;
+    int ln = lane;
+    int64_t wsr = ws_rows;
+    asm volatile("" : "+v"(ln), "+s"(wsr));
+    {
+      const int row = wave * (64 / KCH) + ln / KCH;
+      const int c = (ln % KCH) ^ ((row >> KSH) & (KCH - 1));
+      const half_t *g = Kp + (int64_t)(it.kv_row + k0_ + row) * d + c * 8;
 #pragma unroll
-  for (int i = 0; i < NCH; ++i) {
-    const int c = tid + i * 256;
-    const int r = c / (DH / 8), c8 = c % (DH / 8);
-    gK[i] = Kp + (int64_t)(it.kv_row + r) * d + c8 * 8;
-    oK[i] = r * (DH + PAD) + c8 * 8;
-    const int rr = c >> 3, cc = c & 7;
-    gV[i] = Vt + (int64_t)rr * ws_rows + it.kv_row + cc * 8;
-    oV[i] = rr * (KT + PAD) + cc * 8;
-  }
-  // bias window: thread t stages slots t and (t < BW-256) t + 256
-  const int delta0 = q_first + (QT - 1) - tid;          // distance held by window slot tid for tile 0
-  uint4 rk[NCH], rv[NCH];
-  float rb0, rb1;
-#define ATTN_LOAD_TILE(T)                                                                   \
-  {                                                                                         \
-    const int k0_ = (T) * KT;                                                               \
-    _Pragma("unroll") for (int i = 0; i < NCH; ++i) {                                       \
-      rk[i] = *(const uint4 *)(gK[i] + (int64_t)k0_ * d);                                   \
-      rv[i] = *(const uint4 *)(gV[i] + k0_);                                                \
-    }                                                                                       \
-    int dl_ = delta0 - k0_;                                                                 \
-    int dh_ = dl_ - 256;                                                                    \
-    dl_ = dl_ < 0 ? 0 : (dl_ > D - 1 ? D - 1 : dl_);                                        \
-    dh_ = dh_ < 0 ? 0 : (dh_ > D - 1 ? D - 1 : dh_);                                        \
-    rb0 = bias[dl_];                                                                        \
-    rb1 = bias[dh_];                                                                        \
-  }
-#define ATTN_STORE_TILE(BUF)                                                                \
-  {                                                                                         \
-    _Pragma("unroll") for (int i = 0; i < NCH; ++i) {                                       \
-      *(uint4 *)(&sK[BUF][0][0] + oK[i]) = rk[i];                                           \
-      *(uint4 *)(&sVt[BUF][0][0] + oV[i]) = rv[i];                                          \
-    }                                                                                       \
-    sBias[BUF][tid] = rb0;                                                                  \
-    if (tid < BW - 256) sBias[BUF][tid + 256] = rb1;                                        \
-  }
-
-  if (n_tiles > 0) {
-    ATTN_LOAD_TILE(0);
-    ATTN_STORE_TILE(0);
-  }
-  __syncthreads();
+      for (int i = 0; i < NKI; ++i)
+        __builtin_amdgcn_global_load_lds((gvoid *)(g + (int64_t)(4 * i * (64 / KCH)) * d), (lvoid *)(sb + (wave + 4 * i) * 1024), 16, 0, 0);
+    }
+    {
+      const int row = wave * 4 + (ln >> 4);
+      const int c = (ln & 15) ^ (row & 15);
+      const half_t *g = Vt + (int64_t)row * wsr + (it.kv_row + k0_) + c * 8;
+#pragma unroll
+      for (int i = 0; i < NVI; ++i)
+        __builtin_amdgcn_global_load_lds((gvoid *)(g + (int64_t)(16 * i) * wsr), (lvoid *)(sb + K_BYTES + (wave + 4 * i) * 1024), 16, 0, 0);
+    }
+    int dl_ = q_first + (QT - 1) - (wave * 64 + ln) - k0_;     // distance held by window slot tid
+    int dh_ = dl_ - 256;
+    dl_ = dl_ < 0 ? 0 : (dl_ > D - 1 ? D - 1 : dl_);
+    dh_ = dh_ < 0 ? 0 : (dh_ > D - 1 ? D - 1 : dh_);
+    __builtin_amdgcn_global_load_lds((gvoid *)(bias + dl_), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
+    if (wave < (BW - 256) / 64)
+      __builtin_amdgcn_global_load_lds((gvoid *)(bias + dh_), (lvoid *)(sb + K_BYTES + V_BYTES + 1024 + wave * 256), 4, 0, 0);
+  };
 
   // Window slot of (my row of block qb, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's
   // index in the workgroup tile (0 for candidate rows: they all sit at the same distance from a
@@ -189,65 +183,82 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   int bias_idx[2];
 #pragma unroll
   for (int qb = 0; qb < 2; ++qb) bias_idx[qb] = (QT - 1) - (it.is_cand ? 0 : my_q_local[qb]) + 8 * lhalf;
+  // fragment byte offsets inside a stage.  K (A operand of S^T): MFMA row m takes key pi32(m); per 32-key
+  // block j the row advances by 32 (key bits 0..4 unchanged, so the swizzle key is the same).  V^T (A
+  // operand of O^T): row = feature 32 b + l32, chunk = key / 8.
+  // The swizzled chunk (c ^ key) << 4 never carries into the row bits, so an address is
+  // (row base | key << 4) ^ (c << 4): one XOR with a constant per fragment.
+  const int krow = pi32(l32);
+  const int ka0 = (krow * (DH * 2)) | (((((krow >> KSH) & (KCH - 1)) ^ lhalf) << 4));
+  const int va0 = (K_BYTES + l32 * (KT * 2)) | ((((l32 & 15) ^ lhalf) << 4));
+
+  if (n_tiles > 0) request_tile(0, 0);
 
   for (int t = 0; t < n_tiles; ++t) {
-    const int buf = t & 1;
-    const int k0 = t * KT;
-    const int tn = t + 1 < n_tiles ? t + 1 : t;
-    ATTN_LOAD_TILE(tn);
-    __builtin_amdgcn_sched_barrier(0);   // the prefetch stays ahead of the tile's arithmetic
+    const char *sb = lds + (t & 1) * STAGE;
+    // tile t has landed for this wavefront; past the barrier it has landed for all of them, and everybody
+    // has left tile t-1, whose stage the next request overwrites
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    if (t + 1 < n_tiles) request_tile(t + 1, (t + 1) & 1);
+    __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
+#pragma unroll 1
+    for (int u = 0; u < KT / KH; ++u) {
+    const int k0 = t * KT + u * KH;
     if (wave_active && k0 < wave_vis_max) {
-      // ---- S^T = K Q^T: blocks [qb][j], j = 32-key half of the tile; K fragments shared by both qb.
-      // Fragment reads run one group ahead of the MFMAs that use them (and the first V^T group is
-      // fetched behind the last K group), so LDS latency hides behind matrix work instead of being
-      // paid once per group.
-      f32x16 sacc[2][2];
+      const char *kb = sb + u * (KH * DH * 2);                 // K rows of this half tile
+      const int vau = va0 ^ (u << 7);                          // V^T: chunks 8 u .. 8 u + 7 of each row
+      const bool need_mask = k0 + KH > wave_vis_min;
+      // The two 32-row query blocks of the wavefront go through the half tile one after the other (each
+      // reads its own K and V^T fragments: the LDS has the bandwidth, the register file has no room for
+      // the accumulators of both).
 #pragma unroll
       for (int qb = 0; qb < 2; ++qb) {
-        // one address register per block, the 32 reads use immediate offsets (the empty asm keeps the
-        // compiler from folding the array's LDS offset into every read as a separate add)
-        typedef const __attribute__((address_space(3))) float *lds_cfloat;
-        lds_cfloat bp = (lds_cfloat)(&sBias[buf][0]) + bias_idx[qb];
-        asm volatile("" : "+v"(bp));
+        // ---- S^T = K Q^T: blocks [j], j = 32-key half of the half tile.  Fragment reads run one group
+        // ahead of the MFMAs that use them (and the first V^T group is fetched behind the last K group),
+        // so LDS latency hides behind matrix work instead of being paid once per group.
+        f32x16 sacc[2];
+        {
+          // one address register, the 32 reads use immediate offsets (the empty asm keeps the compiler
+          // from folding constant parts of the address into every read as a separate add)
+          typedef const __attribute__((address_space(3))) float *lds_cfloat;
+          lds_cfloat bp = (lds_cfloat)(sb + K_BYTES + V_BYTES) + (bias_idx[qb] + u * KH);
+          asm volatile("" : "+v"(bp));
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+          for (int j = 0; j < 2; ++j)
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sacc[qb][j][e] = bp[32 * j + 16 * (e >> 3) + (e & 7)];
-      }
-      f16x8 fk[2][2], fv[2][DB];
-#pragma unroll
-      for (int j = 0; j < 2; ++j) fk[0][j] = *(const f16x8 *)&sK[buf][32 * j + pi32(l32)][lhalf * 8];
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        if (s + 1 < KS) {
-#pragma unroll
-          for (int j = 0; j < 2; ++j) fk[(s + 1) & 1][j] = *(const f16x8 *)&sK[buf][32 * j + pi32(l32)][(s + 1) * 16 + lhalf * 8];
-        } else {
-#pragma unroll
-          for (int b = 0; b < DB; ++b) fv[0][b] = *(const f16x8 *)&sVt[buf][32 * b + l32][lhalf * 8];
+            for (int e = 0; e < 16; ++e) sacc[j][e] = bp[32 * j + 16 * (e >> 3) + (e & 7)];
         }
-        __builtin_amdgcn_sched_barrier(0);
+        f16x8 fk[2][2], fv[2][DB];
 #pragma unroll
-        for (int j = 0; j < 2; ++j)
+        for (int j = 0; j < 2; ++j) fk[0][j] = *(const f16x8 *)(kb + j * (32 * DH * 2) + ka0);
 #pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            sacc[qb][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk[s & 1][j], fq[qb][s], sacc[qb][j], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
-      }
-      // ---- P^T = silu(S^T) (the bias is already in the accumulators)
-      const bool need_mask = k0 + KT > wave_vis_min;
-      f16x8 fp[2][4];
+        for (int s = 0; s < KS; ++s) {
+          if (s + 1 < KS) {
 #pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+            for (int j = 0; j < 2; ++j)
+              fk[(s + 1) & 1][j] = *(const f16x8 *)(kb + j * (32 * DH * 2) + (ka0 ^ ((s + 1) << 5)));
+          } else {
+#pragma unroll
+            for (int b = 0; b < DB; ++b) fv[0][b] = *(const f16x8 *)(sb + b * (32 * KT * 2) + vau);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk[s & 1][j], fq[qb][s], sacc[j], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        // ---- P^T = silu(S^T) (the bias is already in the accumulators)
+        f16x8 fp[4];
         bool fast = false;
         {
-          f16x2 yh[2][8], th[2][8];
+          f16x2 th[2][8];
 #pragma unroll
           for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
-              yh[j][i] = f16x2{(half_t)sacc[qb][j][2 * i], (half_t)sacc[qb][j][2 * i + 1]};
-              th[j][i] = yh[j][i] * yh[j][i];
+              const f16x2 yh = f16x2{(half_t)sacc[j][2 * i], (half_t)sacc[j][2 * i + 1]};
+              th[j][i] = yh * yh;
             }
           f16x2 m = th[0][0];
 #pragma unroll
@@ -270,8 +281,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
               float w[16];
 #pragma unroll
               for (int i = 0; i < 8; ++i) {
-                w[2 * i] = __builtin_fmaf((float)th[j][i][0], (float)r[i][0], sacc[qb][j][2 * i]);
-                w[2 * i + 1] = __builtin_fmaf((float)th[j][i][1], (float)r[i][1], sacc[qb][j][2 * i + 1]);
+                w[2 * i] = __builtin_fmaf((float)th[j][i][0], (float)r[i][0], sacc[j][2 * i]);
+                w[2 * i + 1] = __builtin_fmaf((float)th[j][i][1], (float)r[i][1], sacc[j][2 * i + 1]);
               }
               if (need_mask) {
 #pragma unroll
@@ -281,8 +292,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
                 }
               }
               __builtin_amdgcn_sched_barrier(0);
-              fp[qb][2 * j] = pack8(w);
-              fp[qb][2 * j + 1] = pack8(w + 8);
+              fp[2 * j] = pack8(w);
+              fp[2 * j + 1] = pack8(w + 8);
             }
           }
         }
@@ -291,7 +302,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
           for (int j = 0; j < 2; ++j) {
             float p[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) p[e] = silu_half_domain(sacc[qb][j][e]);
+            for (int e = 0; e < 16; ++e) p[e] = silu_half_domain(sacc[j][e]);
             if (need_mask) {
 #pragma unroll
               for (int e = 0; e < 16; ++e) {
@@ -299,33 +310,29 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
                 p[e] = kv < n_vis[qb] ? p[e] : 0.f;
               }
             }
-            fp[qb][2 * j] = pack8(p);
-            fp[qb][2 * j + 1] = pack8(p + 8);
+            fp[2 * j] = pack8(p);
+            fp[2 * j + 1] = pack8(p + 8);
           }
         }
-      }
-      // ---- O^T += V^T P^T; V^T fragments shared by both qb, read one group ahead
+        // ---- O^T += V^T P^T; V^T fragments read one group ahead
 #pragma unroll
-      for (int s2 = 0; s2 < 4; ++s2) {
-        if (s2 + 1 < 4) {
+        for (int s2 = 0; s2 < 4; ++s2) {
+          if (s2 + 1 < 4) {
 #pragma unroll
-          for (int b = 0; b < DB; ++b) fv[(s2 + 1) & 1][b] = *(const f16x8 *)&sVt[buf][32 * b + l32][(s2 + 1) * 16 + lhalf * 8];
+            for (int b = 0; b < DB; ++b)
+              fv[(s2 + 1) & 1][b] = *(const f16x8 *)(sb + b * (32 * KT * 2) + (vau ^ ((s2 + 1) << 5)));
+          }
+          __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+          for (int b = 0; b < DB; ++b)
+            oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv[s2 & 1][b], fp[s2], oacc[qb][b], 0, 0, 0);
+          __builtin_amdgcn_sched_barrier(0);
         }
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int b = 0; b < DB; ++b)
-#pragma unroll
-          for (int qb = 0; qb < 2; ++qb)
-            oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv[s2 & 1][b], fp[qb][s2], oacc[qb][b], 0, 0, 0);
-        __builtin_amdgcn_sched_barrier(0);
       }
     }
-    __builtin_amdgcn_sched_barrier(0);
-    ATTN_STORE_TILE(buf ^ 1);
-    __syncthreads();
+    }
   }
-#undef ATTN_LOAD_TILE
-#undef ATTN_STORE_TILE
+  __builtin_amdgcn_s_barrier();          // everybody has left the last tile: the stages become output patches
 
   // ---- candidates: the row itself is one more key, at distance 0.  Each 32-row block multiplies
   // its candidate rows against themselves and keeps the diagonal.
@@ -362,13 +369,13 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   // ---- write O[q][head*DH + dd]; accumulator element e of block b: dd = 32b + 8*(e/4) + 4*lhalf + e%4.
   // Only two lanes share a query row there (16 contiguous bytes per row and store instruction, and the
   // write path is bound by the number of requests), so each wavefront transposes its 64 x DH patch
-  // through LDS (16-byte chunks XOR-swizzled by row; every wavefront is past the last barrier of the key
+  // through LDS (16-byte chunks XOR-swizzled by row; every wavefront is past the barrier that closes the key
   // loop, nobody reads the tile buffers any more) and stores 16 bytes per lane, a whole head row of
   // 2*DH bytes per group of lanes.
   {
     constexpr int CPR = DH / 8;                       // 16-byte chunks per patch row
     constexpr int RPI = 64 / CPR;                     // patch rows per store instruction
-    char *pb = lds.patch[wave];
+    char *pb = lds + wave * (64 * DH * 2);
     auto pkey = [](int row) { return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };   // spreads 16 rows over 256 bytes
 #pragma unroll
     for (int qb = 0; qb < 2; ++qb) {
