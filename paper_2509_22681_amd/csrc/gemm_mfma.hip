@@ -163,8 +163,14 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   auto main_loop = [&](auto fm) {
     constexpr bool FM = decltype(fm)::value;
     const int nk = K / BK;
+    const int k_rot = (n0 / BN) % nk;              // tied to the output columns, not to the launch's tile numbering
     auto request = [&](int tile, int stage) {            // A_Q + B_Q DMA instructions per wavefront
-      const int kt_ = tile < nk ? tile : nk - 1;
+      // The workgroups that share a row tile (one per column tile) run at the same time on one XCD.  Each walks k
+      // from a different starting tile (rotation by its column tile), so that they touch different lines of the
+      // shared activations at any moment: one of them misses L2 on a line, the others hit it later, instead of
+      // all of them missing together.
+      int kt_ = (tile < nk ? tile : nk - 1) + k_rot;
+      kt_ = kt_ >= nk ? kt_ - nk : kt_;
 #pragma unroll
       for (int q = 0; q < A_Q; ++q)
         __builtin_amdgcn_global_load_lds((gvoid *)(A + aoff[q] + kt_ * a_kstep), (lvoid *)(smem + stage * STAGE + (4 * q + wave) * 1024), 16, 0, 0);
