@@ -9,14 +9,17 @@
 // like a flash-attention tile loop, but the pointwise SiLU needs neither running maximum nor
 // rescaling.
 //
-// Work decomposition: one workgroup = (query tile of 256 rows, head); 4 wavefronts, 64 query rows
-// each (two 32-row MFMA blocks, processed one after the other).  Keys are walked in
-// tiles of 128, processed as two halves of 64.  A tile (K rows, V^T rows and the window of the bias
-// table it needs) is brought into one of two LDS stages by LDS-DMA loads (global_load_lds: no staging
-// registers, no LDS store instructions), requested one tile ahead right after the barrier that opens
-// the current tile: one barrier per 128 keys.  LDS rows are unpadded (a DMA instruction fills 1 KB of
-// consecutive LDS) and 16-byte chunks are XOR-swizzled so that 16 consecutive lanes of a fragment read
-// fall into 16 different slots of the 256 bytes the LDS serves per clock.
+// Work decomposition: one workgroup = (query tile of 128 rows, head); 4 wavefronts of 32 query rows
+// (one 32-row MFMA block each: about 160 registers per lane and 51 KB of LDS per workgroup, so three
+// workgroups = three wavefronts per SIMD fit a CU; the kernel is bound by MFMA + VALU issue, and a third
+// wavefront per SIMD fills part of the issue slots that two leave empty: measured 1.46x from one to two,
+// 1.04x from two to three, the latter net of twice the K/V tile traffic of 256-row query tiles).  Keys
+// are walked in tiles of 64.  A tile (K rows, V^T rows and the window of the bias table it needs) is
+// brought into a ring of three LDS stages by LDS-DMA loads (global_load_lds: no staging registers, no
+// LDS store instructions), requested two tiles ahead right after the barrier that opens the current
+// tile.  LDS rows are unpadded (a DMA instruction fills 1 KB of consecutive LDS) and 16-byte chunks are
+// XOR-swizzled so that 16 consecutive lanes of a fragment read fall into 16 different slots of the 256
+// bytes the LDS serves per clock.
 //
 // Register-level formulation: the products are computed transposed,
 //     S^T[kv][q] = K Q^T      (A operand = K rows, B operand = Q rows)
@@ -44,11 +47,14 @@ namespace flame {
 
 namespace {
 
-constexpr int QT = kAttnQTileBf16;  // query rows per workgroup (4 wavefronts x 64)
-static_assert(QT == 256, "4 wavefronts of 64 query rows");
-constexpr int KT = 128;             // keys per LDS stage
+constexpr int QT = kAttnQTileBf16;  // query rows per workgroup
+constexpr int NW = QT / 32;         // wavefronts per workgroup, 32 query rows each
+static_assert(QT == 128, "4 wavefronts of 32 query rows");
+constexpr int KT = 64;              // keys per LDS stage
+constexpr int NSTAGE = 3;           // LDS stages (ring)
 constexpr int KH = 64;              // keys per half tile (one pass of the register-level loop)
-constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..382
+constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..190
+static_assert(BW <= 64 * NW, "one 64-slot window request per wavefront");
 
 // SiLU for small arguments.  silu(x) - x/2 is even: silu(x) = x/2 + x^2 r(x^2) with
 // r(u) ~ a1 + a3 u + a5 u^2 (weighted least-squares fit of (silu(x) - x/2)/x^2 on [-2, 2], approximation
@@ -74,20 +80,23 @@ __device__ __forceinline__ f16x8 pack8(const float *v) {
 }
 
 template <int DH>
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restrict__ planes, const float *__restrict__ bias_lh,
+__global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__restrict__ planes, const float *__restrict__ bias_lh,
                                                            half_t *__restrict__ O, const AttnItem *__restrict__ items,
                                                            int H, int d, int D, int64_t ws_rows) {
   constexpr int KS = DH / 16;          // k-steps of the Q K^T product
   constexpr int DB = DH / 32;          // 32-row blocks of O^T
   constexpr int KCH = DH / 8;          // 16-byte chunks per K row (8 or 4)
   constexpr int KSH = KCH == 8 ? 1 : 2;            // K rows per 256 bytes = 1 << KSH
-  constexpr int K_BYTES = KT * DH * 2;             // K tile [128 keys][DH]
-  constexpr int V_BYTES = DH * KT * 2;             // V^T tile [DH][128 keys]
-  constexpr int STAGE = K_BYTES + V_BYTES + BW * 4;
+  constexpr int VCH = KT / 8;          // 16-byte chunks per V^T row (16 or 8)
+  constexpr int VSH = VCH == 16 ? 0 : 1;           // V^T rows per 256 bytes = 1 << VSH
+  constexpr int K_BYTES = KT * DH * 2;             // K tile [KT keys][DH]
+  constexpr int V_BYTES = DH * KT * 2;             // V^T tile [DH][KT keys]
+  constexpr int W_BYTES = NW * 256;                // bias window: 64 slots per wavefront (BW <= 64 NW of them are used)
+  constexpr int STAGE = K_BYTES + V_BYTES + W_BYTES;
   static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0 && STAGE % 256 == 0, "stage parts start on 256-byte boundaries");
-  static_assert(4 * 64 * DH * 2 <= 2 * STAGE, "output patches fit in the tile buffers");
-  // two stages; the output patches of the four wavefronts reuse them once the key loop is over
-  __shared__ __attribute__((aligned(256))) char lds[2 * STAGE];
+  static_assert(QT * DH * 2 <= NSTAGE * STAGE, "output patches fit in the tile buffers");
+  // the stages; the output patches of the wavefronts reuse them once the key loop is over
+  __shared__ __attribute__((aligned(256))) char lds[NSTAGE * STAGE];
 
   const int head = blockIdx.x % H;
   const AttnItem it = items[blockIdx.x / H];
@@ -102,32 +111,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   const half_t *Kp = planes + 3 * plane + head * DH;
   const float *bias = bias_lh + (int64_t)head * D;
 
-  // this wavefront's 64 query rows = two 32-row blocks qb = 0, 1
-  const int q_local0 = wave * 64;
+  // this wavefront's 32 query rows
+  const int q_local0 = wave * 32;
   const bool wave_active = q_local0 < it.n_q;
-  int my_q_local[2], n_vis[2];
-  bool row_valid[2];
-  f16x8 fq[2][KS];                     // Q fragments (B operand of S^T): row = my query, k = 16*s + 8*lhalf + 0..7
+  const int my_q_local = q_local0 + l32;
+  const bool row_valid = my_q_local < it.n_q;
+  f16x8 fq[KS];                        // Q fragments (B operand of S^T): row = my query, k = 16*s + 8*lhalf + 0..7
+  int n_vis;
+  {
+    const int64_t row = it.q_row + (row_valid ? my_q_local : it.n_q - 1);   // clamped for loads
+    const int q_index = it.is_cand ? it.L : it.q_pos + my_q_local;
+    n_vis = visible_history(it.is_cand, q_index, it.L);
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb) {
-    my_q_local[qb] = q_local0 + 32 * qb + l32;
-    row_valid[qb] = my_q_local[qb] < it.n_q;
-    const int64_t row = it.q_row + (row_valid[qb] ? my_q_local[qb] : it.n_q - 1);   // clamped for loads
-    const int q_index = it.is_cand ? it.L : it.q_pos + my_q_local[qb];
-    n_vis[qb] = visible_history(it.is_cand, q_index, it.L);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) fq[qb][s] = *(const f16x8 *)(Qp + row * d + s * 16 + lhalf * 8);
+    for (int s = 0; s < KS; ++s) fq[s] = *(const f16x8 *)(Qp + row * d + s * 16 + lhalf * 8);
   }
   const int wave_vis_min = it.is_cand ? it.L : it.q_pos + q_local0 + 1;
-  const int wave_vis_max = it.is_cand ? it.L : it.q_pos + q_local0 + 64;
+  const int wave_vis_max = it.is_cand ? it.L : it.q_pos + q_local0 + 32;
 
-  f32x16 oacc[2][DB];
+  f32x16 oacc[DB];
 #pragma unroll
-  for (int qb = 0; qb < 2; ++qb)
+  for (int b = 0; b < DB; ++b)
 #pragma unroll
-    for (int b = 0; b < DB; ++b)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[qb][b][e] = 0.f;
+    for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
 
   const int n_tiles = (it.n_kv + KT - 1) / KT;
   const int q_first = it.is_cand ? it.L : it.q_pos;     // position of query row 0 of the workgroup tile
@@ -135,54 +140,54 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   // ---- LDS-DMA sources.  One instruction of a wavefront fills 1 KB of LDS, lane p at byte 16 p.
   // K tile: 1 KB = 64 / KCH rows; lane p owns physical chunk p % KCH of row p / KCH and fetches the logical
   // chunk the swizzle maps there (chunk ^ key, key = row bits above the rows that share 256 bytes).
-  // V^T tile: 1 KB = 4 feature rows of 256 bytes; physical chunk p % 16 of row p / 16, key = row % 16.
+  // V^T tile: 1 KB = 64 / VCH feature rows of 2 KT bytes, same scheme.
   // Instruction I = wave + 4 i of either tile belongs to this wavefront.
   typedef __attribute__((address_space(1))) const void gvoid;
   typedef __attribute__((address_space(3))) void lvoid;
-  constexpr int NKI = KCH / 2, NVI = DH / 16;         // instructions per wavefront and tile
-  // Instruction i of a wavefront covers rows 4 i * (64 / KCH) (K) or 16 i (V^T) further down; those steps leave
-  // the swizzle keys unchanged, so one lane pointer per tile kind plus scalar offsets is enough.  The lane
-  // pointers are recomputed at every request (a few dozen instructions per 128 keys) from an opaque copy of
-  // the lane index: kept across the key loop they would be spilled, and their reloads would have to wait for
-  // the requests issued just before.
-  // bias window: slot u = tid (all wavefronts) and u = 256 + tid (wavefronts 0 and 1), 4 bytes per lane
+  // Instruction I of a tile belongs to wavefront I % NW.  The lane pointers are recomputed at every
+  // request (a few dozen instructions per 128 keys) from an opaque copy of the lane index: kept across the
+  // key loop they would be spilled, and their reloads would have to wait for the requests issued just before.
+  // Bias window: slots 64 w .. 64 w + 63 by wavefront w < BW / 64, 4 bytes per lane.
+  constexpr int NKI = K_BYTES / 1024, NVI = V_BYTES / 1024;
+  static_assert(NKI % NW == 0 && NVI % NW == 0, "every wavefront issues the same number of requests per tile");
+  constexpr int REQ = NKI / NW + NVI / NW + 1;       // requests per wavefront and tile
   auto request_tile = [&](int t, int stage) {
     char *sb = lds + stage * STAGE;
     const int k0_ = t * KT;
     int ln = lane;
     int64_t wsr = ws_rows;
     asm volatile("" : "+v"(ln), "+s"(wsr));
-    {
-      const int row = wave * (64 / KCH) + ln / KCH;
-      const int c = (ln % KCH) ^ ((row >> KSH) & (KCH - 1));
-      const half_t *g = Kp + (int64_t)(it.kv_row + k0_ + row) * d + c * 8;
 #pragma unroll
-      for (int i = 0; i < NKI; ++i)
-        __builtin_amdgcn_global_load_lds((gvoid *)(g + (int64_t)(4 * i * (64 / KCH)) * d), (lvoid *)(sb + (wave + 4 * i) * 1024), 16, 0, 0);
+    for (int i = 0; i < (NKI + NW - 1) / NW; ++i) {
+      const int I = wave + NW * i;
+      if (I < NKI) {
+        const int row = I * (64 / KCH) + ln / KCH;
+        const int c = (ln % KCH) ^ ((row >> KSH) & (KCH - 1));
+        __builtin_amdgcn_global_load_lds((gvoid *)(Kp + (int64_t)(it.kv_row + k0_ + row) * d + c * 8), (lvoid *)(sb + I * 1024), 16, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < (NVI + NW - 1) / NW; ++i) {
+      const int I = wave + NW * i;
+      if (I < NVI) {
+        const int row = I * (64 / VCH) + ln / VCH;
+        const int c = (ln % VCH) ^ ((row >> VSH) & (VCH - 1));
+        __builtin_amdgcn_global_load_lds((gvoid *)(Vt + (int64_t)row * wsr + (it.kv_row + k0_) + c * 8), (lvoid *)(sb + K_BYTES + I * 1024), 16, 0, 0);
+      }
     }
     {
-      const int row = wave * 4 + (ln >> 4);
-      const int c = (ln & 15) ^ (row & 15);
-      const half_t *g = Vt + (int64_t)row * wsr + (it.kv_row + k0_) + c * 8;
-#pragma unroll
-      for (int i = 0; i < NVI; ++i)
-        __builtin_amdgcn_global_load_lds((gvoid *)(g + (int64_t)(16 * i) * wsr), (lvoid *)(sb + K_BYTES + (wave + 4 * i) * 1024), 16, 0, 0);
+      // every wavefront issues one window request, so that all of them have the same number of requests in
+      // flight per tile (slots past the window are filled too and never read)
+      int dl_ = q_first + (QT - 1) - (wave * 64 + ln) - k0_;   // distance held by window slot 64 w + lane
+      dl_ = dl_ < 0 ? 0 : (dl_ > D - 1 ? D - 1 : dl_);
+      __builtin_amdgcn_global_load_lds((gvoid *)(bias + dl_), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
     }
-    int dl_ = q_first + (QT - 1) - (wave * 64 + ln) - k0_;     // distance held by window slot tid
-    int dh_ = dl_ - 256;
-    dl_ = dl_ < 0 ? 0 : (dl_ > D - 1 ? D - 1 : dl_);
-    dh_ = dh_ < 0 ? 0 : (dh_ > D - 1 ? D - 1 : dh_);
-    __builtin_amdgcn_global_load_lds((gvoid *)(bias + dl_), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
-    if (wave < (BW - 256) / 64)
-      __builtin_amdgcn_global_load_lds((gvoid *)(bias + dh_), (lvoid *)(sb + K_BYTES + V_BYTES + 1024 + wave * 256), 4, 0, 0);
   };
 
-  // Window slot of (my row of block qb, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's
-  // index in the workgroup tile (0 for candidate rows: they all sit at the same distance from a
-  // key); keys further right sit at increasing slots.
-  int bias_idx[2];
-#pragma unroll
-  for (int qb = 0; qb < 2; ++qb) bias_idx[qb] = (QT - 1) - (it.is_cand ? 0 : my_q_local[qb]) + 8 * lhalf;
+  // Window slot of (my row, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's index in the
+  // workgroup tile (0 for candidate rows: they all sit at the same distance from a key); keys further
+  // right sit at increasing slots.
+  const int bias_idx = (QT - 1) - (it.is_cand ? 0 : my_q_local) + 8 * lhalf;
   // fragment byte offsets inside a stage.  K (A operand of S^T): MFMA row m takes key pi32(m); per 32-key
   // block j the row advances by 32 (key bits 0..4 unchanged, so the swizzle key is the same).  V^T (A
   // operand of O^T): row = feature 32 b + l32, chunk = key / 8.
@@ -190,17 +195,28 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
   // (row base | key << 4) ^ (c << 4): one XOR with a constant per fragment.
   const int krow = pi32(l32);
   const int ka0 = (krow * (DH * 2)) | (((((krow >> KSH) & (KCH - 1)) ^ lhalf) << 4));
-  const int va0 = (K_BYTES + l32 * (KT * 2)) | ((((l32 & 15) ^ lhalf) << 4));
+  const int va0 = (K_BYTES + l32 * (KT * 2)) | (((((l32 >> VSH) & (VCH - 1)) ^ lhalf) << 4));
 
-  if (n_tiles > 0) request_tile(0, 0);
-
+  // Ring of NSTAGE = 3 stages, requests two tiles ahead.  Past the last tile the requests repeat the last
+  // tile (into a free stage), so that "at most REQ requests outstanding" always means "tile t has landed".
+  if (n_tiles > 0) {
+    request_tile(0, 0);
+    request_tile(n_tiles > 1 ? 1 : 0, 1);
+  }
+  int st = 0;
   for (int t = 0; t < n_tiles; ++t) {
-    const char *sb = lds + (t & 1) * STAGE;
+    const char *sb = lds + st * STAGE;
     // tile t has landed for this wavefront; past the barrier it has landed for all of them, and everybody
     // has left tile t-1, whose stage the next request overwrites
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    if (REQ == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
+    else if (REQ == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    if (t + 1 < n_tiles) request_tile(t + 1, (t + 1) & 1);
+    {
+      const int st2 = st + 2 >= NSTAGE ? st + 2 - NSTAGE : st + 2;
+      request_tile(t + 2 < n_tiles ? t + 2 : n_tiles - 1, st2);
+    }
+    st = st + 1 >= NSTAGE ? 0 : st + 1;
     __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
 #pragma unroll 1
     for (int u = 0; u < KT / KH; ++u) {
@@ -209,11 +225,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
       const char *kb = sb + u * (KH * DH * 2);                 // K rows of this half tile
       const int vau = va0 ^ (u << 7);                          // V^T: chunks 8 u .. 8 u + 7 of each row
       const bool need_mask = k0 + KH > wave_vis_min;
-      // The two 32-row query blocks of the wavefront go through the half tile one after the other (each
-      // reads its own K and V^T fragments: the LDS has the bandwidth, the register file has no room for
-      // the accumulators of both).
-#pragma unroll
-      for (int qb = 0; qb < 2; ++qb) {
+      {
         // ---- S^T = K Q^T: blocks [j], j = 32-key half of the half tile.  Fragment reads run one group
         // ahead of the MFMAs that use them (and the first V^T group is fetched behind the last K group),
         // so LDS latency hides behind matrix work instead of being paid once per group.
@@ -222,7 +234,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
           // one address register, the 32 reads use immediate offsets (the empty asm keeps the compiler
           // from folding constant parts of the address into every read as a separate add)
           typedef const __attribute__((address_space(3))) float *lds_cfloat;
-          lds_cfloat bp = (lds_cfloat)(sb + K_BYTES + V_BYTES) + (bias_idx[qb] + u * KH);
+          lds_cfloat bp = (lds_cfloat)(sb + K_BYTES + V_BYTES) + (bias_idx + u * KH);
           asm volatile("" : "+v"(bp));
 #pragma unroll
           for (int j = 0; j < 2; ++j)
@@ -245,7 +257,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int j = 0; j < 2; ++j)
-            sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk[s & 1][j], fq[qb][s], sacc[j], 0, 0, 0);
+            sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk[s & 1][j], fq[s], sacc[j], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
         // ---- P^T = silu(S^T) (the bias is already in the accumulators)
@@ -288,7 +300,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                   const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-                  w[e] = kv < n_vis[qb] ? w[e] : 0.f;
+                  w[e] = kv < n_vis ? w[e] : 0.f;
                 }
               }
               __builtin_amdgcn_sched_barrier(0);
@@ -307,7 +319,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
 #pragma unroll
               for (int e = 0; e < 16; ++e) {
                 const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-                p[e] = kv < n_vis[qb] ? p[e] : 0.f;
+                p[e] = kv < n_vis ? p[e] : 0.f;
               }
             }
             fp[2 * j] = pack8(p);
@@ -325,76 +337,70 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const half_t *__restr
           __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
           for (int b = 0; b < DB; ++b)
-            oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv[s2 & 1][b], fp[s2], oacc[qb][b], 0, 0, 0);
+            oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv[s2 & 1][b], fp[s2], oacc[b], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
     }
     }
   }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated requests of the tail have landed
   __builtin_amdgcn_s_barrier();          // everybody has left the last tile: the stages become output patches
 
-  // ---- candidates: the row itself is one more key, at distance 0.  Each 32-row block multiplies
-  // its candidate rows against themselves and keeps the diagonal.
+  // ---- candidates: the row itself is one more key, at distance 0.  The wavefront multiplies its 32
+  // candidate rows against themselves and keeps the diagonal.
   if (it.is_cand && wave_active) {
     const float b0 = bias[0];
+    const int64_t base_row = it.q_row + q_local0;   // multiple of 32 inside the padded workspace
+    f32x16 sacc;
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int64_t base_row = it.q_row + q_local0 + 32 * qb;   // multiple of 32 inside the padded workspace
-      f32x16 sacc;
+    for (int e = 0; e < 16; ++e) sacc[e] = b0;
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[e] = b0;
-#pragma unroll
-      for (int s = 0; s < KS; ++s) {
-        const f16x8 fk = *(const f16x8 *)(Kp + (base_row + pi32(l32)) * d + s * 16 + lhalf * 8);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[qb][s], sacc, 0, 0, 0);
-      }
-      float p[16];
-#pragma unroll
-      for (int e = 0; e < 16; ++e) {
-        const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
-        p[e] = (kv_local == l32 && row_valid[qb]) ? silu_half_domain(sacc[e]) : 0.f;
-      }
-      const f16x8 fps[2] = {pack8(p), pack8(p + 8)};
-#pragma unroll
-      for (int s2 = 0; s2 < 2; ++s2)
-#pragma unroll
-        for (int b = 0; b < DB; ++b) {
-          const f16x8 fv = *(const f16x8 *)(Vt + (int64_t)(32 * b + l32) * ws_rows + base_row + s2 * 16 + lhalf * 8);
-          oacc[qb][b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fps[s2], oacc[qb][b], 0, 0, 0);
-        }
+    for (int s = 0; s < KS; ++s) {
+      const f16x8 fk = *(const f16x8 *)(Kp + (base_row + pi32(l32)) * d + s * 16 + lhalf * 8);
+      sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sacc, 0, 0, 0);
     }
+    float p[16];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
+      p[e] = (kv_local == l32 && row_valid) ? silu_half_domain(sacc[e]) : 0.f;
+    }
+    const f16x8 fps[2] = {pack8(p), pack8(p + 8)};
+#pragma unroll
+    for (int s2 = 0; s2 < 2; ++s2)
+#pragma unroll
+      for (int b = 0; b < DB; ++b) {
+        const f16x8 fv = *(const f16x8 *)(Vt + (int64_t)(32 * b + l32) * ws_rows + base_row + s2 * 16 + lhalf * 8);
+        oacc[b] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fv, fps[s2], oacc[b], 0, 0, 0);
+      }
   }
 
   // ---- write O[q][head*DH + dd]; accumulator element e of block b: dd = 32b + 8*(e/4) + 4*lhalf + e%4.
   // Only two lanes share a query row there (16 contiguous bytes per row and store instruction, and the
-  // write path is bound by the number of requests), so each wavefront transposes its 64 x DH patch
+  // write path is bound by the number of requests), so each wavefront transposes its 32 x DH patch
   // through LDS (16-byte chunks XOR-swizzled by row; every wavefront is past the barrier that closes the key
   // loop, nobody reads the tile buffers any more) and stores 16 bytes per lane, a whole head row of
   // 2*DH bytes per group of lanes.
   {
     constexpr int CPR = DH / 8;                       // 16-byte chunks per patch row
     constexpr int RPI = 64 / CPR;                     // patch rows per store instruction
-    char *pb = lds + wave * (64 * DH * 2);
+    char *pb = lds + wave * (32 * DH * 2);
     auto pkey = [](int row) { return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };   // spreads 16 rows over 256 bytes
 #pragma unroll
-    for (int qb = 0; qb < 2; ++qb) {
-      const int row = 32 * qb + l32;
+    for (int b = 0; b < DB; ++b)
 #pragma unroll
-      for (int b = 0; b < DB; ++b)
+      for (int g = 0; g < 4; ++g) {
+        f16x4 v;
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-          f16x4 v;
-#pragma unroll
-          for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[qb][b][4 * g + i]);
-          const int c = 4 * b + g;
-          *(f16x4 *)(pb + row * (DH * 2) + ((c ^ pkey(row)) << 4) + 8 * lhalf) = v;
-        }
-    }
+        for (int i = 0; i < 4; ++i) v[i] = to_f16_sat(oacc[b][4 * g + i]);
+        const int c = 4 * b + g;
+        *(f16x4 *)(pb + l32 * (DH * 2) + ((c ^ pkey(l32)) << 4) + 8 * lhalf) = v;
+      }
     const int rl = lane / CPR, c = lane % CPR;
     half_t *obase = O + (int64_t)it.q_row * d + head * DH + c * 8;
 #pragma unroll
-    for (int t = 0; t < 64 / RPI; ++t) {
+    for (int t = 0; t < 32 / RPI; ++t) {
       const int row = t * RPI + rl;
       const f16x8 v = *(const f16x8 *)(pb + row * (DH * 2) + ((c ^ pkey(row)) << 4));
       if (q_local0 + row < it.n_q) *(f16x8 *)(obase + (int64_t)(q_local0 + row) * d) = v;
@@ -408,7 +414,7 @@ void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const A
                       const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   const int grid = n_items * sh.H;
-#define ATTN_CASE(DHV) attn_mfma_kernel<DHV><<<grid, 256, 0, s>>>((const half_t *)planes, bias_lh, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
+#define ATTN_CASE(DHV) attn_mfma_kernel<DHV><<<grid, 64 * NW, 0, s>>>((const half_t *)planes, bias_lh, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
   if (sh.dh == 32) ATTN_CASE(32);
   else ATTN_CASE(64);
 #undef ATTN_CASE

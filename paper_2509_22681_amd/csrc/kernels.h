@@ -68,7 +68,7 @@ void launch_k3_fused(const void *O, const void *U, const void *gamma, const void
                      float *X, void *Xh, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first,
                      const Shape &sh, hipStream_t s);
 
-constexpr int kAttnQTileBf16 = 256;  // query rows per attention work item, MFMA path
+constexpr int kAttnQTileBf16 = 128;  // query rows per attention work item, MFMA path
 constexpr int kAttnQTileF32 = 64;    // fp32 path
 
 }  // namespace flame
