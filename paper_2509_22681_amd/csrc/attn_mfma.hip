@@ -145,7 +145,7 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
   typedef __attribute__((address_space(1))) const void gvoid;
   typedef __attribute__((address_space(3))) void lvoid;
   // Instruction I of a tile belongs to wavefront I % NW.  The lane pointers are recomputed at every
-  // request (a few dozen instructions per 128 keys) from an opaque copy of the lane index: kept across the
+  // request (a few dozen instructions per tile) from an opaque copy of the lane index: kept across the
   // key loop they would be spilled, and their reloads would have to wait for the requests issued just before.
   // Bias window: slots 64 w .. 64 w + 63 by wavefront w < BW / 64, 4 bytes per lane.
   constexpr int NKI = K_BYTES / 1024, NVI = V_BYTES / 1024;
