@@ -144,44 +144,42 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
   // Instruction I = wave + 4 i of either tile belongs to this wavefront.
   typedef __attribute__((address_space(1))) const void gvoid;
   typedef __attribute__((address_space(3))) void lvoid;
-  // Instruction I of a tile belongs to wavefront I % NW.  The lane pointers are recomputed at every
-  // request (a few dozen instructions per tile) from an opaque copy of the lane index: kept across the
-  // key loop they would be spilled, and their reloads would have to wait for the requests issued just before.
-  // Bias window: slots 64 w .. 64 w + 63 by wavefront w < BW / 64, 4 bytes per lane.
+  // Instruction I of a tile belongs to wavefront I % NW; going from I to I + NW leaves the swizzle key
+  // unchanged, so a wavefront keeps one lane pointer per tile kind (for the tile to request next) and adds
+  // scalar offsets for its further instructions.  Bias window: slots 64 w .. 64 w + 63 by wavefront w.
   constexpr int NKI = K_BYTES / 1024, NVI = V_BYTES / 1024;
   static_assert(NKI % NW == 0 && NVI % NW == 0, "every wavefront issues the same number of requests per tile");
+  static_assert((NW * (64 / KCH)) % (KCH << KSH) == 0 && (NW * (64 / VCH)) % (VCH << VSH) == 0, "swizzle keys do not depend on the instruction");
   constexpr int REQ = NKI / NW + NVI / NW + 1;       // requests per wavefront and tile
-  auto request_tile = [&](int t, int stage) {
+  const half_t *pK, *pV;
+  int dW = q_first + (QT - 1) - (wave * 64 + lane);   // distance held by window slot 64 w + lane, next tile
+  {
+    const int row = wave * (64 / KCH) + lane / KCH;
+    const int c = (lane % KCH) ^ ((row >> KSH) & (KCH - 1));
+    pK = Kp + (int64_t)(it.kv_row + row) * d + c * 8;
+  }
+  {
+    const int row = wave * (64 / VCH) + lane / VCH;
+    const int c = (lane % VCH) ^ ((row >> VSH) & (VCH - 1));
+    pV = Vt + (int64_t)row * ws_rows + it.kv_row + c * 8;
+  }
+  auto request_tile = [&](int stage) {
     char *sb = lds + stage * STAGE;
-    const int k0_ = t * KT;
-    int ln = lane;
-    int64_t wsr = ws_rows;
-    asm volatile("" : "+v"(ln), "+s"(wsr));
 #pragma unroll
-    for (int i = 0; i < (NKI + NW - 1) / NW; ++i) {
-      const int I = wave + NW * i;
-      if (I < NKI) {
-        const int row = I * (64 / KCH) + ln / KCH;
-        const int c = (ln % KCH) ^ ((row >> KSH) & (KCH - 1));
-        __builtin_amdgcn_global_load_lds((gvoid *)(Kp + (int64_t)(it.kv_row + k0_ + row) * d + c * 8), (lvoid *)(sb + I * 1024), 16, 0, 0);
-      }
-    }
+    for (int i = 0; i < NKI / NW; ++i)
+      __builtin_amdgcn_global_load_lds((gvoid *)(pK + (int64_t)(i * NW * (64 / KCH)) * d), (lvoid *)(sb + (wave + NW * i) * 1024), 16, 0, 0);
 #pragma unroll
-    for (int i = 0; i < (NVI + NW - 1) / NW; ++i) {
-      const int I = wave + NW * i;
-      if (I < NVI) {
-        const int row = I * (64 / VCH) + ln / VCH;
-        const int c = (ln % VCH) ^ ((row >> VSH) & (VCH - 1));
-        __builtin_amdgcn_global_load_lds((gvoid *)(Vt + (int64_t)row * wsr + (it.kv_row + k0_) + c * 8), (lvoid *)(sb + K_BYTES + I * 1024), 16, 0, 0);
-      }
-    }
-    {
-      // every wavefront issues one window request, so that all of them have the same number of requests in
-      // flight per tile (slots past the window are filled too and never read)
-      int dl_ = q_first + (QT - 1) - (wave * 64 + ln) - k0_;   // distance held by window slot 64 w + lane
-      dl_ = dl_ < 0 ? 0 : (dl_ > D - 1 ? D - 1 : dl_);
-      __builtin_amdgcn_global_load_lds((gvoid *)(bias + dl_), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
-    }
+    for (int i = 0; i < NVI / NW; ++i)
+      __builtin_amdgcn_global_load_lds((gvoid *)(pV + (int64_t)(i * NW * (64 / VCH)) * ws_rows), (lvoid *)(sb + K_BYTES + (wave + NW * i) * 1024), 16, 0, 0);
+    // every wavefront issues one window request, so that all of them have the same number of requests in
+    // flight per tile (slots past the window are filled too and never read)
+    const int dl_ = dW < 0 ? 0 : (dW > D - 1 ? D - 1 : dW);
+    __builtin_amdgcn_global_load_lds((gvoid *)(bias + dl_), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
+  };
+  auto next_tile = [&]() {
+    pK += (int64_t)KT * d;
+    pV += KT;
+    dW -= KT;
   };
 
   // Window slot of (my row, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's index in the
@@ -200,8 +198,9 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
   // Ring of NSTAGE = 3 stages, requests two tiles ahead.  Past the last tile the requests repeat the last
   // tile (into a free stage), so that "at most REQ requests outstanding" always means "tile t has landed".
   if (n_tiles > 0) {
-    request_tile(0, 0);
-    request_tile(n_tiles > 1 ? 1 : 0, 1);
+    request_tile(0);
+    if (n_tiles > 1) next_tile();
+    request_tile(1);
   }
   int st = 0;
   for (int t = 0; t < n_tiles; ++t) {
@@ -214,7 +213,8 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
     __builtin_amdgcn_s_barrier();
     {
       const int st2 = st + 2 >= NSTAGE ? st + 2 - NSTAGE : st + 2;
-      request_tile(t + 2 < n_tiles ? t + 2 : n_tiles - 1, st2);
+      if (t + 2 < n_tiles) next_tile();
+      request_tile(st2);
     }
     st = st + 1 >= NSTAGE ? 0 : st + 1;
     __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
