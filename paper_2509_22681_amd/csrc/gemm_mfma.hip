@@ -133,19 +133,41 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   const int a_kstep = a_blocked ? 64 * BK : BK;
   const half_t *Wn0 = W + (int64_t)n0 * K;            // n0 % 64 == 0: a block boundary
   const int boff = rloc * 32 + dch * 8;
-  f32x16 acc[MB][NB];
-#pragma unroll
-  for (int i = 0; i < MB; ++i)
-#pragma unroll
-    for (int j = 0; j < NB; ++j)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
-
   // Operand order.  Row-major outputs (U, Q, K planes, X) want each lane to hold 4 consecutive
   // features of one token, which is the transposed accumulator: W rows as the A operand.  The V
   // plane is stored feature-major for the attention kernel (V^T is its A operand) and wants 4
   // consecutive tokens of one feature: activations as the A operand.
   const bool feature_major = (EPI == 0) && plane == 1;
+  // Accumulators.  In the projection (EPI 0) they start from the bias, which then costs no instruction per
+  // output: accumulator element e of block (i, j) is feature 32 j + 16 lhalf + e of the wavefront's columns
+  // in the row-major planes, and feature 32 j + l32 (all elements alike) in the feature-major plane.
+  f32x16 acc[MB][NB];
+  if (EPI == 0) {
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+      const bf16_t *bp = bias + plane * d + n_in_plane + wn * WN + 32 * j;
+      if (!feature_major) {
+        const bf16x8 b0v = *(const bf16x8 *)(bp + 16 * lhalf), b1v = *(const bf16x8 *)(bp + 16 * lhalf + 8);
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[i][j][e] = (float)(e < 8 ? b0v[e & 7] : b1v[e & 7]);
+      } else {
+        const float bv = to_f32(bp[l32]);
+#pragma unroll
+        for (int i = 0; i < MB; ++i)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) acc[i][j][e] = bv;
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < MB; ++i)
+#pragma unroll
+      for (int j = 0; j < NB; ++j)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+  }
   // fragment byte offsets inside a stage for the two 16-deep steps (32-row blocks are 2048 bytes apart);
   // the operand that plays A is read in sigma32 row order
   int f0[2], g0[2];
@@ -239,27 +261,33 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     char *pb = smem + wave * (128 * WN * 2);
     half_t *P = planes + (int64_t)plane * ws_rows * d;
     if (!feature_major) {
-      // patch[128 tokens][WN features]; lane holds token 32i + l32, features 32j + 16*lhalf + 0..15.
-      // Q leaves this kernel multiplied by alpha / 2: the attention kernel works on halved logits.
+      // patch[128 tokens][WN features]; lane holds token 32i + l32, features 32j + 16*lhalf + 0..15
+      // (the bias is already in the accumulators).  Q leaves this kernel multiplied by alpha / 2: the
+      // attention kernel works on halved logits; the other planes are stored plain.
       constexpr int CPR = WN / 8;                     // 16-byte chunks per patch row
-      const float sc = plane == 2 ? alpha * 0.5f : 1.0f;
-      const bf16_t *brow = bias + plane * d + n_in_plane + wn * WN + 16 * lhalf;
+      auto to_patch = [&](auto scaled) {
+        const float sc = alpha * 0.5f;
 #pragma unroll
-      for (int j = 0; j < NB; ++j) {
-        const bf16x8 bv0 = *(const bf16x8 *)(brow + 32 * j), bv1 = *(const bf16x8 *)(brow + 32 * j + 8);
+        for (int j = 0; j < NB; ++j) {
 #pragma unroll
-        for (int i = 0; i < MB; ++i) {
-          const int row = 32 * i + l32;
+          for (int i = 0; i < MB; ++i) {
+            const int row = 32 * i + l32;
 #pragma unroll
-          for (int g = 0; g < 2; ++g) {
-            f16x8 o;
+            for (int g = 0; g < 2; ++g) {
+              f16x8 o;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + (float)(g ? bv1[q] : bv0[q])) * sc);
-            const int c = 4 * j + 2 * lhalf + g;
-            *(f16x8 *)(pb + row * (WN * 2) + ((c ^ patch_key<CPR>(row)) << 4)) = o;
+              for (int q = 0; q < 8; ++q) {
+                const float w = silu_fast(acc[i][j][8 * g + q]);
+                o[q] = to_f16_sat(decltype(scaled)::value ? w * sc : w);
+              }
+              const int c = 4 * j + 2 * lhalf + g;
+              *(f16x8 *)(pb + row * (WN * 2) + ((c ^ patch_key<CPR>(row)) << 4)) = o;
+            }
           }
         }
-      }
+      };
+      if (plane == 2) to_patch(std::true_type{});
+      else to_patch(std::false_type{});
       constexpr int RPI = 64 / CPR;                   // patch rows per store instruction
       const int rl = lane / CPR, c = lane % CPR;
       half_t *pcol = P + n_in_plane + wn * WN + c * 8;
@@ -272,10 +300,8 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
       }
     } else {
       // patch[WN features][128 tokens]; lane holds feature 32j + l32, tokens 32i + 16*lhalf + 0..15
-      const bf16_t *bcol = bias + plane * d + n_in_plane + wn * WN + l32;
 #pragma unroll
       for (int j = 0; j < NB; ++j) {
-        const float bv = to_f32(bcol[32 * j]);
         const int fr = 32 * j + l32;
 #pragma unroll
         for (int i = 0; i < MB; ++i) {
@@ -283,7 +309,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
           for (int g = 0; g < 2; ++g) {
             f16x8 o;
 #pragma unroll
-            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q] + bv));
+            for (int q = 0; q < 8; ++q) o[q] = to_f16_sat(silu_fast(acc[i][j][8 * g + q]));
             const int c = 4 * i + 2 * lhalf + g;
             *(f16x8 *)(pb + fr * 256 + (((c ^ fr) & 15) << 4)) = o;
           }
