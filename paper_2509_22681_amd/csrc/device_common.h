@@ -52,7 +52,8 @@ constexpr float kLn2 = 0.6931471805599453f;
 // its logits in this form (the factor 1/2 is folded into Q and into the bias table, both exactly):
 // silu(x) = x/2 + x^2 r(x^2) then starts from the logit itself, see the polynomial route there.
 __device__ __forceinline__ float silu_half_domain(float s) {
-  return (2.0f * s) * __builtin_amdgcn_rcpf(1.0f + __builtin_amdgcn_exp2f(s * (-2.0f * kLog2e)));
+  // x / (1 + e^-x) = s / (1/2 + 2^(-2 log2(e) s - 1)): fma, exp2, add, rcp, mul
+  return s * __builtin_amdgcn_rcpf(0.5f + __builtin_amdgcn_exp2f(__builtin_fmaf(s, -2.0f * kLog2e, -1.0f)));
 }
 
 // "k-tile blocked" layout of the fp16 GEMM operands (the activation copy Xh and the converted weight
