@@ -78,11 +78,12 @@ def oracle_all(wl, stages=None):
                           wl.cand_offsets, stages)
 
 
-def stress(L, M, d, H, dtype, *, layers=2, nb=16, D=None, seed=7, name="stress", hot=True):
+def stress(L, M, d, H, dtype, *, layers=2, nb=16, D=None, seed=7, name="stress", hot=True, attn_scale=1.0):
     if hot:   # pre-activations of order +-5: exercises the SiLU tails, the bias and the affine terms
         return W.make_custom(L, M, d=d, H=H, n_layers=layers, n_buckets=nb, max_rel_dist=D, dtype=dtype, seed=seed,
-                             emb_std=1.0, rab_std=1.0, bias_amp=0.1, affine_random=True, name=name)
-    return W.make_custom(L, M, d=d, H=H, n_layers=layers, n_buckets=nb, max_rel_dist=D, dtype=dtype, seed=seed, name=name)
+                             emb_std=1.0, rab_std=1.0, bias_amp=0.1, affine_random=True, attn_scale=attn_scale, name=name)
+    return W.make_custom(L, M, d=d, H=H, n_layers=layers, n_buckets=nb, max_rel_dist=D, dtype=dtype, seed=seed,
+                         attn_scale=attn_scale, name=name)
 
 
 STRESS = {
@@ -94,6 +95,11 @@ STRESS = {
     "S3": dict(L=[700], M=[130], d=128, H=2, nb=16, D=1024),
     # several ragged requests around the tile sizes
     "S4": dict(L=[65, 127, 129, 3, 257, 300], M=[1, 63, 65, 200, 255, 257], d=128, H=2, nb=32, D=128),
+    # d not a multiple of 128 (64-wide GEMM tiles, unfused LN-gate + output projection) with head width 64,
+    # and an attention scale that is no power of two
+    "S5": dict(L=[200, 77, 0], M=[33, 100, 9], d=192, H=3, nb=32, D=256, attn_scale=0.3),
+    # head width 32 on the 128-wide GEMM tiles and the fused K3 (d = 256, 8 heads), three layers
+    "S6": dict(L=[150, 64], M=[70, 128], d=256, H=8, nb=16, D=256, layers=3, attn_scale=0.75),
 }
 
 
