@@ -69,6 +69,9 @@ typedef struct {
   int32_t n_streams;         /* 0 or 1 = everything on the caller's stream; k > 1 = requests are
                                 partitioned into k cost-balanced groups that run on k internal
                                 streams, joined to the caller's stream by events (Section 3.3) */
+  int32_t kv_cache;          /* 0 = one-pass forward only; 1 = also allocate per-layer U/V/Q/K workspaces
+                                (n_layers times the one-pass amount) so that flame_gr_prefill and
+                                flame_gr_score can keep the history keys and values of every layer */
 } flame_gr_config;
 
 /* Model weights: device pointers, caller-owned, read-only, element type = config.dtype unless
@@ -111,6 +114,40 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *weights,
                      const void *cand_emb, const int32_t *cand_offsets,
                      int32_t n_requests, float *scores, void *stream);
 
+/* Two-stage scoring with a history key/value cache: the paradigm that Section 5 leaves for future
+ * work, expecting it to pay for long contexts and larger models.  Because a history row never looks
+ * at a candidate (mask of Section 3.2), the history part of every layer does not depend on the
+ * candidates: flame_gr_prefill runs it once and keeps K and V of the history rows of every layer on
+ * the device, and flame_gr_score then runs only the candidate rows against them, as often as the
+ * caller has candidate batches for the same users.  Scores equal those of flame_gr_forward on the
+ * same inputs bit for bit.  Needs a handle created with kv_cache = 1 and dtype FLAME_GR_BF16
+ * (UNSUPPORTED otherwise).
+ *
+ * flame_gr_prefill
+ *   history_emb, history_offsets, n_requests, stream   as in flame_gr_forward
+ *   cand_capacity    HOST int32 [n_requests]: the largest candidate count that a later
+ *                    flame_gr_score may bring for each request (rows are reserved for it; the
+ *                    capacity checks of create apply to L_i + cand_capacity[i], and a request is
+ *                    never split: L_i + cand_capacity[i] above a non-zero max_seq_tokens is
+ *                    UNSUPPORTED)
+ * The cache belongs to the handle and is replaced by the next flame_gr_prefill; a
+ * flame_gr_forward on the same handle invalidates it. */
+int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *weights, const void *history_emb,
+                     const int32_t *history_offsets, const int32_t *cand_capacity, int32_t n_requests,
+                     void *stream);
+
+/* flame_gr_score: score candidates of the requests of the last flame_gr_prefill on this handle.
+ *   weights          the same weights as at prefill (device contents unchanged since then)
+ *   cand_emb         device [sum M_i][d]
+ *   cand_offsets     HOST   int32 [n_requests+1], M_i <= cand_capacity[i]; M_i = 0 is legal
+ *   n_requests       must equal that of the prefill
+ *   scores           device fp32 [sum M_i]
+ * May be called any number of times after one prefill; calls are serialised on the device like
+ * forwards.  Errors: as flame_gr_forward, plus INVALID_ARGUMENT when no prefill is valid or
+ * n_requests differs, CAPACITY_EXCEEDED when M_i exceeds its reserved capacity. */
+int flame_gr_score(flame_gr_t *h, const flame_gr_weights *weights, const void *cand_emb,
+                   const int32_t *cand_offsets, int32_t n_requests, float *scores, void *stream);
+
 /* Release the handle and its workspaces (synchronises the device work of the handle first).
  * NULL is a no-op that returns 0. */
 int flame_gr_destroy(flame_gr_t *h);
@@ -146,6 +183,15 @@ int flame_gr_host_mask(int32_t L, int32_t M, int32_t n_buckets, int32_t max_rel_
 int flame_gr_host_plan(const flame_gr_config *cfg, const int32_t *history_offsets,
                        const int32_t *cand_offsets, int32_t n_requests, int32_t *tok_off,
                        int32_t *n_segments, int32_t *seg, int32_t cap_segments);
+
+/* Plan of the two-stage path: as flame_gr_host_plan, but with candidate rows reserved for
+ * cand_capacity[i] (HOST int32 [n_requests]) candidates per request, the layout that flame_gr_prefill
+ * (with all candidate counts 0) and flame_gr_score (with the actual counts) build.  Segment rows and
+ * stream groups depend on history_offsets and cand_capacity only; requests are never split. */
+int flame_gr_host_plan_reserved(const flame_gr_config *cfg, const int32_t *history_offsets,
+                                const int32_t *cand_offsets, const int32_t *cand_capacity,
+                                int32_t n_requests, int32_t *n_segments, int32_t *seg,
+                                int32_t cap_segments);
 
 /* ------------------------------------------------------------------------------------------
  * Debug / parity exports (device work; not on the timed path).

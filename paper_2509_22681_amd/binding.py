@@ -38,7 +38,7 @@ class flame_gr_config(C.Structure):
                 ("n_buckets", C.c_int32), ("max_rel_dist", C.c_int32), ("dtype", C.c_int32),
                 ("ln_eps", C.c_float), ("attn_scale", C.c_float),
                 ("max_requests", C.c_int32), ("max_total_tokens", C.c_int32),
-                ("max_seq_tokens", C.c_int32), ("n_streams", C.c_int32)]
+                ("max_seq_tokens", C.c_int32), ("n_streams", C.c_int32), ("kv_cache", C.c_int32)]
 
 
 class flame_gr_weights(C.Structure):
@@ -53,6 +53,10 @@ _lib.flame_gr_create.restype = C.c_int
 _lib.flame_gr_forward.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p, C.c_void_p]
 _lib.flame_gr_forward.restype = C.c_int
+_lib.flame_gr_prefill.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, _i32p, C.c_int32, C.c_void_p]
+_lib.flame_gr_prefill.restype = C.c_int
+_lib.flame_gr_score.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_int32, C.c_void_p, C.c_void_p]
+_lib.flame_gr_score.restype = C.c_int
 _lib.flame_gr_destroy.argtypes = [C.c_void_p]
 _lib.flame_gr_destroy.restype = C.c_int
 _lib.flame_gr_last_error.argtypes = [C.c_void_p]
@@ -63,6 +67,8 @@ _lib.flame_gr_host_mask.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, 
 _lib.flame_gr_host_mask.restype = C.c_int
 _lib.flame_gr_host_plan.argtypes = [C.POINTER(flame_gr_config), _i32p, _i32p, C.c_int32, _i32p, _i32p, _i32p, C.c_int32]
 _lib.flame_gr_host_plan.restype = C.c_int
+_lib.flame_gr_host_plan_reserved.argtypes = [C.POINTER(flame_gr_config), _i32p, _i32p, _i32p, C.c_int32, _i32p, _i32p, C.c_int32]
+_lib.flame_gr_host_plan_reserved.restype = C.c_int
 _lib.flame_gr_debug_capture.argtypes = [C.c_void_p, C.c_int32]
 _lib.flame_gr_debug_capture.restype = C.c_int
 _lib.flame_gr_debug_stage.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
@@ -74,8 +80,9 @@ _lib.flame_gr_debug_profile.restype = C.c_int
 _lib.flame_gr_debug_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), _i32p]
 _lib.flame_gr_debug_profile_read.restype = C.c_int
 
-EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_destroy", "flame_gr_last_error",
-           "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan",
+EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
+           "flame_gr_last_error",
+           "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan", "flame_gr_host_plan_reserved",
            "flame_gr_debug_capture", "flame_gr_debug_stage", "flame_gr_debug_device_mask",
            "flame_gr_debug_profile", "flame_gr_debug_profile_read")
 
@@ -106,10 +113,10 @@ def _ptr(t) -> Optional[int]:
 
 
 def make_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dtype, *, ln_eps=1e-6, attn_scale=1.0,
-                max_requests=0, max_total_tokens=0, max_seq_tokens=0, n_streams=0) -> flame_gr_config:
+                max_requests=0, max_total_tokens=0, max_seq_tokens=0, n_streams=0, kv_cache=0) -> flame_gr_config:
     dt = {"f32": FLAME_GR_F32, "bf16": FLAME_GR_BF16}.get(dtype, dtype)
     return flame_gr_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dt, ln_eps, attn_scale,
-                           max_requests, max_total_tokens, max_seq_tokens, n_streams)
+                           max_requests, max_total_tokens, max_seq_tokens, n_streams, int(kv_cache))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -148,6 +155,33 @@ def flame_gr_forward(h, weights, history_emb, history_offsets, cand_emb, cand_of
     _check(rc, h)
 
 
+def _stream_ptr(stream) -> int:
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return getattr(stream, "cuda_stream", stream)
+
+
+def flame_gr_prefill(h, weights, history_emb, history_offsets, cand_capacity, stream=None) -> None:
+    """History stage of the two-stage path; cand_capacity: host int32 [n_requests]."""
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    ho, cc = _i32(history_offsets), _i32(cand_capacity)
+    n = len(ho) - 1
+    if len(cc) != n:
+        raise ValueError("cand_capacity must have one entry per request")
+    rc = _lib.flame_gr_prefill(h, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), cc.ctypes.data_as(_i32p), n,
+                               C.c_void_p(_stream_ptr(stream)))
+    _check(rc, h)
+
+
+def flame_gr_score(h, weights, cand_emb, cand_offsets, scores, stream=None) -> None:
+    """Candidate stage of the two-stage path, against the history cached by the last prefill."""
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    co = _i32(cand_offsets)
+    rc = _lib.flame_gr_score(h, C.byref(ws), _ptr(cand_emb), co.ctypes.data_as(_i32p), len(co) - 1, _ptr(scores),
+                             C.c_void_p(_stream_ptr(stream)))
+    _check(rc, h)
+
+
 def flame_gr_last_error(h=None) -> str:
     return _lib.flame_gr_last_error(h).decode()
 
@@ -178,6 +212,19 @@ def flame_gr_host_plan(cfg: flame_gr_config, history_offsets, cand_offsets):
     _check(_lib.flame_gr_host_plan(C.byref(cfg), ho.ctypes.data_as(_i32p), co.ctypes.data_as(_i32p), n,
                                    tok.ctypes.data_as(_i32p), C.byref(nseg), seg.ctypes.data_as(_i32p), len(seg)))
     return tok, seg[:nseg.value]
+
+
+def flame_gr_host_plan_reserved(cfg: flame_gr_config, history_offsets, cand_offsets, cand_capacity):
+    """-> segments [S,6] of the two-stage layout: request, L, cand_begin, M, row_start, group"""
+    ho, co, cc = _i32(history_offsets), _i32(cand_offsets), _i32(cand_capacity)
+    n = len(ho) - 1
+    if len(co) - 1 != n or len(cc) != n:
+        raise ValueError("offset and capacity arrays differ in length")
+    seg = np.zeros((max(n, 1), 6), np.int32)
+    nseg = C.c_int32(0)
+    _check(_lib.flame_gr_host_plan_reserved(C.byref(cfg), ho.ctypes.data_as(_i32p), co.ctypes.data_as(_i32p),
+                                            cc.ctypes.data_as(_i32p), n, C.byref(nseg), seg.ctypes.data_as(_i32p), len(seg)))
+    return seg[:nseg.value]
 
 
 def flame_gr_debug_capture(h, layer: int) -> None:
@@ -228,10 +275,10 @@ def to_device(workload, device="cuda:0"):
     return dw, up(workload.history_emb), up(workload.cand_emb)
 
 
-def config_for(workload, *, n_streams=0, max_seq_tokens=0, slack_requests=0) -> flame_gr_config:
+def config_for(workload, *, n_streams=0, max_seq_tokens=0, slack_requests=0, kv_cache=0, slack_tokens=0) -> flame_gr_config:
     c = workload.cfg
     tot = int(workload.history_offsets[-1]) + int(workload.cand_offsets[-1])
     return make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype,
                        ln_eps=c.ln_eps, attn_scale=c.attn_scale,
-                       max_requests=workload.n_requests + slack_requests, max_total_tokens=tot,
-                       max_seq_tokens=max_seq_tokens, n_streams=n_streams)
+                       max_requests=workload.n_requests + slack_requests, max_total_tokens=tot + slack_tokens,
+                       max_seq_tokens=max_seq_tokens, n_streams=n_streams, kv_cache=kv_cache)

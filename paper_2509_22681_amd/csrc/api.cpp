@@ -26,8 +26,11 @@ enum { KIND_ASSEMBLE = 0, KIND_BIAS, KIND_UVQK, KIND_ATTN, KIND_LNGATE, KIND_OUT
 thread_local std::string g_create_error;
 
 struct StageLayout {  // byte offsets inside one staging buffer (host pinned and device mirror)
-  size_t blocks, items, cand_items, cand_blocks, total;
+  size_t blocks, items, cand_items, cand_blocks, hist_items, hist_blocks, total;
 };
+
+// What a pass covers: the whole batch, or one stage of the two-stage path (Section 5).
+enum PassMode { PASS_FULL = 0, PASS_HISTORY, PASS_CANDIDATES };
 
 struct ProfEvent { hipEvent_t a, b; int kind; };
 
@@ -62,6 +65,10 @@ struct flame_gr {
   bool has_prev = false;
   // last plan (kept for the debug exports)
   Plan plan;
+  // two-stage path: what the last prefill cached (layer l keeps its planes at planes + l * plane_set_bytes)
+  size_t plane_set_bytes = 0;
+  bool kv_valid = false;
+  std::vector<int32_t> kv_hoff, kv_cap;
   // debug capture
   int capture_layer = -1;
   void *cap_planes = nullptr, *cap_O = nullptr;
@@ -139,9 +146,12 @@ struct Timed {
   ~Timed() { if (pe) (void)hipEventRecord(pe->b, s); }
 };
 
-// The layer sequence of one stream group.
+// The layer sequence of one stream group.  PASS_FULL: all rows, one set of planes reused by every
+// layer.  PASS_HISTORY / PASS_CANDIDATES: the history rows (resp. candidate rows) only, every layer
+// on its own set of planes, so that the candidate pass finds K and V of the history rows of layer l
+// where the history pass left them.
 void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const void *hist, const void *cand,
-               float *scores, hipStream_t s) {
+               float *scores, hipStream_t s, PassMode mode) {
   const Shape &sh = h->sh;
   const int dt = h->cfg.dtype;
   const int d = sh.d;
@@ -150,12 +160,24 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
   const AttnItem *items = (const AttnItem *)(h->stage_dev + h->lay.items);
   const AttnItem *citems = (const AttnItem *)(h->stage_dev + h->lay.cand_items);
   const int32_t *cblks = (const int32_t *)(h->stage_dev + h->lay.cand_blocks);
+  const AttnItem *hitems = (const AttnItem *)(h->stage_dev + h->lay.hist_items);
+  const int32_t *hblks = (const int32_t *)(h->stage_dev + h->lay.hist_blocks);
   const int n_blk = G.blk_end - G.blk_begin;
-  if (n_blk == 0) return;
-  { Timed t(h, KIND_ASSEMBLE, s); launch_assemble(dt, blocks, G.blk_begin, G.blk_end, hist, cand, h->X, h->Xb, d, s); }
+  const int32_t *cl = cblks + G.cblk_begin;
+  const int n_cblk = G.cblk_end - G.cblk_begin;
+  const int32_t *hl = hblks + G.hblk_begin;
+  const int n_hblk = G.hblk_end - G.hblk_begin;
+  // the rows of this pass outside the last layer: a contiguous block range, or a list
+  const int32_t *pass_list = mode == PASS_FULL ? nullptr : mode == PASS_HISTORY ? hl : cl;
+  const int pass_n = mode == PASS_FULL ? n_blk : mode == PASS_HISTORY ? n_hblk : n_cblk;
+  const int pass_first = mode == PASS_FULL ? G.blk_begin : 0;
+  if (pass_n == 0) return;
+  { Timed t(h, KIND_ASSEMBLE, s); launch_assemble(dt, blocks, pass_list, pass_n, pass_first, hist, cand, h->X, h->Xb, d, s); }
   const int64_t plane = sh.ws_rows * d;
   for (int l = 0; l < sh.n_layers; ++l) {
-    const bool last = (l == sh.n_layers - 1) && h->capture_layer != l;
+    const bool capture = mode == PASS_FULL && h->capture_layer == l;
+    const bool last = (l == sh.n_layers - 1) && !capture;
+    char *planes = (char *)h->planes + (mode == PASS_FULL ? 0 : (size_t)l * h->plane_set_bytes);
     const char *w1 = (const char *)(dt == FLAME_GR_BF16 ? h->W1h : w.w1) + (size_t)l * 4 * d * d * e;
     const char *b1 = (const char *)w.b1 + (size_t)l * 4 * d * e;
     const char *w2 = (const char *)(dt == FLAME_GR_BF16 ? h->W2h : w.w2) + (size_t)l * d * d * e;
@@ -166,43 +188,44 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
     // In the last layer only candidate rows feed the scores, and history rows never look at
     // candidates: history rows need K and V only, attention and the output projection run on
     // candidate rows only.
-    const int32_t *cl = cblks + G.cblk_begin;
-    const int n_cblk = G.cblk_end - G.cblk_begin;
     if (dt == FLAME_GR_BF16) {
       Timed t(h, KIND_UVQK, s);
-      if (!last) {
-        launch_uvqk_bf16(h->Xb, w1, b1, h->planes, nullptr, n_blk, G.blk_begin, 0xF, sh, s);
+      if (mode == PASS_FULL && last) {
+        launch_uvqk_bf16(h->Xb, w1, b1, planes, nullptr, n_blk, G.blk_begin, 0xA, sh, s);  // V, K: all rows
+        launch_uvqk_bf16(h->Xb, w1, b1, planes, cl, n_cblk, 0, 0x5, sh, s);                // U, Q: candidates
       } else {
-        launch_uvqk_bf16(h->Xb, w1, b1, h->planes, nullptr, n_blk, G.blk_begin, 0xA, sh, s);  // V, K: all rows
-        launch_uvqk_bf16(h->Xb, w1, b1, h->planes, cl, n_cblk, 0, 0x5, sh, s);                // U, Q: candidates
+        launch_uvqk_bf16(h->Xb, w1, b1, planes, pass_list, pass_n, pass_first, mode == PASS_HISTORY && last ? 0xA : 0xF, sh, s);
       }
     } else {
       Timed t(h, KIND_UVQK, s);
-      launch_uvqk_f32(h->X, (const float *)w1, (const float *)b1, (float *)h->planes, G.blk_begin, n_blk, sh, s);
+      launch_uvqk_f32(h->X, (const float *)w1, (const float *)b1, (float *)planes, G.blk_begin, n_blk, sh, s);
     }
+    if (mode == PASS_HISTORY && last) break;  // the history rows of the last layer end at K and V
     {
       Timed t(h, KIND_ATTN, s);
-      const AttnItem *it = last ? citems + G.citem_begin : items + G.item_begin;
-      const int n_it = last ? G.citem_end - G.citem_begin : G.item_end - G.item_begin;
-      if (dt == FLAME_GR_BF16) launch_attn_bf16(h->planes, bias_l, h->O, it, n_it, sh, s);
-      else launch_attn_f32((const float *)h->planes, bias_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
+      const AttnItem *it = items + G.item_begin;
+      int n_it = G.item_end - G.item_begin;
+      if (mode == PASS_HISTORY) { it = hitems + G.hitem_begin; n_it = G.hitem_end - G.hitem_begin; }
+      else if (mode == PASS_CANDIDATES || last) { it = citems + G.citem_begin; n_it = G.citem_end - G.citem_begin; }
+      if (dt == FLAME_GR_BF16) launch_attn_bf16(planes, bias_l, h->O, it, n_it, sh, s);
+      else launch_attn_f32((const float *)planes, bias_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
     }
-    const int32_t *bl = last ? cl : nullptr;
-    const int nb = last ? n_cblk : n_blk;
-    const int bf = last ? 0 : G.blk_begin;
+    const int32_t *bl = mode == PASS_FULL ? (last ? cl : nullptr) : pass_list;
+    const int nb = mode == PASS_FULL ? (last ? n_cblk : n_blk) : pass_n;
+    const int bf = mode == PASS_FULL && !last ? G.blk_begin : 0;
     if (dt == FLAME_GR_BF16 && k3_fused_supported(d)) {
       Timed t(h, KIND_OUTPROJ, s);
-      launch_k3_fused(h->O, h->planes, lg, lb, (const char *)h->W2p + (size_t)l * d * d * e, b2, h->X, h->Xb, blocks, bl, nb, bf, sh, s);
+      launch_k3_fused(h->O, planes, lg, lb, (const char *)h->W2p + (size_t)l * d * d * e, b2, h->X, h->Xb, blocks, bl, nb, bf, sh, s);
     } else {
       {
         Timed t(h, KIND_LNGATE, s);
-        launch_ln_gate(dt, h->O, h->planes, lg, lb, h->G, blocks, bl, nb, bf, d, sh.eps, s);
+        launch_ln_gate(dt, h->O, planes, lg, lb, h->G, blocks, bl, nb, bf, d, sh.eps, s);
       }
       Timed t(h, KIND_OUTPROJ, s);
       if (dt == FLAME_GR_BF16) launch_outproj_bf16(h->G, w2, b2, h->X, h->Xb, bl, nb, bf, sh, s);
       else launch_outproj_f32((const float *)h->G, (const float *)w2, (const float *)b2, h->X, bl, nb, bf, sh, s);
     }
-    if (h->capture_layer == l && h->cap_planes) {
+    if (capture && h->cap_planes) {
       const size_t r0 = (size_t)G.row_begin * d, nr = (size_t)(G.row_end - G.row_begin) * d;
       for (int p = 0; p < 4; ++p) {
         if (dt == FLAME_GR_BF16 && p == 1) {
@@ -218,10 +241,75 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
       (void)hipMemcpyAsync(h->cap_X + r0, h->X + r0, nr * sizeof(float), hipMemcpyDeviceToDevice, s);
     }
   }
+  if (mode == PASS_HISTORY) return;
   {
     Timed t(h, KIND_SCORE, s);
-    launch_scores(dt, h->X, w.w_s, w.b_s, blocks, cblks + G.cblk_begin, G.cblk_end - G.cblk_begin, scores, d, s);
+    launch_scores(dt, h->X, w.w_s, w.b_s, blocks, cl, n_cblk, scores, d, s);
   }
+}
+
+// Stage h->plan through pinned memory, refresh the derived weights and run `mode` on every stream group.
+int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb, const void *cand_emb, float *scores,
+                 hipStream_t s0, PassMode mode) {
+  const Plan &P = h->plan;
+  // stage the plan: one pinned buffer
+  const int slot = h->stage_next;
+  h->stage_next = (slot + 1) % kStageSlots;
+  if (h->stage_used[slot]) HIP_TRY(h, hipEventSynchronize(h->stage_done[slot]));
+  char *sh_ = h->stage_host[slot];
+  // a pass on another stream must not overtake the previous one on this handle
+  if (h->has_prev) HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_done, 0));
+  // the tables are copied separately, only as far as they are filled and only those the pass reads
+  auto stage = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
+    if (bytes == 0) return hipSuccess;
+    std::memcpy(sh_ + off, src, bytes);
+    return hipMemcpyAsync(h->stage_dev + off, sh_ + off, bytes, hipMemcpyHostToDevice, s0);
+  };
+  HIP_TRY(h, stage(h->lay.blocks, P.blocks.data(), P.blocks.size() * sizeof(RowBlock)));
+  if (mode == PASS_FULL) HIP_TRY(h, stage(h->lay.items, P.items.data(), P.items.size() * sizeof(AttnItem)));
+  if (mode != PASS_HISTORY) {
+    HIP_TRY(h, stage(h->lay.cand_items, P.cand_items.data(), P.cand_items.size() * sizeof(AttnItem)));
+    HIP_TRY(h, stage(h->lay.cand_blocks, P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t)));
+  }
+  if (mode == PASS_HISTORY) {
+    HIP_TRY(h, stage(h->lay.hist_items, P.hist_items.data(), P.hist_items.size() * sizeof(AttnItem)));
+    HIP_TRY(h, stage(h->lay.hist_blocks, P.hist_blocks.data(), P.hist_blocks.size() * sizeof(int32_t)));
+  }
+  HIP_TRY(h, hipEventRecord(h->stage_done[slot], s0));
+  h->stage_used[slot] = true;
+  {
+    Timed t(h, KIND_BIAS, s0);
+    if (h->cfg.dtype == FLAME_GR_BF16) {
+      // the caller owns the weights and may have changed them: convert on every pass
+      const int dm = h->sh.d;
+      launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dm, dm, true, s0);
+      if (k3_fused_supported(dm)) launch_pack_w2(w->w2, h->W2p, dm, h->sh.n_layers, s0);
+      else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dm, dm, true, s0);
+    }
+    launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
+                       h->cfg.dtype == FLAME_GR_BF16 ? 0.5f : 1.0f, s0);
+  }
+  if (h->n_groups == 1) {
+    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0, mode);
+  } else {
+    HIP_TRY(h, hipEventRecord(h->ev_fork, s0));
+    for (int g = 0; g < h->n_groups; ++g) {
+      if (P.groups[g].blk_end == P.groups[g].blk_begin) continue;
+      HIP_TRY(h, hipStreamWaitEvent(h->gstream[g], h->ev_fork, 0));
+      run_group(h, *w, P.groups[g], history_emb, cand_emb, scores, h->gstream[g], mode);
+      HIP_TRY(h, hipEventRecord(h->ev_join[g], h->gstream[g]));
+      HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_join[g], 0));
+    }
+  }
+  HIP_TRY(h, hipEventRecord(h->ev_done, s0));
+  h->has_prev = true;
+  hipError_t le = hipGetLastError();
+  if (le != hipSuccess) { h->err = std::string("kernel launch: ") + hipGetErrorString(le); return FLAME_GR_HIP_ERROR; }
+  return FLAME_GR_OK;
+}
+
+bool weights_complete(const flame_gr_weights *w) {
+  return w->w1 && w->b1 && w->rab && w->ln_g && w->ln_b && w->w2 && w->b2 && w->w_s;
 }
 
 }  // namespace
@@ -266,7 +354,9 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   CR(hipGetDevice(&h->device));
   const size_t rows = (size_t)h->ws_rows, d = (size_t)cfg.d_model, e = h->elt;
   CR(hipMalloc(&h->X, rows * d * sizeof(float)));
-  CR(hipMalloc(&h->planes, 4 * rows * d * e));
+  h->plane_set_bytes = 4 * rows * d * e;
+  const size_t n_plane_sets = cfg.kv_cache ? (size_t)cfg.n_layers : 1;
+  CR(hipMalloc(&h->planes, n_plane_sets * h->plane_set_bytes));
   CR(hipMalloc(&h->O, rows * d * e));
   CR(hipMalloc(&h->G, rows * d * e));
   if (cfg.dtype == FLAME_GR_BF16) {
@@ -280,7 +370,7 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   // Every workspace starts finite: rows that a batch leaves as padding are read (and multiplied
   // by zero weights) by the tiled kernels.
   CR(hipMemset(h->X, 0, rows * d * sizeof(float)));
-  CR(hipMemset(h->planes, 0, 4 * rows * d * e));
+  CR(hipMemset(h->planes, 0, n_plane_sets * h->plane_set_bytes));
   CR(hipMemset(h->O, 0, rows * d * e));
   CR(hipMemset(h->G, 0, rows * d * e));
   if (h->Xb) CR(hipMemset(h->Xb, 0, rows * d * e));
@@ -294,7 +384,9 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   h->lay.items = h->lay.blocks + nblk * sizeof(RowBlock);
   h->lay.cand_items = h->lay.items + nblk * sizeof(AttnItem);
   h->lay.cand_blocks = h->lay.cand_items + nblk * sizeof(AttnItem);
-  h->lay.total = h->lay.cand_blocks + nblk * sizeof(int32_t);
+  h->lay.hist_items = h->lay.cand_blocks + nblk * sizeof(int32_t);
+  h->lay.hist_blocks = h->lay.hist_items + nblk * sizeof(AttnItem);
+  h->lay.total = h->lay.hist_blocks + nblk * sizeof(int32_t);
   CR(hipMalloc(&h->stage_dev, h->lay.total));
   for (int i = 0; i < kStageSlots; ++i) {
     CR(hipHostMalloc((void **)&h->stage_host[i], h->lay.total, hipHostMallocDefault));
@@ -340,65 +432,69 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   const int64_t sumL = n_requests ? history_offsets[n_requests] : 0, sumM = n_requests ? cand_offsets[n_requests] : 0;
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
   if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
-  if (plan.total_rows > 0 && (!w->w1 || !w->b1 || !w->rab || !w->ln_g || !w->ln_b || !w->w2 || !w->b2 || !w->w_s))
-    return bad("a weight pointer is NULL");
+  if (plan.total_rows > 0 && !weights_complete(w)) return bad("a weight pointer is NULL");
   h->plan = std::move(plan);
   h->cap_valid = false;
+  h->kv_valid = false;  // the one-pass forward works in the planes of layer 0
   if (h->plan.total_rows == 0) return FLAME_GR_OK;
-
-  hipStream_t s0 = (hipStream_t)stream_v;
-  const Plan &P = h->plan;
-  // stage the plan: one pinned buffer, one copy
-  const int slot = h->stage_next;
-  h->stage_next = (slot + 1) % kStageSlots;
-  if (h->stage_used[slot]) HIP_TRY(h, hipEventSynchronize(h->stage_done[slot]));
-  char *sh_ = h->stage_host[slot];
-  std::memcpy(sh_ + h->lay.blocks, P.blocks.data(), P.blocks.size() * sizeof(RowBlock));
-  std::memcpy(sh_ + h->lay.items, P.items.data(), P.items.size() * sizeof(AttnItem));
-  std::memcpy(sh_ + h->lay.cand_items, P.cand_items.data(), P.cand_items.size() * sizeof(AttnItem));
-  std::memcpy(sh_ + h->lay.cand_blocks, P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t));
-  // a forward on another stream must not overtake the previous one on this handle
-  if (h->has_prev) HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_done, 0));
-  // the four tables are copied separately only as far as they are filled
-  HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.blocks, sh_ + h->lay.blocks, P.blocks.size() * sizeof(RowBlock), hipMemcpyHostToDevice, s0));
-  if (!P.items.empty())
-    HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.items, sh_ + h->lay.items, P.items.size() * sizeof(AttnItem), hipMemcpyHostToDevice, s0));
-  if (!P.cand_items.empty())
-    HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.cand_items, sh_ + h->lay.cand_items, P.cand_items.size() * sizeof(AttnItem), hipMemcpyHostToDevice, s0));
-  if (!P.cand_blocks.empty())
-    HIP_TRY(h, hipMemcpyAsync(h->stage_dev + h->lay.cand_blocks, sh_ + h->lay.cand_blocks, P.cand_blocks.size() * sizeof(int32_t), hipMemcpyHostToDevice, s0));
-  HIP_TRY(h, hipEventRecord(h->stage_done[slot], s0));
-  h->stage_used[slot] = true;
-  {
-    Timed t(h, KIND_BIAS, s0);
-    if (h->cfg.dtype == FLAME_GR_BF16) {
-      // the caller owns the weights and may have changed them: convert on every forward
-      const int dm = h->sh.d;
-      launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dm, dm, true, s0);
-      if (k3_fused_supported(dm)) launch_pack_w2(w->w2, h->W2p, dm, h->sh.n_layers, s0);
-      else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dm, dm, true, s0);
-    }
-    launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
-                       h->cfg.dtype == FLAME_GR_BF16 ? 0.5f : 1.0f, s0);
-  }
-  if (h->n_groups == 1) {
-    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0);
-  } else {
-    HIP_TRY(h, hipEventRecord(h->ev_fork, s0));
-    for (int g = 0; g < h->n_groups; ++g) {
-      if (P.groups[g].blk_end == P.groups[g].blk_begin) continue;
-      HIP_TRY(h, hipStreamWaitEvent(h->gstream[g], h->ev_fork, 0));
-      run_group(h, *w, P.groups[g], history_emb, cand_emb, scores, h->gstream[g]);
-      HIP_TRY(h, hipEventRecord(h->ev_join[g], h->gstream[g]));
-      HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_join[g], 0));
-    }
-  }
-  HIP_TRY(h, hipEventRecord(h->ev_done, s0));
-  h->has_prev = true;
+  rc = enqueue_pass(h, w, history_emb, cand_emb, scores, (hipStream_t)stream_v, PASS_FULL);
+  if (rc) return rc;
   h->cap_valid = h->capture_layer >= 0 && h->cap_planes;
-  hipError_t le = hipGetLastError();
-  if (le != hipSuccess) { h->err = std::string("kernel launch: ") + hipGetErrorString(le); return FLAME_GR_HIP_ERROR; }
   return FLAME_GR_OK;
+}
+
+int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+                     const int32_t *history_offsets, const int32_t *cand_capacity, int32_t n_requests,
+                     void *stream_v) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  h->err.clear();
+  auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  if (!h->cfg.kv_cache) { h->err = "handle was created without kv_cache"; return FLAME_GR_UNSUPPORTED; }
+  if (!w) return bad("weights is NULL");
+  if (n_requests < 0) return bad("n_requests < 0");
+  if (n_requests > 0 && (!history_offsets || !cand_capacity)) return bad("history_offsets or cand_capacity is NULL");
+  const std::vector<int32_t> no_cands((size_t)n_requests + 1, 0);
+  Plan plan;
+  int rc = build_plan(h->cfg, history_offsets, no_cands.data(), n_requests, h->q_tile, h->n_groups, h->ws_rows, plan,
+                      h->err, cand_capacity);
+  if (rc) return rc;
+  const int64_t sumL = n_requests ? history_offsets[n_requests] : 0;
+  if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
+  if (sumL > 0 && !weights_complete(w)) return bad("a weight pointer is NULL");
+  h->plan = std::move(plan);
+  h->cap_valid = false;
+  h->kv_valid = false;
+  h->kv_hoff.assign(history_offsets, history_offsets + (n_requests ? n_requests + 1 : 0));
+  h->kv_cap.assign(cand_capacity, cand_capacity + n_requests);
+  if (sumL > 0) {
+    rc = enqueue_pass(h, w, history_emb, nullptr, nullptr, (hipStream_t)stream_v, PASS_HISTORY);
+    if (rc) return rc;
+  }
+  h->kv_valid = true;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_score(flame_gr_t *h, const flame_gr_weights *w, const void *cand_emb, const int32_t *cand_offsets,
+                   int32_t n_requests, float *scores, void *stream_v) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  h->err.clear();
+  auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  if (!h->cfg.kv_cache) { h->err = "handle was created without kv_cache"; return FLAME_GR_UNSUPPORTED; }
+  if (!h->kv_valid) return bad("no valid prefill on this handle");
+  if (!w) return bad("weights is NULL");
+  if (n_requests != (int32_t)h->kv_cap.size()) return bad("n_requests differs from the prefill");
+  if (n_requests > 0 && !cand_offsets) return bad("cand_offsets is NULL");
+  Plan plan;
+  int rc = build_plan(h->cfg, h->kv_hoff.data(), cand_offsets, n_requests, h->q_tile, h->n_groups, h->ws_rows, plan,
+                      h->err, h->kv_cap.data());
+  if (rc) return rc;
+  const int64_t sumM = n_requests ? cand_offsets[n_requests] : 0;
+  if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
+  if (sumM > 0 && !weights_complete(w)) return bad("a weight pointer is NULL");
+  h->plan = std::move(plan);
+  h->cap_valid = false;
+  if (sumM == 0) return FLAME_GR_OK;
+  return enqueue_pass(h, w, nullptr, cand_emb, scores, (hipStream_t)stream_v, PASS_CANDIDATES);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -438,8 +534,9 @@ int flame_gr_host_mask(int32_t L, int32_t M, int32_t n_buckets, int32_t max_rel_
   return FLAME_GR_OK;
 }
 
-int flame_gr_host_plan(const flame_gr_config *cfg_in, const int32_t *history_offsets, const int32_t *cand_offsets,
-                       int32_t n_requests, int32_t *tok_off, int32_t *n_segments, int32_t *seg, int32_t cap_segments) {
+static int host_plan(const flame_gr_config *cfg_in, const int32_t *history_offsets, const int32_t *cand_offsets,
+                     const int32_t *cand_capacity, int32_t n_requests, int32_t *tok_off, int32_t *n_segments,
+                     int32_t *seg, int32_t cap_segments) {
   if (!cfg_in) return FLAME_GR_INVALID_ARGUMENT;
   flame_gr_config cfg = *cfg_in;
   std::string err;
@@ -448,7 +545,7 @@ int flame_gr_host_plan(const flame_gr_config *cfg_in, const int32_t *history_off
     Plan P;
     const int q_tile = cfg.dtype == FLAME_GR_BF16 ? kAttnQTileBf16 : kAttnQTileF32;
     rc = build_plan(cfg, history_offsets, cand_offsets, n_requests, q_tile, cfg.n_streams > 1 ? cfg.n_streams : 1,
-                    workspace_rows(cfg), P, err);
+                    workspace_rows(cfg), P, err, cand_capacity);
     if (!rc) {
       if (tok_off) std::memcpy(tok_off, P.tok_off.data(), P.tok_off.size() * sizeof(int32_t));
       if (n_segments) *n_segments = (int32_t)P.segs.size();
@@ -464,6 +561,20 @@ int flame_gr_host_plan(const flame_gr_config *cfg_in, const int32_t *history_off
   }
   if (rc) g_create_error = err;
   return rc;
+}
+
+int flame_gr_host_plan(const flame_gr_config *cfg_in, const int32_t *history_offsets, const int32_t *cand_offsets,
+                       int32_t n_requests, int32_t *tok_off, int32_t *n_segments, int32_t *seg, int32_t cap_segments) {
+  return host_plan(cfg_in, history_offsets, cand_offsets, nullptr, n_requests, tok_off, n_segments, seg, cap_segments);
+}
+
+int flame_gr_host_plan_reserved(const flame_gr_config *cfg_in, const int32_t *history_offsets,
+                                const int32_t *cand_offsets, const int32_t *cand_capacity, int32_t n_requests,
+                                int32_t *n_segments, int32_t *seg, int32_t cap_segments) {
+  if (n_requests > 0 && !cand_capacity) { g_create_error = "cand_capacity is NULL"; return FLAME_GR_INVALID_ARGUMENT; }
+  static const int32_t none = 0;
+  return host_plan(cfg_in, history_offsets, cand_offsets, n_requests > 0 ? cand_capacity : &none, n_requests, nullptr,
+                   n_segments, seg, cap_segments);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -16,7 +16,8 @@ struct Shape {
 
 // ---- shared small kernels (misc.hip) --------------------------------------------------------
 // X[rows of blocks) <- embeddings (fp32 copy, and a k-tile blocked fp16 copy Xh in the MFMA path); padding rows zeroed.
-void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
+// The n blocks are list[0..n) if list is given, else first..first+n.
+void launch_assemble(int dtype, const RowBlock *blocks, const int32_t *list, int n, int first, const void *hist,
                      const void *cand, float *X, void *Xh, int d, hipStream_t s);
 // fp16 copy of a bf16 matrix of `rows` rows of K elements (K % 8 == 0); blocked: written in the k-tile
 // blocked layout of the GEMM operands (rows % 64 == 0, K % 32 == 0), else element for element

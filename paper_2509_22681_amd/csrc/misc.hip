@@ -12,10 +12,10 @@ namespace flame {
 // X is row-major fp32; the fp16 copy Xh (MFMA path) is k-tile blocked.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restrict__ blocks, int blk_begin,
+__global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restrict__ blocks, const int32_t *__restrict__ list, int blk_begin,
                                                        const T *__restrict__ hist, const T *__restrict__ cand,
                                                        float *__restrict__ X, half_t *__restrict__ Xh, int d) {
-  const int b = blk_begin + blockIdx.x;
+  const int b = list ? list[blockIdx.x] : blk_begin + blockIdx.x;
   const RowBlock rb = blocks[b];
   const T *src = rb.kind ? cand : hist;
   const int64_t dst0 = (int64_t)b * kRowAlign * d;
@@ -29,14 +29,13 @@ __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restric
   }
 }
 
-void launch_assemble(int dtype, const RowBlock *blocks, int blk_begin, int blk_end, const void *hist,
+void launch_assemble(int dtype, const RowBlock *blocks, const int32_t *list, int n, int first, const void *hist,
                      const void *cand, float *X, void *Xh, int d, hipStream_t s) {
-  const int n = blk_end - blk_begin;
   if (n <= 0) return;
   if (dtype == FLAME_GR_BF16)
-    assemble_kernel<bf16_t><<<n, 256, 0, s>>>(blocks, blk_begin, (const bf16_t *)hist, (const bf16_t *)cand, X, (half_t *)Xh, d);
+    assemble_kernel<bf16_t><<<n, 256, 0, s>>>(blocks, list, first, (const bf16_t *)hist, (const bf16_t *)cand, X, (half_t *)Xh, d);
   else
-    assemble_kernel<float><<<n, 256, 0, s>>>(blocks, blk_begin, (const float *)hist, (const float *)cand, X, nullptr, d);
+    assemble_kernel<float><<<n, 256, 0, s>>>(blocks, list, first, (const float *)hist, (const float *)cand, X, nullptr, d);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -25,6 +25,11 @@ int validate_config(const flame_gr_config &c, std::string &err) {
   if (c.ln_eps < 0.f || c.attn_scale < 0.f) return bad("ln_eps and attn_scale must be >= 0");
   if (c.max_requests < 0 || c.max_total_tokens < 0 || c.max_seq_tokens < 0) return bad("capacities must be >= 0");
   if (c.n_streams < 0 || c.n_streams > 16) return bad("n_streams must be in [0, 16]");
+  if (c.kv_cache != 0 && c.kv_cache != 1) return bad("kv_cache must be 0 or 1");
+  if (c.kv_cache && c.dtype != FLAME_GR_BF16) {
+    err = "the two-stage path (kv_cache) is built for the bf16 kernels only";
+    return FLAME_GR_UNSUPPORTED;
+  }
   if (c.dtype == FLAME_GR_BF16) {
     int dh = c.d_model / c.n_heads;
     if (c.d_model % 64 || !(dh == 32 || dh == 64)) {
@@ -61,7 +66,8 @@ int64_t workspace_rows(const flame_gr_config &c) {
 }
 
 int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *coff, int32_t B,
-               int32_t q_tile, int32_t n_groups, int64_t ws_rows, Plan &p, std::string &err) {
+               int32_t q_tile, int32_t n_groups, int64_t ws_rows, Plan &p, std::string &err,
+               const int32_t *cand_capacity) {
   auto fail = [&](int code, const std::string &m) { err = m; return code; };
   if (B < 0) return fail(FLAME_GR_INVALID_ARGUMENT, "n_requests < 0");
   if (B > 0 && (!hoff || !coff)) return fail(FLAME_GR_INVALID_ARGUMENT, "offset arrays are NULL");
@@ -69,10 +75,12 @@ int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *c
   p = Plan();
   p.tok_off.assign(B + 1, 0);
   if (B > 0 && (hoff[0] != 0 || coff[0] != 0)) return fail(FLAME_GR_INVALID_ARGUMENT, "offsets must start at 0");
+  int64_t cap_sum = 0;
   for (int i = 0; i < B; ++i) {
     if (hoff[i + 1] < hoff[i] || coff[i + 1] < coff[i])
       return fail(FLAME_GR_INVALID_ARGUMENT, "offsets must be non-decreasing (request " + std::to_string(i) + ")");
-    int64_t t = (int64_t)hoff[i + 1] + coff[i + 1];
+    cap_sum += cand_capacity ? std::max(cand_capacity[i], 0) : 0;
+    int64_t t = (int64_t)hoff[i + 1] + (cand_capacity ? cap_sum : (int64_t)coff[i + 1]);
     if (t > cfg.max_total_tokens) return fail(FLAME_GR_CAPACITY_EXCEEDED, "total tokens exceed max_total_tokens");
     p.tok_off[i + 1] = (int32_t)t;
   }
@@ -82,6 +90,22 @@ int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *c
   // 1. segments (descending-size split of over-long requests)
   for (int i = 0; i < B; ++i) {
     const int32_t L = hoff[i + 1] - hoff[i], M = coff[i + 1] - coff[i];
+    if (cand_capacity) {
+      // reserved layout: one segment per request, candidate rows for the capacity
+      const int32_t C = cand_capacity[i];
+      if (C < 0) return fail(FLAME_GR_INVALID_ARGUMENT, "negative candidate capacity (request " + std::to_string(i) + ")");
+      if (M > C) return fail(FLAME_GR_CAPACITY_EXCEEDED, "request " + std::to_string(i) + " has more candidates than its reserved capacity");
+      if (cfg.max_seq_tokens > 0 && L + C > cfg.max_seq_tokens)
+        return fail(FLAME_GR_UNSUPPORTED, "a request with reserved candidates would need splitting (max_seq_tokens)");
+      Segment s{};
+      s.req = i; s.L = L; s.cand_begin = 0; s.M = M;
+      s.Lp = round_up(L, kRowAlign); s.Mp = round_up(C, kRowAlign);
+      const int64_t N = (int64_t)L + C;
+      const int64_t P = (int64_t)L * (L + 1) / 2 + (int64_t)C * (L + 1);
+      s.cost = 10 * N * d * d + 4 * P * d;
+      p.segs.push_back(s);
+      continue;
+    }
     int32_t cap = M;
     if (cfg.max_seq_tokens > 0 && L + M > cfg.max_seq_tokens && M > 0) {
       cap = cfg.max_seq_tokens - L;
@@ -129,15 +153,21 @@ int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *c
     G.item_begin = (int32_t)p.items.size();
     G.citem_begin = (int32_t)p.cand_items.size();
     G.cblk_begin = (int32_t)p.cand_blocks.size();
+    G.hitem_begin = (int32_t)p.hist_items.size();
+    G.hblk_begin = (int32_t)p.hist_blocks.size();
     for (; si < p.segs.size() && p.segs[si].group == g; ++si) {
       Segment &s = p.segs[si];
       if (row + s.Lp + s.Mp > ws_rows) return fail(FLAME_GR_CAPACITY_EXCEEDED, "padded batch does not fit the workspace sized at create");
       s.row_start = (int32_t)row;
-      for (int32_t b = 0; b < s.Lp; b += kRowAlign)
+      for (int32_t b = 0; b < s.Lp; b += kRowAlign) {
+        p.hist_blocks.push_back((int32_t)p.blocks.size());
         p.blocks.push_back(RowBlock{hoff[s.req] + b, std::min(kRowAlign, s.L - b), 0, (int32_t)si});
+      }
       for (int32_t b = 0; b < s.Mp; b += kRowAlign) {
-        p.cand_blocks.push_back((int32_t)p.blocks.size());
-        p.blocks.push_back(RowBlock{coff[s.req] + s.cand_begin + b, std::min(kRowAlign, s.M - b), 1, (int32_t)si});
+        // reserved rows past the actual candidates form blocks without valid rows: not in the work lists
+        const int32_t nv = std::max(0, std::min(kRowAlign, s.M - b));
+        if (nv > 0) p.cand_blocks.push_back((int32_t)p.blocks.size());
+        p.blocks.push_back(RowBlock{coff[s.req] + s.cand_begin + b, nv, 1, (int32_t)si});
       }
       // candidate tiles first (they see the whole history), then history tiles from the end
       for (int32_t j = 0; j < s.M; j += q_tile) {
@@ -147,7 +177,9 @@ int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *c
       }
       for (int32_t q0 = (s.L - 1) / q_tile * q_tile; s.L > 0 && q0 >= 0; q0 -= q_tile) {
         const int32_t nq = std::min(q_tile, s.L - q0);
-        p.items.push_back(AttnItem{s.row_start + q0, nq, s.row_start, s.L, q0, 0, q0 + nq, 0});
+        AttnItem it{s.row_start + q0, nq, s.row_start, s.L, q0, 0, q0 + nq, 0};
+        p.items.push_back(it);
+        p.hist_items.push_back(it);
       }
       row += s.Lp + s.Mp;
       p.total_cands += s.M;
@@ -157,6 +189,8 @@ int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *c
     G.item_end = (int32_t)p.items.size();
     G.citem_end = (int32_t)p.cand_items.size();
     G.cblk_end = (int32_t)p.cand_blocks.size();
+    G.hitem_end = (int32_t)p.hist_items.size();
+    G.hblk_end = (int32_t)p.hist_blocks.size();
   }
   p.total_rows = (int32_t)row;
   return FLAME_GR_OK;

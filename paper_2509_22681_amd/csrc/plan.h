@@ -52,8 +52,10 @@ struct Group {
   int32_t row_begin, row_end;          // workspace rows [begin, end) of this stream group (multiples of 64)
   int32_t blk_begin, blk_end;          // RowBlock range
   int32_t item_begin, item_end;        // AttnItem range, all layers but the last
-  int32_t citem_begin, citem_end;      // AttnItem range of candidate tiles only (last layer)
-  int32_t cblk_begin, cblk_end;        // range in cand_blocks (last-layer row pruning, score head)
+  int32_t citem_begin, citem_end;      // AttnItem range of candidate tiles only (last layer, score stage)
+  int32_t cblk_begin, cblk_end;        // range in cand_blocks (last-layer row pruning, score head, score stage)
+  int32_t hitem_begin, hitem_end;      // AttnItem range of history tiles only (prefill stage)
+  int32_t hblk_begin, hblk_end;        // range in hist_blocks (prefill stage)
 };
 
 struct Plan {
@@ -62,7 +64,9 @@ struct Plan {
   std::vector<RowBlock> blocks;        // total_rows / 64 entries
   std::vector<AttnItem> items;         // per group: cost-descending
   std::vector<AttnItem> cand_items;    // candidate tiles only
-  std::vector<int32_t> cand_blocks;    // indices of candidate RowBlocks, per group contiguous
+  std::vector<int32_t> cand_blocks;    // indices of candidate RowBlocks with valid rows, per group contiguous
+  std::vector<AttnItem> hist_items;    // history tiles only
+  std::vector<int32_t> hist_blocks;    // indices of history RowBlocks, per group contiguous
   std::vector<Group> groups;
   int32_t total_rows = 0;
   int64_t total_cands = 0;
@@ -72,8 +76,12 @@ struct Plan {
 // Validation + planning.  q_tile = query rows per attention item.  Returns a flame_gr_status;
 // on failure `err` holds the reason.
 int validate_config(const flame_gr_config &cfg, std::string &err);
+// cand_capacity (optional, [B]): rows are reserved for that many candidates per request (>= the actual
+// count), and layout and stream groups depend on the capacities only, not on the actual counts: the plans
+// of a prefill (no candidates yet) and of the score calls that follow it then agree on every row.
 int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *coff, int32_t B,
-               int32_t q_tile, int32_t n_groups, int64_t ws_rows, Plan &plan, std::string &err);
+               int32_t q_tile, int32_t n_groups, int64_t ws_rows, Plan &plan, std::string &err,
+               const int32_t *cand_capacity = nullptr);
 
 // bucket(delta) for delta in [0, D)
 void bucket_table(int32_t n_buckets, int32_t D, int32_t *out);

@@ -153,3 +153,56 @@ def test_config_validation_codes():
 def test_destroy_null_is_a_noop_and_bad_handle_is_reported():
     assert B._lib.flame_gr_destroy(None) == 0
     assert B._lib.flame_gr_forward(None, None, None, None, None, None, 0, None, None) == -4
+
+
+# ------------------------------------------------------------------ two-stage layout (reserved candidate rows)
+@settings(max_examples=60, deadline=None)
+@given(st.lists(st.tuples(st.integers(0, 400), st.integers(0, 300), st.integers(0, 200)), min_size=0, max_size=12),
+       st.integers(1, 5))
+def test_reserved_plan_depends_on_capacity_only(lmc, n_streams):
+    """The prefill (no candidates yet) and every later score call (any counts up to the capacity) must agree on
+    each request's rows and stream group, or the candidate pass would not find the cached history."""
+    L = [a for a, _, _ in lmc]
+    M = [b for _, b, _ in lmc]
+    cap = np.array([b + c for _, b, c in lmc], np.int32)
+    ho = np.concatenate([[0], np.cumsum(L)]).astype(np.int32)
+    co = np.concatenate([[0], np.cumsum(M)]).astype(np.int32)
+    zero = np.zeros(len(L) + 1, np.int32)
+    cfg = _cfg(n_streams=n_streams, kv_cache=1)
+    pre = B.flame_gr_host_plan_reserved(cfg, ho, zero, cap)
+    act = B.flame_gr_host_plan_reserved(cfg, ho, co, cap)
+    assert len(pre) == len(act) == len(L)
+    assert np.array_equal(pre[:, [0, 1, 2, 4, 5]], act[:, [0, 1, 2, 4, 5]])
+    assert np.array_equal(act[:, 3], np.asarray(M, np.int32)[act[:, 0]]) and not act[:, 2].any()
+    # rows: aligned, disjoint, with room for the whole capacity
+    end_prev = 0
+    for s in act:
+        req, Lr, _, _, row, grp = (int(v) for v in s)
+        assert row % 64 == 0 and row >= end_prev and 0 <= grp < n_streams
+        end_prev = row + (Lr + 63) // 64 * 64 + (int(cap[req]) + 63) // 64 * 64
+    assert list(act[:, 5]) == sorted(act[:, 5])
+
+
+def test_reserved_plan_rejections():
+    ho = np.array([0, 100, 130], np.int32)
+    co = np.array([0, 20, 30], np.int32)
+    with pytest.raises(B.FlameGRError) as e:                            # more candidates than reserved
+        B.flame_gr_host_plan_reserved(_cfg(kv_cache=1), ho, co, [19, 10])
+    assert e.value.code == -2
+    with pytest.raises(B.FlameGRError) as e:
+        B.flame_gr_host_plan_reserved(_cfg(kv_cache=1), ho, co, [20, -1])
+    assert e.value.code == -1
+    with pytest.raises(B.FlameGRError) as e:                            # reserved rows count against the capacity
+        B.flame_gr_host_plan_reserved(_cfg(kv_cache=1, max_total_tokens=200), ho, co, [20, 60])
+    assert e.value.code == -2
+    with pytest.raises(B.FlameGRError) as e:                            # a reserved request is never split
+        B.flame_gr_host_plan_reserved(_cfg(kv_cache=1, max_seq_tokens=110), ho, co, [20, 10])
+    assert e.value.code == -5
+    with pytest.raises(B.FlameGRError) as e:                            # the fp32 kernels have no two-stage path
+        B.flame_gr_host_plan_reserved(_cfg(dtype="f32", kv_cache=1), ho, co, [20, 10])
+    assert e.value.code == -5
+    with pytest.raises(B.FlameGRError) as e:
+        B.flame_gr_host_plan_reserved(_cfg(kv_cache=2), ho, co, [20, 10])
+    assert e.value.code == -1
+    seg = B.flame_gr_host_plan_reserved(_cfg(kv_cache=1), ho, co, [20, 10])
+    assert len(seg) == 2
