@@ -114,6 +114,27 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *weights,
                      const void *cand_emb, const int32_t *cand_offsets,
                      int32_t n_requests, float *scores, void *stream);
 
+/* Explicit-shape executor (Section 3.3): with the batch shape fixed, the whole forward is recorded
+ * once into a HIP graph and later requests of that shape replay it, which removes the per-kernel
+ * launch cost that dominates small batches.
+ *
+ * flame_gr_capture takes the arguments of flame_gr_forward (no stream: it synchronises the handle's
+ * earlier work, uploads the plan, derives the weight copies and records the kernels on an internal
+ * stream; nothing is scored yet).  The graph is bound to the shape (the offsets), to the four device
+ * buffers history_emb, cand_emb, scores and the weight pointers, and to the weight VALUES at capture
+ * time: the caller refreshes the contents of history_emb / cand_emb in place before each replay and
+ * captures again after changing weights.  This setup call may allocate (graph objects, one stream);
+ * flame_gr_replay does not.  Needs n_streams <= 1 (UNSUPPORTED otherwise) and at least one candidate.
+ * Any flame_gr_forward / flame_gr_prefill / flame_gr_score on the handle drops the graph.
+ *
+ * flame_gr_replay enqueues the captured forward on `stream` (hipStream_t or NULL); scores are valid
+ * once the stream has been synchronised.  INVALID_ARGUMENT if the handle holds no graph. */
+int flame_gr_capture(flame_gr_t *h, const flame_gr_weights *weights,
+                     const void *history_emb, const int32_t *history_offsets,
+                     const void *cand_emb, const int32_t *cand_offsets,
+                     int32_t n_requests, float *scores);
+int flame_gr_replay(flame_gr_t *h, void *stream);
+
 /* Two-stage scoring with a history key/value cache: the paradigm that Section 5 leaves for future
  * work, expecting it to pay for long contexts and larger models.  Because a history row never looks
  * at a candidate (mask of Section 3.2), the history part of every layer does not depend on the

@@ -53,6 +53,11 @@ _lib.flame_gr_create.restype = C.c_int
 _lib.flame_gr_forward.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p, C.c_void_p]
 _lib.flame_gr_forward.restype = C.c_int
+_lib.flame_gr_capture.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
+                                  C.c_int32, C.c_void_p]
+_lib.flame_gr_capture.restype = C.c_int
+_lib.flame_gr_replay.argtypes = [C.c_void_p, C.c_void_p]
+_lib.flame_gr_replay.restype = C.c_int
 _lib.flame_gr_prefill.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, _i32p, C.c_int32, C.c_void_p]
 _lib.flame_gr_prefill.restype = C.c_int
 _lib.flame_gr_score.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_int32, C.c_void_p, C.c_void_p]
@@ -80,7 +85,33 @@ _lib.flame_gr_debug_profile.restype = C.c_int
 _lib.flame_gr_debug_profile_read.argtypes = [C.c_void_p, C.POINTER(C.c_float), _i32p]
 _lib.flame_gr_debug_profile_read.restype = C.c_int
 
-EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
+class flame_dso_config(C.Structure):
+    _fields_ = [("hist_len", C.c_int32), ("n_profiles", C.c_int32), ("profiles", _i32p),
+                ("executors_per_profile", C.c_int32), ("explicit_shapes", C.c_int32)]
+
+
+_lib.flame_dso_create.argtypes = [C.POINTER(flame_gr_config), C.POINTER(flame_gr_weights), C.POINTER(flame_dso_config),
+                                  C.POINTER(C.c_void_p)]
+_lib.flame_dso_create.restype = C.c_int
+_lib.flame_dso_submit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int64)]
+_lib.flame_dso_submit.restype = C.c_int
+_lib.flame_dso_wait.argtypes = [C.c_void_p, C.c_int64]
+_lib.flame_dso_wait.restype = C.c_int
+_lib.flame_dso_drain.argtypes = [C.c_void_p]
+_lib.flame_dso_drain.restype = C.c_int
+_lib.flame_dso_destroy.argtypes = [C.c_void_p]
+_lib.flame_dso_destroy.restype = C.c_int
+_lib.flame_dso_last_error.argtypes = [C.c_void_p]
+_lib.flame_dso_last_error.restype = C.c_char_p
+_lib.flame_dso_route.argtypes = [_i32p, C.c_int32, C.c_int32, C.c_int32, C.c_int32, C.c_int32, _i32p, C.c_int32, _i32p]
+_lib.flame_dso_route.restype = C.c_int
+_lib.flame_dso_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
+_lib.flame_dso_stats.restype = C.c_int
+
+DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_wait", "flame_dso_drain", "flame_dso_destroy",
+               "flame_dso_last_error", "flame_dso_route", "flame_dso_stats")
+
+EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
            "flame_gr_last_error",
            "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan", "flame_gr_host_plan_reserved",
            "flame_gr_debug_capture", "flame_gr_debug_stage", "flame_gr_debug_device_mask",
@@ -159,6 +190,22 @@ def _stream_ptr(stream) -> int:
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
     return getattr(stream, "cuda_stream", stream)
+
+
+def flame_gr_capture(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores) -> None:
+    """Record the forward of this fixed batch (shape, buffers, weight values) into the handle's HIP graph."""
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    ho, co = _i32(history_offsets), _i32(cand_offsets)
+    n = len(ho) - 1
+    if len(co) - 1 != n:
+        raise ValueError("offset arrays differ in length")
+    rc = _lib.flame_gr_capture(h, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
+                               co.ctypes.data_as(_i32p), n, _ptr(scores))
+    _check(rc, h)
+
+
+def flame_gr_replay(h, stream=None) -> None:
+    _check(_lib.flame_gr_replay(h, C.c_void_p(_stream_ptr(stream))), h)
 
 
 def flame_gr_prefill(h, weights, history_emb, history_offsets, cand_capacity, stream=None) -> None:
@@ -255,6 +302,86 @@ def flame_gr_debug_profile_read(h):
     n = (C.c_int32 * len(KERNEL_KINDS))()
     _check(_lib.flame_gr_debug_profile_read(h, ms, n), h)
     return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(KERNEL_KINDS)}
+
+
+# ---------------------------------------------------------------------------------------------
+# request orchestrator (include/flame_dso.h); embeddings and scores are HOST numpy arrays here
+# ---------------------------------------------------------------------------------------------
+def _dso_check(rc: int, dso=None):
+    if rc != 0:
+        msg = _lib.flame_dso_last_error(dso)
+        raise FlameGRError(rc, msg.decode() if msg else "")
+
+
+def flame_dso_create(cfg: flame_gr_config, weights, hist_len: int, profiles, executors_per_profile: int,
+                     explicit_shapes: bool = True) -> C.c_void_p:
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    prof = _i32(profiles)
+    dc = flame_dso_config(hist_len, len(prof), prof.ctypes.data_as(_i32p), executors_per_profile, int(explicit_shapes))
+    out = C.c_void_p()
+    _dso_check(_lib.flame_dso_create(C.byref(cfg), C.byref(ws), C.byref(dc), C.byref(out)))
+    return out
+
+
+def host_embedding(a, dtype: str) -> np.ndarray:
+    """fp32 numpy values -> the raw host layout the orchestrator expects (bf16 as uint16 bit patterns;
+    the values are expected to be bf16-representable already, as the workload generators make them)."""
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    if dtype == "f32":
+        return a
+    bits = a.view(np.uint32)
+    if (bits & 0xFFFF).any():
+        raise ValueError("values are not bf16-representable")
+    return np.ascontiguousarray((bits >> 16).astype(np.uint16))
+
+
+def flame_dso_submit(dso, history_emb: np.ndarray, cand_emb: np.ndarray, scores: np.ndarray) -> int:
+    """history_emb / cand_emb: contiguous host arrays in the model dtype (see host_embedding);
+    scores: contiguous float32 host array [n_cand], filled by the wait that retires the ticket."""
+    if not (cand_emb.flags.c_contiguous and scores.flags.c_contiguous and scores.dtype == np.float32):
+        raise ValueError("cand_emb and scores must be contiguous, scores float32")
+    t = C.c_int64(0)
+    hp = history_emb.ctypes.data if history_emb is not None and history_emb.size else None
+    _dso_check(_lib.flame_dso_submit(dso, hp, cand_emb.ctypes.data, int(cand_emb.shape[0]), scores.ctypes.data, C.byref(t)), dso)
+    return t.value
+
+
+def flame_dso_wait(dso, ticket: int) -> None:
+    _dso_check(_lib.flame_dso_wait(dso, ticket), dso)
+
+
+def flame_dso_drain(dso) -> None:
+    _dso_check(_lib.flame_dso_drain(dso), dso)
+
+
+def flame_dso_destroy(dso) -> None:
+    _dso_check(_lib.flame_dso_destroy(dso))
+
+
+def flame_dso_last_error(dso=None) -> str:
+    return _lib.flame_dso_last_error(dso).decode()
+
+
+def flame_dso_stats(dso) -> Dict[str, int]:
+    out = (C.c_int64 * 4)()
+    _dso_check(_lib.flame_dso_stats(dso, out), dso)
+    return dict(zip(("requests", "chunks", "candidate_rows_computed", "waits_for_a_busy_executor"), (int(v) for v in out)))
+
+
+def flame_dso_route(profiles, hist_len: int, d_model: int, n_cand: int, explicit_shapes: bool = True):
+    """-> list of (profile index, candidates taken)"""
+    prof = _i32(profiles)
+    n = C.c_int32(0)
+    rc = _lib.flame_dso_route(prof.ctypes.data_as(_i32p), len(prof), hist_len, d_model, int(explicit_shapes), n_cand, None, 0,
+                              C.byref(n))
+    if rc not in (0, -2):
+        raise FlameGRError(rc, "flame_dso_route")
+    buf = np.zeros((max(n.value, 1), 2), np.int32)
+    rc = _lib.flame_dso_route(prof.ctypes.data_as(_i32p), len(prof), hist_len, d_model, int(explicit_shapes), n_cand,
+                              buf.ctypes.data_as(_i32p), len(buf), C.byref(n))
+    if rc != 0:
+        raise FlameGRError(rc, "flame_dso_route")
+    return [(int(a), int(b)) for a, b in buf[:n.value]]
 
 
 # ---------------------------------------------------------------------------------------------

@@ -65,6 +65,10 @@ struct flame_gr {
   bool has_prev = false;
   // last plan (kept for the debug exports)
   Plan plan;
+  // explicit-shape executor: the one-pass forward of one fixed batch, captured as a HIP graph
+  hipStream_t cap_stream = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+  bool graph_valid = false;
   // two-stage path: what the last prefill cached (layer l keeps its planes at planes + l * plane_set_bytes)
   size_t plane_set_bytes = 0;
   bool kv_valid = false;
@@ -124,6 +128,8 @@ void free_all(flame_gr *h) {
     if (h->gstream[g]) (void)hipStreamDestroy(h->gstream[g]);
     if (h->ev_join[g]) (void)hipEventDestroy(h->ev_join[g]);
   }
+  if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
+  if (h->cap_stream) (void)hipStreamDestroy(h->cap_stream);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_done) (void)hipEventDestroy(h->ev_done);
   for (auto &p : h->prof_pool) { (void)hipEventDestroy(p.a); (void)hipEventDestroy(p.b); }
@@ -248,10 +254,24 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
   }
 }
 
+// What the kernels read in place of the caller's weights: fp16 copies of the projection matrices in
+// the operand layouts of the GEMMs (MFMA path), and the bias table indexed by distance.
+void derive_weights(flame_gr *h, const flame_gr_weights *w, hipStream_t s) {
+  if (h->cfg.dtype == FLAME_GR_BF16) {
+    const int dm = h->sh.d;
+    launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dm, dm, true, s);
+    if (k3_fused_supported(dm)) launch_pack_w2(w->w2, h->W2p, dm, h->sh.n_layers, s);
+    else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dm, dm, true, s);
+  }
+  launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
+                     h->cfg.dtype == FLAME_GR_BF16 ? 0.5f : 1.0f, s);
+}
+
 // Stage h->plan through pinned memory, refresh the derived weights and run `mode` on every stream group.
 int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb, const void *cand_emb, float *scores,
                  hipStream_t s0, PassMode mode) {
   const Plan &P = h->plan;
+  h->graph_valid = false;  // the captured forward reads the plan tables and workspaces this pass overwrites
   // stage the plan: one pinned buffer
   const int slot = h->stage_next;
   h->stage_next = (slot + 1) % kStageSlots;
@@ -278,16 +298,9 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
   HIP_TRY(h, hipEventRecord(h->stage_done[slot], s0));
   h->stage_used[slot] = true;
   {
+    // the caller owns the weights and may have changed them: derive on every pass
     Timed t(h, KIND_BIAS, s0);
-    if (h->cfg.dtype == FLAME_GR_BF16) {
-      // the caller owns the weights and may have changed them: convert on every pass
-      const int dm = h->sh.d;
-      launch_bf16_to_f16(w->w1, h->W1h, (int64_t)h->sh.n_layers * 4 * dm, dm, true, s0);
-      if (k3_fused_supported(dm)) launch_pack_w2(w->w2, h->W2p, dm, h->sh.n_layers, s0);
-      else launch_bf16_to_f16(w->w2, h->W2h, (int64_t)h->sh.n_layers * dm, dm, true, s0);
-    }
-    launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
-                       h->cfg.dtype == FLAME_GR_BF16 ? 0.5f : 1.0f, s0);
+    derive_weights(h, w, s0);
   }
   if (h->n_groups == 1) {
     run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0, mode);
@@ -440,6 +453,77 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   rc = enqueue_pass(h, w, history_emb, cand_emb, scores, (hipStream_t)stream_v, PASS_FULL);
   if (rc) return rc;
   h->cap_valid = h->capture_layer >= 0 && h->cap_planes;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_capture(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+                     const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
+                     int32_t n_requests, float *scores) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  h->err.clear();
+  auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  if (h->n_groups != 1) { h->err = "capture needs a handle without internal stream groups (n_streams <= 1)"; return FLAME_GR_UNSUPPORTED; }
+  if (h->capture_layer >= 0) { h->err = "capture is not available while a debug layer capture is selected"; return FLAME_GR_UNSUPPORTED; }
+  if (!w) return bad("weights is NULL");
+  if (n_requests < 0) return bad("n_requests < 0");
+  if (n_requests > 0 && (!history_offsets || !cand_offsets)) return bad("offset arrays are NULL");
+  Plan plan;
+  int rc = build_plan(h->cfg, history_offsets, cand_offsets, n_requests, h->q_tile, 1, h->ws_rows, plan, h->err);
+  if (rc) return rc;
+  const int64_t sumL = n_requests ? history_offsets[n_requests] : 0, sumM = n_requests ? cand_offsets[n_requests] : 0;
+  if (sumM == 0) return bad("nothing to capture: the batch has no candidates");
+  if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
+  if (!cand_emb || !scores) return bad("cand_emb or scores is NULL");
+  if (!weights_complete(w)) return bad("a weight pointer is NULL");
+  // setup, outside the graph: wait for earlier work on the handle, then upload the plan and derive the weights
+  if (h->has_prev) HIP_TRY(h, hipEventSynchronize(h->ev_done));
+  h->graph_valid = false;
+  h->kv_valid = false;
+  h->cap_valid = false;
+  if (h->graph_exec) { HIP_TRY(h, hipGraphExecDestroy(h->graph_exec)); h->graph_exec = nullptr; }
+  if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
+  h->plan = std::move(plan);
+  const Plan &P = h->plan;
+  auto upload = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
+    return bytes ? hipMemcpy(h->stage_dev + off, src, bytes, hipMemcpyHostToDevice) : hipSuccess;
+  };
+  HIP_TRY(h, upload(h->lay.blocks, P.blocks.data(), P.blocks.size() * sizeof(RowBlock)));
+  HIP_TRY(h, upload(h->lay.items, P.items.data(), P.items.size() * sizeof(AttnItem)));
+  HIP_TRY(h, upload(h->lay.cand_items, P.cand_items.data(), P.cand_items.size() * sizeof(AttnItem)));
+  HIP_TRY(h, upload(h->lay.cand_blocks, P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t)));
+  derive_weights(h, w, h->cap_stream);
+  HIP_TRY(h, hipStreamSynchronize(h->cap_stream));
+  // the layer sequence, recorded instead of run (kernel launches only: no copies, no memsets)
+  const bool prof = h->profiling;
+  h->profiling = false;
+  hipGraph_t graph = nullptr;
+  hipError_t e = hipStreamBeginCapture(h->cap_stream, hipStreamCaptureModeThreadLocal);
+  if (e == hipSuccess) {
+    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, h->cap_stream, PASS_FULL);
+    e = hipStreamEndCapture(h->cap_stream, &graph);
+  }
+  h->profiling = prof;
+  if (e == hipSuccess) e = hipGraphInstantiate(&h->graph_exec, graph, nullptr, nullptr, 0);
+  if (graph) (void)hipGraphDestroy(graph);
+  if (e != hipSuccess) {
+    (void)hipGetLastError();
+    h->graph_exec = nullptr;
+    h->err = std::string("graph capture: ") + hipGetErrorString(e);
+    return FLAME_GR_HIP_ERROR;
+  }
+  h->graph_valid = true;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_replay(flame_gr_t *h, void *stream_v) {
+  if (!live(h)) return FLAME_GR_BAD_HANDLE;
+  h->err.clear();
+  if (!h->graph_valid) { h->err = "no captured forward on this handle"; return FLAME_GR_INVALID_ARGUMENT; }
+  hipStream_t s0 = (hipStream_t)stream_v;
+  if (h->has_prev) HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_done, 0));
+  HIP_TRY(h, hipGraphLaunch(h->graph_exec, s0));
+  HIP_TRY(h, hipEventRecord(h->ev_done, s0));
+  h->has_prev = true;
   return FLAME_GR_OK;
 }
 

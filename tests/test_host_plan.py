@@ -20,13 +20,14 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
 def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "flame_gr.h")).read()
-    declared = set(re.findall(r"\b(flame_gr_[a-z_]+)\s*\(", header))
-    assert {"flame_gr_create", "flame_gr_forward", "flame_gr_destroy"} <= declared
+    inc = os.path.join(ROOT, "include")
+    header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
+    declared = set(re.findall(r"\b(flame_(?:gr|dso)_[a-z_]+)\s*\(", header))
+    assert {"flame_gr_create", "flame_gr_forward", "flame_gr_destroy", "flame_dso_create", "flame_dso_submit"} <= declared
     lib = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
-    assert declared == set(B.EXPORTS)
+    assert declared == set(B.EXPORTS) | set(B.DSO_EXPORTS)
 
 
 @pytest.mark.parametrize("nb,D", [(128, 128), (128, 1024), (128, 4096), (128, 8192), (512, 16384),
