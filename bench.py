@@ -131,6 +131,60 @@ def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128)
             "scores_per_s": float(M[idx].sum() / wall)}
 
 
+def mixed_traffic_leg(B, wl, dw, n_requests=320, executors_per_profile=2, hist_len=1024,
+                      profiles=(128, 256, 512, 1024), seed=0):
+    """The paper's mixed-traffic experiment (Section 4.2.3, DSO table) on this model: single-user requests with a
+    history of 1024 items and a candidate count drawn uniformly from {128, 256, 512, 1024}, host embeddings in,
+    host scores out, served in a closed loop by the orchestrator: once with explicit-shape executors (captured
+    graphs, profile queues) and once with the implicit-shape baseline (same pool, dynamic-shape eager forward).
+    Latency is host wall-clock from submit to scores delivered."""
+    c = wl.cfg
+    cfg = B.make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype, ln_eps=c.ln_eps,
+                        attn_scale=c.attn_scale)
+    rng = np.random.default_rng(seed)
+    Ms = rng.choice(np.asarray(profiles), size=n_requests)
+    pool = 8                                   # distinct users; every request gets its own candidate slice
+    std = 0.1
+    from paper_2509_22681_amd import workloads as W
+    hist_pool = [B.host_embedding(W._round_storage(rng.standard_normal((hist_len, c.d_model)).astype(np.float32) * std, c.dtype), c.dtype)
+                 for _ in range(pool)]
+    cand_pool = B.host_embedding(W._round_storage(rng.standard_normal((max(profiles) * 2, c.d_model)).astype(np.float32) * std, c.dtype), c.dtype)
+    out = {"hist_len": hist_len, "profiles": list(profiles), "requests": n_requests,
+           "executors_per_profile": executors_per_profile, "user_item_pairs": int(Ms.sum())}
+    for mode, explicit in (("explicit_shape", True), ("implicit_shape", False)):
+        dso = B.flame_dso_create(cfg, dw, hist_len, list(profiles), executors_per_profile, explicit_shapes=explicit)
+        try:
+            depth = len(profiles) * executors_per_profile
+            res = None
+            for rep in range(2):               # first pass warms up
+                lat, inflight = [], []
+                outs = [np.empty(int(m), np.float32) for m in Ms]
+                t0 = time.perf_counter()
+                for k, m in enumerate(Ms):
+                    if len(inflight) == depth:
+                        t, ts = inflight.pop(0)
+                        B.flame_dso_wait(dso, t)
+                        lat.append(time.perf_counter() - ts)
+                    off = int(rng.integers(0, max(profiles)))
+                    ts = time.perf_counter()
+                    t = B.flame_dso_submit(dso, hist_pool[k % pool], cand_pool[off:off + int(m)], outs[k])
+                    inflight.append((t, ts))
+                for t, ts in inflight:
+                    B.flame_dso_wait(dso, t)
+                    lat.append(time.perf_counter() - ts)
+                wall = time.perf_counter() - t0
+                assert all(np.isfinite(o).all() for o in outs), "non-finite scores"
+                lat = np.array(lat) * 1e3
+                res = {"user_item_pairs_per_s": float(Ms.sum() / wall), "mean_latency_ms": float(lat.mean()),
+                       "p50_latency_ms": float(np.percentile(lat, 50)), "p99_latency_ms": float(np.percentile(lat, 99)),
+                       "requests_per_s": float(n_requests / wall)}
+            res.update(B.flame_dso_stats(dso))
+            out[mode] = res
+        finally:
+            B.flame_dso_destroy(dso)
+    return out
+
+
 def two_stage_leg(B, wl, ws, hist, cand, one_pass_scores, steps, warmup):
     """History prefill once (per-layer K/V kept on the device), then `steps` candidate-only score calls against
     it: the two-stage paradigm of the paper's Section 5.  Reported beside the headline, never as `value`."""
@@ -174,6 +228,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-latency", action="store_true")
     ap.add_argument("--no-two-stage", action="store_true")
+    ap.add_argument("--no-mixed-traffic", action="store_true")
+    ap.add_argument("--executors-per-profile", type=int, default=2)
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy kernel of this many MiB "
                          "(a kernel of known HBM traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -271,6 +327,8 @@ def main():
         out["request_latency_8_executors"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=8)
     if two_stage is not None:
         out["two_stage"] = two_stage
+    if not args.no_mixed_traffic:
+        out["mixed_traffic"] = mixed_traffic_leg(B, wl, dw, executors_per_profile=args.executors_per_profile)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

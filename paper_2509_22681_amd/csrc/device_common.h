@@ -71,9 +71,25 @@ __device__ __forceinline__ int visible_history(int is_cand, int q_index, int L) 
   return is_cand ? L : q_index + 1;
 }
 
+// Sum over the 64 lanes, delivered to every lane: the butterfly v += v[lane ^ o] for o = 32, 16, 8, 4, 2, 1,
+// without the LDS crossbar.  The two widest steps use the half- and row-swap instructions of gfx950 (each
+// returns both halves of the exchange, whose sum is the butterfly step in either half); the others are DPP
+// operands of the add.  After the step for o, lanes that differ only in bits >= o hold equal values, so a row
+// rotation by 4 (resp. 2) reaches a lane that holds exactly what lane ^ 4 (resp. lane ^ 2) holds: every lane
+// gets the bits the plain butterfly would give.
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+  {
+    const auto r = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    v = __uint_as_float(r[0]) + __uint_as_float(r[1]);
+  }
+  v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x128, 0xf, 0xf, false));  // row_ror:8
+  v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x124, 0xf, 0xf, false));  // row_ror:4
+  v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0x4e, 0xf, 0xf, false));   // quad_perm 2,3,0,1
+  v += __uint_as_float(__builtin_amdgcn_update_dpp(0, __float_as_uint(v), 0xb1, 0xf, 0xf, false));   // quad_perm 1,0,3,2
   return v;
 }
 

@@ -94,27 +94,38 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
     const int set = batch & 1;
     if (batch + 1 < 16 / RB4) issue(set ^ 1, batch + 1);
     __builtin_amdgcn_sched_barrier(0);
+    // the four rows go through each step together, so that their reduction chains overlap
+    float v[RB4][CPL][8], mu[RB4], rstd[RB4];
 #pragma unroll
     for (int q = 0; q < RB4; ++q) {
-      const int r = wave * 16 + batch * RB4 + q;
-      float v[CPL][8];
       float sum = 0.f;
 #pragma unroll
       for (int c = 0; c < CPL; ++c)
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          v[c][k] = lane + 64 * c < NCHUNK ? (float)ov[set][q][c][k] : 0.f;
-          sum += v[c][k];
+          v[q][c][k] = lane + 64 * c < NCHUNK ? (float)ov[set][q][c][k] : 0.f;
+          sum += v[q][c][k];
         }
-      const float mu = wave_sum(sum) * (1.0f / d);
+      mu[q] = sum;
+    }
+#pragma unroll
+    for (int q = 0; q < RB4; ++q) mu[q] = wave_sum(mu[q]) * (1.0f / d);
+#pragma unroll
+    for (int q = 0; q < RB4; ++q) {
       float sq = 0.f;
 #pragma unroll
       for (int c = 0; c < CPL; ++c)
         if (lane + 64 * c < NCHUNK) {
 #pragma unroll
-          for (int k = 0; k < 8; ++k) { const float t = v[c][k] - mu; sq += t * t; }
+          for (int k = 0; k < 8; ++k) { const float t = v[q][c][k] - mu[q]; sq += t * t; }
         }
-      const float rstd = rsqrtf(wave_sum(sq) * (1.0f / d) + eps);
+      rstd[q] = sq;
+    }
+#pragma unroll
+    for (int q = 0; q < RB4; ++q) rstd[q] = rsqrtf(wave_sum(rstd[q]) * (1.0f / d) + eps);
+#pragma unroll
+    for (int q = 0; q < RB4; ++q) {
+      const int r = wave * 16 + batch * RB4 + q;
       const bool pad = r >= n_valid;               // padding rows carry a zero branch so that they stay finite
 #pragma unroll
       for (int c = 0; c < CPL; ++c) {
@@ -123,7 +134,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
           f16x8 o;
 #pragma unroll
           for (int k = 0; k < 8; ++k)
-            o[k] = pad ? (half_t)0.f : to_f16_sat(((v[c][k] - mu) * rstd * g[c][k] + bt[c][k]) * (float)uv[set][q][c][k]);
+            o[k] = pad ? (half_t)0.f : to_f16_sat(((v[q][c][k] - mu[q]) * rstd[q] * g[c][k] + bt[c][k]) * (float)uv[set][q][c][k]);
           *(f16x8 *)(smem + r * (d * 2) + ((ch ^ (r & 15)) << 4)) = o;
         }
       }
@@ -141,31 +152,45 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   constexpr int NKS = d / 16;
+  // The W2 fragments come from L2, whose latency is several times the 8 MFMAs of a k-step: they are requested
+  // PD - 1 k-steps ahead into a register ring (scheduling barriers keep the compiler from sinking the requests
+  // back to their first use); the activations come from LDS, one step ahead.
+  constexpr int PD = 4;
+  static_assert(NKS % PD == 0, "k-steps are walked in groups of the ring depth");
   const half_t *wp = W2p + ((int64_t)(wave * NBW) * 64 + lane) * 8;      // + (ks * (d/32) + j) * 512
-  f16x8 fw[2][NBW], fa[2][2];
+  f16x8 fw[PD][NBW], fa[2][2];
 #pragma unroll
-  for (int j = 0; j < NBW; ++j) fw[0][j] = *(const f16x8 *)(wp + (int64_t)j * 512);
+  for (int p = 0; p < PD - 1; ++p)
+#pragma unroll
+    for (int j = 0; j < NBW; ++j) fw[p][j] = *(const f16x8 *)(wp + ((int64_t)p * (d / 32) + j) * 512);
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int r = 32 * i + l32;
     fa[0][i] = *(const f16x8 *)(smem + r * (d * 2) + ((lhalf ^ (r & 15)) << 4));
   }
-#pragma unroll 4
-  for (int ks = 0; ks < NKS; ++ks) {
-    const int cur = ks & 1, nxt = cur ^ 1;
-    const int kn = ks + 1 < NKS ? ks + 1 : ks;
+  __builtin_amdgcn_sched_barrier(0);
+  for (int ks0 = 0; ks0 < NKS; ks0 += PD) {
 #pragma unroll
-    for (int j = 0; j < NBW; ++j) fw[nxt][j] = *(const f16x8 *)(wp + ((int64_t)kn * (d / 32) + j) * 512);
+    for (int u = 0; u < PD; ++u) {
+      const int ks = ks0 + u;
+      const int cur = u & 1, nxt = cur ^ 1;
+      const int kw = ks + PD - 1 < NKS ? ks + PD - 1 : NKS - 1;
+      const int kn = ks + 1 < NKS ? ks + 1 : ks;
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int r = 32 * i + l32;
-      fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ (r & 15)) << 4));
+      for (int j = 0; j < NBW; ++j) fw[(u + PD - 1) % PD][j] = *(const f16x8 *)(wp + ((int64_t)kw * (d / 32) + j) * 512);
+#pragma unroll
+      for (int i = 0; i < 2; ++i) {
+        const int r = 32 * i + l32;
+        fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ (r & 15)) << 4));
+      }
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NBW; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[u][j], fa[cur][i], acc[i][j], 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
     }
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < NBW; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[cur][j], fa[cur][i], acc[i][j], 0, 0, 0);
   }
 
   // ---- phase 3: residual.  In the accumulators a lane holds one token and scattered features, and only

@@ -29,11 +29,46 @@ __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restric
   }
 }
 
+// bf16 inputs: 16 bytes per lane, each 64-row block cut into gridDim.y row slices so that a small batch
+// still spreads over many compute units and no lane walks a long chain of dependent loads.
+__global__ __launch_bounds__(256) void assemble_bf16_kernel(const RowBlock *__restrict__ blocks, const int32_t *__restrict__ list,
+                                                            int blk_begin, const bf16_t *__restrict__ hist,
+                                                            const bf16_t *__restrict__ cand, float *__restrict__ X,
+                                                            half_t *__restrict__ Xh, int d) {
+  const int b = list ? list[blockIdx.x] : blk_begin + blockIdx.x;
+  const RowBlock rb = blocks[b];
+  const bf16_t *src = rb.kind ? cand : hist;
+  const int cpr = d / 8;                                   // 16-byte chunks per row
+  const int rows = kRowAlign / gridDim.y, r0 = blockIdx.y * rows;
+  const int64_t row_base = (int64_t)b * kRowAlign;
+#pragma unroll 4
+  for (int i = threadIdx.x; i < rows * cpr; i += 256) {
+    const int r = r0 + i / cpr, c = i % cpr;
+    bf16x8 v;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) v[k] = (bf16_t)0.f;
+    if (r < rb.n_valid) v = *(const bf16x8 *)(src + ((int64_t)rb.src_row + r) * d + c * 8);
+    f32x4 lo, hi;
+    f16x8 o;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      lo[k] = (float)v[k];
+      hi[k] = (float)v[4 + k];
+      o[k] = to_f16_sat(lo[k]);
+      o[4 + k] = to_f16_sat(hi[k]);
+    }
+    float *xp = X + (row_base + r) * d + c * 8;
+    *(f32x4 *)xp = lo;
+    *(f32x4 *)(xp + 4) = hi;
+    *(f16x8 *)(Xh + blocked_index(row_base + r, c * 8, d)) = o;
+  }
+}
+
 void launch_assemble(int dtype, const RowBlock *blocks, const int32_t *list, int n, int first, const void *hist,
                      const void *cand, float *X, void *Xh, int d, hipStream_t s) {
   if (n <= 0) return;
   if (dtype == FLAME_GR_BF16)
-    assemble_kernel<bf16_t><<<n, 256, 0, s>>>(blocks, list, first, (const bf16_t *)hist, (const bf16_t *)cand, X, (half_t *)Xh, d);
+    assemble_bf16_kernel<<<dim3(n, 4), 256, 0, s>>>(blocks, list, first, (const bf16_t *)hist, (const bf16_t *)cand, X, (half_t *)Xh, d);
   else
     assemble_kernel<float><<<n, 256, 0, s>>>(blocks, list, first, (const float *)hist, (const float *)cand, X, nullptr, d);
 }
