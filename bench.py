@@ -131,12 +131,13 @@ def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128)
             "scores_per_s": float(M[idx].sum() / wall)}
 
 
-def mixed_traffic_leg(B, wl, dw, n_requests=320, executors_per_profile=2, hist_len=1024,
+def mixed_traffic_leg(B, wl, dw, n_requests=320, n_executors=4, hist_len=1024,
                       profiles=(128, 256, 512, 1024), seed=0):
     """The paper's mixed-traffic experiment (Section 4.2.3, DSO table) on this model: single-user requests with a
     history of 1024 items and a candidate count drawn uniformly from {128, 256, 512, 1024}, host embeddings in,
-    host scores out, served in a closed loop by the orchestrator: once with explicit-shape executors (captured
-    graphs, profile queues) and once with the implicit-shape baseline (same pool, dynamic-shape eager forward).
+    host scores out, served in a closed loop by the orchestrator: once with explicit-shape executors (one captured
+    graph per profile on every executor) and once with the implicit-shape baseline (same pool, dynamic-shape eager
+    forward).
     Latency is host wall-clock from submit to scores delivered."""
     c = wl.cfg
     cfg = B.make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype, ln_eps=c.ln_eps,
@@ -150,11 +151,11 @@ def mixed_traffic_leg(B, wl, dw, n_requests=320, executors_per_profile=2, hist_l
                  for _ in range(pool)]
     cand_pool = B.host_embedding(W._round_storage(rng.standard_normal((max(profiles) * 2, c.d_model)).astype(np.float32) * std, c.dtype), c.dtype)
     out = {"hist_len": hist_len, "profiles": list(profiles), "requests": n_requests,
-           "executors_per_profile": executors_per_profile, "user_item_pairs": int(Ms.sum())}
+           "executors": n_executors, "user_item_pairs": int(Ms.sum())}
     for mode, explicit in (("explicit_shape", True), ("implicit_shape", False)):
-        dso = B.flame_dso_create(cfg, dw, hist_len, list(profiles), executors_per_profile, explicit_shapes=explicit)
+        dso = B.flame_dso_create(cfg, dw, hist_len, list(profiles), n_executors, explicit_shapes=explicit)
         try:
-            depth = len(profiles) * executors_per_profile
+            depth = n_executors
             res = None
             for rep in range(2):               # first pass warms up
                 lat, inflight = [], []
@@ -229,7 +230,7 @@ def main():
     ap.add_argument("--no-latency", action="store_true")
     ap.add_argument("--no-two-stage", action="store_true")
     ap.add_argument("--no-mixed-traffic", action="store_true")
-    ap.add_argument("--executors-per-profile", type=int, default=2)
+    ap.add_argument("--executors", type=int, default=4, help="executors of the mixed-traffic orchestrator")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy kernel of this many MiB "
                          "(a kernel of known HBM traffic for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -328,7 +329,7 @@ def main():
     if two_stage is not None:
         out["two_stage"] = two_stage
     if not args.no_mixed_traffic:
-        out["mixed_traffic"] = mixed_traffic_leg(B, wl, dw, executors_per_profile=args.executors_per_profile)
+        out["mixed_traffic"] = mixed_traffic_leg(B, wl, dw, n_executors=args.executors)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))

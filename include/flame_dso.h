@@ -3,17 +3,20 @@
  *
  * The paper's Dynamic Stream Orchestrator (Section 3.3): upstream services send one user at a time
  * with a varying number of candidates.  Instead of one dynamic-shape engine, a set of executors is
- * built ahead of time, one per (candidate-count profile, slot): each executor owns pre-allocated
- * input and output buffers, a stream, and the forward of its explicit shape captured as a graph.
- * Free executors wait in an index queue per profile.  A request is split by candidate count in
- * descending profile order, every chunk is handed to a free executor of its profile, and the
- * executor's index returns to the queue once its work has completed.  Inputs travel through pinned
- * host buffers that belong to the executors (the "pinned data transfer" of Section 3.1), so a
- * chunk's upload overlaps the compute of the chunks before it on other streams.
+ * built ahead of time for a few candidate-count profiles: an executor owns pre-allocated input and
+ * output buffers, a stream, and the forward of its explicit shapes captured as graphs.  Free
+ * executors wait in an index queue.  A request is split by candidate count in descending profile
+ * order, every chunk is handed to a free executor, and the executor's index returns to the queue
+ * once its work has completed.  Inputs travel through pinned host buffers that belong to the
+ * executors (the "pinned data transfer" of Section 3.1), so a chunk's upload overlaps the compute
+ * of the chunks before it on other streams.
  *
- * Here an executor is a flame_gr handle with a captured HIP graph (flame_gr_capture), a pinned
- * input buffer, a device input buffer, a device and a pinned score buffer, a stream and an event.
- * Every chunk re-runs the user's history (as the split of Section 3.3 does).
+ * Here an executor is a flame_gr handle with one captured HIP graph per profile (flame_gr_capture,
+ * one slot each, all bound to the executor's one set of buffers), a pinned input buffer, a device
+ * input buffer, a device and a pinned score buffer, a stream and an event.  Because every executor
+ * can replay every profile there is one queue, not one per profile: a burst of one candidate count
+ * never waits while executors of another profile idle.  Every chunk re-runs the user's history (as
+ * the split of Section 3.3 does).
  *
  * Conventions as in flame_gr.h: 0 or a negative flame_gr_status is returned, nothing throws.  All
  * embedding and score pointers of this header are HOST pointers (any host memory).  One host thread
@@ -36,8 +39,9 @@ typedef struct {
   int32_t hist_len;              /* L: every request brings exactly this many history items (the
                                     explicit shape of every executor) */
   int32_t n_profiles;            /* 1..16 */
-  const int32_t *profiles;       /* HOST [n_profiles]: candidate counts, strictly ascending, >= 1 */
-  int32_t executors_per_profile; /* 1..64 slots per profile (each with its own stream) */
+  const int32_t *profiles;       /* HOST [n_profiles]: candidate counts, strictly ascending, >= 1;
+                                    at most FLAME_GR_MAX_GRAPHS when explicit_shapes = 1 */
+  int32_t n_executors;           /* 1..256 executors (each with its own stream and buffers) */
   int32_t explicit_shapes;       /* 1: the executors described above (graph replay, a chunk with fewer
                                        candidates than its profile is padded with rows whose scores are
                                        dropped).
@@ -65,8 +69,8 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
  *   ticket       receives a handle for flame_dso_wait
  * The call copies the embeddings into the executors' pinned buffers (both host arrays may be reused
  * when it returns), enqueues upload, forward and download on the executors' streams and returns
- * without waiting for the GPU, unless every executor of a needed profile is busy: then it first
- * waits for the one that was handed out earliest. */
+ * without waiting for the GPU, unless every executor is busy: then it first waits for the one that
+ * was handed out earliest. */
 int flame_dso_submit(flame_dso_t *dso, const void *history_emb, const void *cand_emb, int32_t n_cand,
                      float *scores, int64_t *ticket);
 

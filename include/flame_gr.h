@@ -115,25 +115,30 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *weights,
                      int32_t n_requests, float *scores, void *stream);
 
 /* Explicit-shape executor (Section 3.3): with the batch shape fixed, the whole forward is recorded
- * once into a HIP graph and later requests of that shape replay it, which removes the per-kernel
- * launch cost that dominates small batches.
+ * once into a HIP graph and later requests of that shape replay it with one call instead of one
+ * launch per kernel.  A handle holds up to FLAME_GR_MAX_GRAPHS such graphs (`slot`), e.g. one per
+ * candidate-count profile, all working in the handle's one set of workspaces.
  *
  * flame_gr_capture takes the arguments of flame_gr_forward (no stream: it synchronises the handle's
- * earlier work, uploads the plan, derives the weight copies and records the kernels on an internal
- * stream; nothing is scored yet).  The graph is bound to the shape (the offsets), to the four device
- * buffers history_emb, cand_emb, scores and the weight pointers, and to the weight VALUES at capture
- * time: the caller refreshes the contents of history_emb / cand_emb in place before each replay and
- * captures again after changing weights.  This setup call may allocate (graph objects, one stream);
+ * earlier work, uploads the plan into tables owned by the slot, derives the weight copies and records
+ * the kernels on an internal stream; nothing is scored yet).  The graph is bound to the shape (the
+ * offsets) and to the device buffers history_emb, cand_emb, scores and the weight pointers: the
+ * caller refreshes the contents of history_emb / cand_emb in place before each replay.  The derived
+ * weight copies belong to the handle and are rewritten by every capture and every eager call from the
+ * weights passed there: keep to one set of weight values per handle, and capture again after changing
+ * them.  This setup call may allocate (graph objects, the slot's tables, one stream);
  * flame_gr_replay does not.  Needs n_streams <= 1 (UNSUPPORTED otherwise) and at least one candidate.
- * Any flame_gr_forward / flame_gr_prefill / flame_gr_score on the handle drops the graph.
+ * Capturing into a used slot replaces its graph.
  *
- * flame_gr_replay enqueues the captured forward on `stream` (hipStream_t or NULL); scores are valid
- * once the stream has been synchronised.  INVALID_ARGUMENT if the handle holds no graph. */
-int flame_gr_capture(flame_gr_t *h, const flame_gr_weights *weights,
+ * flame_gr_replay enqueues the captured forward of `slot` on `stream` (hipStream_t or NULL); scores
+ * are valid once the stream has been synchronised.  Calls on one handle are serialised on the device
+ * like forwards.  INVALID_ARGUMENT if the slot holds no graph. */
+#define FLAME_GR_MAX_GRAPHS 16
+int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *weights,
                      const void *history_emb, const int32_t *history_offsets,
                      const void *cand_emb, const int32_t *cand_offsets,
                      int32_t n_requests, float *scores);
-int flame_gr_replay(flame_gr_t *h, void *stream);
+int flame_gr_replay(flame_gr_t *h, int32_t slot, void *stream);
 
 /* Two-stage scoring with a history key/value cache: the paradigm that Section 5 leaves for future
  * work, expecting it to pay for long contexts and larger models.  Because a history row never looks

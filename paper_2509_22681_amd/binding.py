@@ -53,10 +53,10 @@ _lib.flame_gr_create.restype = C.c_int
 _lib.flame_gr_forward.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p, C.c_void_p]
 _lib.flame_gr_forward.restype = C.c_int
-_lib.flame_gr_capture.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
+_lib.flame_gr_capture.argtypes = [C.c_void_p, C.c_int32, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p]
 _lib.flame_gr_capture.restype = C.c_int
-_lib.flame_gr_replay.argtypes = [C.c_void_p, C.c_void_p]
+_lib.flame_gr_replay.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
 _lib.flame_gr_replay.restype = C.c_int
 _lib.flame_gr_prefill.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, _i32p, C.c_int32, C.c_void_p]
 _lib.flame_gr_prefill.restype = C.c_int
@@ -87,7 +87,7 @@ _lib.flame_gr_debug_profile_read.restype = C.c_int
 
 class flame_dso_config(C.Structure):
     _fields_ = [("hist_len", C.c_int32), ("n_profiles", C.c_int32), ("profiles", _i32p),
-                ("executors_per_profile", C.c_int32), ("explicit_shapes", C.c_int32)]
+                ("n_executors", C.c_int32), ("explicit_shapes", C.c_int32)]
 
 
 _lib.flame_dso_create.argtypes = [C.POINTER(flame_gr_config), C.POINTER(flame_gr_weights), C.POINTER(flame_dso_config),
@@ -192,20 +192,20 @@ def _stream_ptr(stream) -> int:
     return getattr(stream, "cuda_stream", stream)
 
 
-def flame_gr_capture(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores) -> None:
-    """Record the forward of this fixed batch (shape, buffers, weight values) into the handle's HIP graph."""
+def flame_gr_capture(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores, slot: int = 0) -> None:
+    """Record the forward of this fixed batch (shape, buffers) into graph `slot` of the handle."""
     ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
     ho, co = _i32(history_offsets), _i32(cand_offsets)
     n = len(ho) - 1
     if len(co) - 1 != n:
         raise ValueError("offset arrays differ in length")
-    rc = _lib.flame_gr_capture(h, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
+    rc = _lib.flame_gr_capture(h, slot, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
                                co.ctypes.data_as(_i32p), n, _ptr(scores))
     _check(rc, h)
 
 
-def flame_gr_replay(h, stream=None) -> None:
-    _check(_lib.flame_gr_replay(h, C.c_void_p(_stream_ptr(stream))), h)
+def flame_gr_replay(h, stream=None, slot: int = 0) -> None:
+    _check(_lib.flame_gr_replay(h, slot, C.c_void_p(_stream_ptr(stream))), h)
 
 
 def flame_gr_prefill(h, weights, history_emb, history_offsets, cand_capacity, stream=None) -> None:
@@ -313,11 +313,11 @@ def _dso_check(rc: int, dso=None):
         raise FlameGRError(rc, msg.decode() if msg else "")
 
 
-def flame_dso_create(cfg: flame_gr_config, weights, hist_len: int, profiles, executors_per_profile: int,
+def flame_dso_create(cfg: flame_gr_config, weights, hist_len: int, profiles, n_executors: int,
                      explicit_shapes: bool = True) -> C.c_void_p:
     ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
     prof = _i32(profiles)
-    dc = flame_dso_config(hist_len, len(prof), prof.ctypes.data_as(_i32p), executors_per_profile, int(explicit_shapes))
+    dc = flame_dso_config(hist_len, len(prof), prof.ctypes.data_as(_i32p), n_executors, int(explicit_shapes))
     out = C.c_void_p()
     _dso_check(_lib.flame_dso_create(C.byref(cfg), C.byref(ws), C.byref(dc), C.byref(out)))
     return out

@@ -21,6 +21,7 @@ namespace {
 constexpr uint32_t kMagic = 0x464c4752u;  // "FLGR"
 constexpr int kStageSlots = 2;
 constexpr int kMaxGroups = 16;
+constexpr int kMaxGraphs = FLAME_GR_MAX_GRAPHS;
 enum { KIND_ASSEMBLE = 0, KIND_BIAS, KIND_UVQK, KIND_ATTN, KIND_LNGATE, KIND_OUTPROJ, KIND_SCORE, KIND_COUNT };
 
 thread_local std::string g_create_error;
@@ -33,6 +34,14 @@ struct StageLayout {  // byte offsets inside one staging buffer (host pinned and
 enum PassMode { PASS_FULL = 0, PASS_HISTORY, PASS_CANDIDATES };
 
 struct ProfEvent { hipEvent_t a, b; int kind; };
+
+// One captured forward: the graph and the plan tables its kernels read (its own copy, so that eager
+// passes and the other graphs of the handle, which stage their own plans, leave it intact).
+struct CapturedGraph {
+  hipGraphExec_t exec = nullptr;
+  char *tables = nullptr;
+  bool valid = false;
+};
 
 }  // namespace
 
@@ -67,8 +76,7 @@ struct flame_gr {
   Plan plan;
   // explicit-shape executor: the one-pass forward of one fixed batch, captured as a HIP graph
   hipStream_t cap_stream = nullptr;
-  hipGraphExec_t graph_exec = nullptr;
-  bool graph_valid = false;
+  CapturedGraph graphs[kMaxGraphs];
   // two-stage path: what the last prefill cached (layer l keeps its planes at planes + l * plane_set_bytes)
   size_t plane_set_bytes = 0;
   bool kv_valid = false;
@@ -128,7 +136,10 @@ void free_all(flame_gr *h) {
     if (h->gstream[g]) (void)hipStreamDestroy(h->gstream[g]);
     if (h->ev_join[g]) (void)hipEventDestroy(h->ev_join[g]);
   }
-  if (h->graph_exec) (void)hipGraphExecDestroy(h->graph_exec);
+  for (CapturedGraph &g : h->graphs) {
+    if (g.exec) (void)hipGraphExecDestroy(g.exec);
+    (void)hipFree(g.tables);
+  }
   if (h->cap_stream) (void)hipStreamDestroy(h->cap_stream);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_done) (void)hipEventDestroy(h->ev_done);
@@ -271,7 +282,6 @@ void derive_weights(flame_gr *h, const flame_gr_weights *w, hipStream_t s) {
 int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb, const void *cand_emb, float *scores,
                  hipStream_t s0, PassMode mode) {
   const Plan &P = h->plan;
-  h->graph_valid = false;  // the captured forward reads the plan tables and workspaces this pass overwrites
   // stage the plan: one pinned buffer
   const int slot = h->stage_next;
   h->stage_next = (slot + 1) % kStageSlots;
@@ -456,12 +466,13 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   return FLAME_GR_OK;
 }
 
-int flame_gr_capture(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, const void *history_emb,
                      const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
                      int32_t n_requests, float *scores) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  if (slot < 0 || slot >= kMaxGraphs) return bad("graph slot out of range");
   if (h->n_groups != 1) { h->err = "capture needs a handle without internal stream groups (n_streams <= 1)"; return FLAME_GR_UNSUPPORTED; }
   if (h->capture_layer >= 0) { h->err = "capture is not available while a debug layer capture is selected"; return FLAME_GR_UNSUPPORTED; }
   if (!w) return bad("weights is NULL");
@@ -477,15 +488,17 @@ int flame_gr_capture(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   if (!weights_complete(w)) return bad("a weight pointer is NULL");
   // setup, outside the graph: wait for earlier work on the handle, then upload the plan and derive the weights
   if (h->has_prev) HIP_TRY(h, hipEventSynchronize(h->ev_done));
-  h->graph_valid = false;
+  CapturedGraph &cg = h->graphs[slot];
+  cg.valid = false;
   h->kv_valid = false;
   h->cap_valid = false;
-  if (h->graph_exec) { HIP_TRY(h, hipGraphExecDestroy(h->graph_exec)); h->graph_exec = nullptr; }
+  if (cg.exec) { HIP_TRY(h, hipGraphExecDestroy(cg.exec)); cg.exec = nullptr; }
+  if (!cg.tables) HIP_TRY(h, hipMalloc((void **)&cg.tables, h->lay.total));
   if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
   h->plan = std::move(plan);
   const Plan &P = h->plan;
   auto upload = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
-    return bytes ? hipMemcpy(h->stage_dev + off, src, bytes, hipMemcpyHostToDevice) : hipSuccess;
+    return bytes ? hipMemcpy(cg.tables + off, src, bytes, hipMemcpyHostToDevice) : hipSuccess;
   };
   HIP_TRY(h, upload(h->lay.blocks, P.blocks.data(), P.blocks.size() * sizeof(RowBlock)));
   HIP_TRY(h, upload(h->lay.items, P.items.data(), P.items.size() * sizeof(AttnItem)));
@@ -493,37 +506,43 @@ int flame_gr_capture(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   HIP_TRY(h, upload(h->lay.cand_blocks, P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t)));
   derive_weights(h, w, h->cap_stream);
   HIP_TRY(h, hipStreamSynchronize(h->cap_stream));
-  // the layer sequence, recorded instead of run (kernel launches only: no copies, no memsets)
+  // the layer sequence, recorded instead of run (kernel launches only: no copies, no memsets), reading this slot's tables
   const bool prof = h->profiling;
+  char *const eager_tables = h->stage_dev;
   h->profiling = false;
+  h->stage_dev = cg.tables;
   hipGraph_t graph = nullptr;
   hipError_t e = hipStreamBeginCapture(h->cap_stream, hipStreamCaptureModeThreadLocal);
   if (e == hipSuccess) {
     run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, h->cap_stream, PASS_FULL);
     e = hipStreamEndCapture(h->cap_stream, &graph);
   }
+  h->stage_dev = eager_tables;
   h->profiling = prof;
-  if (e == hipSuccess) e = hipGraphInstantiate(&h->graph_exec, graph, nullptr, nullptr, 0);
+  if (e == hipSuccess) e = hipGraphInstantiate(&cg.exec, graph, nullptr, nullptr, 0);
   if (graph) (void)hipGraphDestroy(graph);
   if (e != hipSuccess) {
     (void)hipGetLastError();
-    h->graph_exec = nullptr;
+    cg.exec = nullptr;
     h->err = std::string("graph capture: ") + hipGetErrorString(e);
     return FLAME_GR_HIP_ERROR;
   }
-  h->graph_valid = true;
+  cg.valid = true;
   return FLAME_GR_OK;
 }
 
-int flame_gr_replay(flame_gr_t *h, void *stream_v) {
+int flame_gr_replay(flame_gr_t *h, int32_t slot, void *stream_v) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
-  if (!h->graph_valid) { h->err = "no captured forward on this handle"; return FLAME_GR_INVALID_ARGUMENT; }
+  if (slot < 0 || slot >= kMaxGraphs) { h->err = "graph slot out of range"; return FLAME_GR_INVALID_ARGUMENT; }
+  if (!h->graphs[slot].valid) { h->err = "no captured forward in this slot"; return FLAME_GR_INVALID_ARGUMENT; }
   hipStream_t s0 = (hipStream_t)stream_v;
   if (h->has_prev) HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_done, 0));
-  HIP_TRY(h, hipGraphLaunch(h->graph_exec, s0));
+  HIP_TRY(h, hipGraphLaunch(h->graphs[slot].exec, s0));
   HIP_TRY(h, hipEventRecord(h->ev_done, s0));
   h->has_prev = true;
+  h->kv_valid = false;  // the replay works in the planes of layer 0
+  h->cap_valid = false;
   return FLAME_GR_OK;
 }
 

@@ -1,9 +1,9 @@
-// Request orchestrator (flame_dso.h): explicit-shape executors with captured graphs, index queues
-// per profile, descending-size split routing, pinned staging (Sections 3.1 and 3.3 of the paper).
+// Request orchestrator (flame_dso.h): explicit-shape executors with captured graphs, an executor
+// index queue, descending-size split routing, pinned staging (Sections 3.1 and 3.3 of the paper).
 //
 // Single host thread, no threads of its own: completion is tracked with one event per executor,
-// and an executor's index goes back to its queue when its event is found complete (on wait, drain,
-// or when a submit needs a slot of a profile whose queue is empty).
+// and an executor's index goes back to the queue when its event is found complete (on wait, drain,
+// or when a submit finds the queue empty).
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -24,8 +24,7 @@ struct Pending { int64_t ticket = -1; float *dst = nullptr; int32_t m = 0; };
 
 struct Executor {
   flame_gr_t *h = nullptr;
-  int32_t profile = -1;     // index into profiles (-1: implicit shape, any count up to cap)
-  int32_t cap = 0;          // candidate rows of the buffers
+  int32_t cap = 0;          // candidate rows of the buffers (the largest profile)
   hipStream_t stream = nullptr;
   hipEvent_t done = nullptr;
   char *pin_in = nullptr, *dev_in = nullptr;
@@ -94,7 +93,7 @@ struct flame_dso {
   size_t elt = 2;
   std::vector<int32_t> profiles;
   std::vector<Executor> ex;
-  std::vector<std::deque<int>> free_q, busy_q;  // per profile (one queue each when shapes are implicit)
+  std::deque<int> free_q, busy_q;  // executor indices: free ones, and busy ones in the order they were handed out
   int64_t next_ticket = 1;
   int64_t stats[4] = {0, 0, 0, 0};
   std::string err;
@@ -113,8 +112,6 @@ bool live(const flame_dso *d) { return d && d->magic == kDsoMagic; }
     }                                                                        \
   } while (0)
 
-int queue_of(const flame_dso *d, const Executor &e) { return d->explicit_shapes ? e.profile : 0; }
-
 // The executor's work is complete: deliver its scores and put its index back into the queue.
 int retire(flame_dso *d, int idx) {
   Executor &e = d->ex[idx];
@@ -123,9 +120,8 @@ int retire(flame_dso *d, int idx) {
   std::memcpy(e.pending.dst, e.pin_scores, (size_t)e.pending.m * sizeof(float));
   e.busy = false;
   e.pending = Pending();
-  std::deque<int> &bq = d->busy_q[queue_of(d, e)];
-  bq.erase(std::find(bq.begin(), bq.end(), idx));
-  d->free_q[queue_of(d, e)].push_back(idx);
+  d->busy_q.erase(std::find(d->busy_q.begin(), d->busy_q.end(), idx));
+  d->free_q.push_back(idx);
   return FLAME_GR_OK;
 }
 
@@ -173,7 +169,8 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
   if (!model || !weights || !cfg || !out) return bad("a pointer argument is NULL");
   if (!profiles_ok(cfg->profiles, cfg->n_profiles)) return bad("profiles must be 1..16 strictly ascending positive counts");
   if (cfg->hist_len < 0) return bad("hist_len < 0");
-  if (cfg->executors_per_profile < 1 || cfg->executors_per_profile > 64) return bad("executors_per_profile must be in [1, 64]");
+  if (cfg->n_executors < 1 || cfg->n_executors > 256) return bad("n_executors must be in [1, 256]");
+  if (cfg->explicit_shapes && cfg->n_profiles > FLAME_GR_MAX_GRAPHS) return bad("more profiles than graph slots per executor");
   flame_dso *d = new (std::nothrow) flame_dso();
   if (!d) { g_dso_create_error = "out of host memory"; return FLAME_GR_HIP_ERROR; }
   d->model = *model;
@@ -183,9 +180,6 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
   d->d = model->d_model;
   d->elt = model->dtype == FLAME_GR_BF16 ? 2 : 4;
   d->profiles.assign(cfg->profiles, cfg->profiles + cfg->n_profiles);
-  const int n_queues = d->explicit_shapes ? cfg->n_profiles : 1;
-  d->free_q.resize(n_queues);
-  d->busy_q.resize(n_queues);
   auto fail = [&](int code, const std::string &m) {
     g_dso_create_error = m;
     release_all(d);
@@ -199,39 +193,37 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
     if (e_ != hipSuccess) return fail(FLAME_GR_HIP_ERROR, std::string(#expr) + ": " + hipGetErrorString(e_)); \
   } while (0)
   const size_t row = (size_t)d->d * d->elt;
-  const int n_exec = cfg->n_profiles * cfg->executors_per_profile;
-  d->ex.reserve(n_exec);
-  for (int p = 0; p < cfg->n_profiles; ++p)
-    for (int k = 0; k < cfg->executors_per_profile; ++k) {
-      d->ex.emplace_back();
-      Executor &e = d->ex.back();
-      e.profile = d->explicit_shapes ? p : -1;
-      e.cap = d->explicit_shapes ? d->profiles[p] : d->profiles.back();
-      flame_gr_config c = *model;
-      c.max_requests = 1;
-      c.max_total_tokens = d->L + e.cap;
-      c.max_seq_tokens = 0;
-      c.n_streams = 0;
-      c.kv_cache = 0;
-      int rc = flame_gr_create(&c, &e.h);
-      if (rc) return fail(rc, std::string("executor create: ") + flame_gr_last_error(nullptr));
-      const size_t in_bytes = (size_t)(d->L + e.cap) * row;
-      CR(hipStreamCreateWithFlags(&e.stream, hipStreamNonBlocking));
-      CR(hipEventCreateWithFlags(&e.done, hipEventDisableTiming));
-      CR(hipHostMalloc((void **)&e.pin_in, in_bytes, hipHostMallocDefault));
-      CR(hipHostMalloc((void **)&e.pin_scores, (size_t)e.cap * sizeof(float), hipHostMallocDefault));
-      CR(hipMalloc((void **)&e.dev_in, in_bytes));
-      CR(hipMalloc((void **)&e.dev_scores, (size_t)e.cap * sizeof(float)));
-      // padded candidate rows of a chunk are computed and dropped: they must hold finite values
-      CR(hipMemset(e.dev_in, 0, in_bytes));
-      CR(hipMemset(e.dev_scores, 0, (size_t)e.cap * sizeof(float)));
-      if (d->explicit_shapes) {
-        const int32_t hoff[2] = {0, d->L}, coff[2] = {0, e.cap};
-        rc = flame_gr_capture(e.h, weights, e.dev_in, hoff, e.dev_in + (size_t)d->L * row, coff, 1, e.dev_scores);
+  d->ex.reserve(cfg->n_executors);
+  for (int k = 0; k < cfg->n_executors; ++k) {
+    d->ex.emplace_back();
+    Executor &e = d->ex.back();
+    e.cap = d->profiles.back();
+    flame_gr_config c = *model;
+    c.max_requests = 1;
+    c.max_total_tokens = d->L + e.cap;
+    c.max_seq_tokens = 0;
+    c.n_streams = 0;
+    c.kv_cache = 0;
+    int rc = flame_gr_create(&c, &e.h);
+    if (rc) return fail(rc, std::string("executor create: ") + flame_gr_last_error(nullptr));
+    const size_t in_bytes = (size_t)(d->L + e.cap) * row;
+    CR(hipStreamCreateWithFlags(&e.stream, hipStreamNonBlocking));
+    CR(hipEventCreateWithFlags(&e.done, hipEventDisableTiming));
+    CR(hipHostMalloc((void **)&e.pin_in, in_bytes, hipHostMallocDefault));
+    CR(hipHostMalloc((void **)&e.pin_scores, (size_t)e.cap * sizeof(float), hipHostMallocDefault));
+    CR(hipMalloc((void **)&e.dev_in, in_bytes));
+    CR(hipMalloc((void **)&e.dev_scores, (size_t)e.cap * sizeof(float)));
+    // padded candidate rows of a chunk are computed and dropped: they must hold finite values
+    CR(hipMemset(e.dev_in, 0, in_bytes));
+    CR(hipMemset(e.dev_scores, 0, (size_t)e.cap * sizeof(float)));
+    if (d->explicit_shapes)
+      for (int p = 0; p < cfg->n_profiles; ++p) {      // one graph per profile, all on this executor's buffers
+        const int32_t hoff[2] = {0, d->L}, coff[2] = {0, d->profiles[p]};
+        rc = flame_gr_capture(e.h, p, weights, e.dev_in, hoff, e.dev_in + (size_t)d->L * row, coff, 1, e.dev_scores);
         if (rc) return fail(rc, std::string("executor capture: ") + flame_gr_last_error(e.h));
       }
-      d->free_q[d->explicit_shapes ? p : 0].push_back((int)d->ex.size() - 1);
-    }
+    d->free_q.push_back(k);
+  }
   CR(hipDeviceSynchronize());
 #undef CR
   *out = d;
@@ -254,28 +246,27 @@ int flame_dso_submit(flame_dso_t *d, const void *history_emb, const void *cand_e
   int32_t taken = 0;
   ++d->stats[0];
   for (const Piece &pc : pieces) {
-    const int q = d->explicit_shapes ? pc.profile : 0;
-    if (d->free_q[q].empty()) {
-      // every slot of this profile is in flight: the one handed out earliest comes back first
+    if (d->free_q.empty()) {
+      // every executor is in flight: the one handed out earliest comes back first
       ++d->stats[3];
-      int rc = retire(d, d->busy_q[q].front());
+      int rc = retire(d, d->busy_q.front());
       if (rc) return rc;
     }
-    const int idx = d->free_q[q].front();
-    d->free_q[q].pop_front();
+    const int idx = d->free_q.front();
+    d->free_q.pop_front();
     Executor &e = d->ex[idx];
     const int32_t m = pc.count;
     if (hist_bytes) std::memcpy(e.pin_in, history_emb, hist_bytes);
     std::memcpy(e.pin_in + hist_bytes, (const char *)cand_emb + (size_t)taken * row, (size_t)m * row);
     e.busy = true;
     e.pending = Pending{t, scores + taken, m};
-    d->busy_q[q].push_back(idx);
+    d->busy_q.push_back(idx);
     ++d->stats[1];
-    d->stats[2] += d->explicit_shapes ? e.cap : m;
+    d->stats[2] += d->explicit_shapes ? d->profiles[pc.profile] : m;
     DSO_HIP(d, hipMemcpyAsync(e.dev_in, e.pin_in, hist_bytes + (size_t)m * row, hipMemcpyHostToDevice, e.stream));
     int rc;
     if (d->explicit_shapes) {
-      rc = flame_gr_replay(e.h, e.stream);
+      rc = flame_gr_replay(e.h, pc.profile, e.stream);
     } else {
       const int32_t hoff[2] = {0, d->L}, coff[2] = {0, m};
       rc = flame_gr_forward(e.h, &d->weights, e.dev_in, hoff, e.dev_in + hist_bytes, coff, 1, e.dev_scores, e.stream);

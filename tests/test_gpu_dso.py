@@ -103,11 +103,28 @@ def test_capture_error_paths_and_invalidation(B):
         B.flame_gr_replay(h)
         torch.cuda.synchronize()
         assert np.array_equal(one.cpu().numpy(), ref[:8])
-        # an eager forward reuses the plan tables: the graph is dropped, not left dangling
-        B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
-        torch.cuda.synchronize()
+        # a second slot holds another shape side by side; eager forwards in between stage their own plan
+        # tables and leave both graphs intact
+        B.flame_gr_capture(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores, slot=3)
+        for _ in range(2):
+            scores.fill_(float("nan"))
+            B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+            torch.cuda.synchronize()
+            assert np.array_equal(scores.cpu().numpy(), ref)
+            one.fill_(float("nan"))
+            B.flame_gr_replay(h, slot=0)
+            torch.cuda.synchronize()
+            assert np.array_equal(one.cpu().numpy(), ref[:8])
+            scores.fill_(float("nan"))
+            B.flame_gr_replay(h, slot=3)
+            torch.cuda.synchronize()
+            assert np.array_equal(scores.cpu().numpy(), ref)
+        for slot in (1, -1, 16):
+            with pytest.raises(B.FlameGRError) as e:          # empty slot, slots out of range
+                B.flame_gr_replay(h, slot=slot)
+            assert e.value.code == -1
         with pytest.raises(B.FlameGRError) as e:
-            B.flame_gr_replay(h)
+            B.flame_gr_capture(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores, slot=16)
         assert e.value.code == -1
     finally:
         B.flame_gr_destroy(h)
@@ -136,7 +153,7 @@ def test_orchestrator_scores_every_request(B, dtype, explicit):
     reqs = _requests(shape, L, Ms, seed=21, dtype=dtype)
     dw, _, _ = B.to_device(reqs[0])
     cfg = B.config_for(reqs[0])
-    dso = B.flame_dso_create(cfg, dw, L, profiles, executors_per_profile=2, explicit_shapes=explicit)
+    dso = B.flame_dso_create(cfg, dw, L, profiles, n_executors=3, explicit_shapes=explicit)
     try:
         outs = [np.full(M, np.nan, np.float32) for M in Ms]
         tickets = []
@@ -176,8 +193,8 @@ def test_orchestrator_rejects_bad_configurations(B):
     wl = stress([10], [4], 64, 2, "bf16", nb=16, D=128, name="dsoerr")
     dw, _, _ = B.to_device(wl)
     cfg = B.config_for(wl)
-    for kw in (dict(profiles=[], executors_per_profile=1), dict(profiles=[8, 4], executors_per_profile=1),
-               dict(profiles=[4], executors_per_profile=0), dict(profiles=[4], executors_per_profile=65)):
+    for kw in (dict(profiles=[], n_executors=1), dict(profiles=[8, 4], n_executors=1),
+               dict(profiles=[4], n_executors=0), dict(profiles=[4], n_executors=257)):
         with pytest.raises(B.FlameGRError) as e:
             B.flame_dso_create(cfg, dw, 10, **kw)
         assert e.value.code == -1
