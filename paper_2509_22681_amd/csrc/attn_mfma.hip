@@ -403,7 +403,7 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
     for (int t = 0; t < 32 / RPI; ++t) {
       const int row = t * RPI + rl;
       const f16x8 v = *(const f16x8 *)(pb + row * (DH * 2) + ((c ^ pkey(row)) << 4));
-      if (q_local0 + row < it.n_q) *(f16x8 *)(obase + (int64_t)(q_local0 + row) * d) = v;
+      if (q_local0 + row < it.n_q) __builtin_nontemporal_store(v, (f16x8 *)(obase + (int64_t)(q_local0 + row) * d));
     }
   }
 }

@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
         const int row = it * RPI + rl;
         const f16x8 v = *(const f16x8 *)(pb + row * (WN * 2) + ((c ^ patch_key<CPR>(row)) << 4));
         const int rblk = row >= 64 ? b1 : b0;
-        if (rblk >= 0) *(f16x8 *)(pcol + ((int64_t)rblk * kRowAlign + (row & 63)) * d) = v;
+        if (rblk >= 0) __builtin_nontemporal_store(v, (f16x8 *)(pcol + ((int64_t)rblk * kRowAlign + (row & 63)) * d));
       }
     } else {
       // patch[WN features][128 tokens]; lane holds feature 32j + l32, tokens 32i + 16*lhalf + 0..15
@@ -323,7 +323,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
         for (int it = 0; it < WN / 4; ++it) {
           const int fr = it * 4 + rl;
           const f16x8 v = *(const f16x8 *)(pb + fr * 256 + (((c ^ fr) & 15) << 4));
-          *(f16x8 *)(prow + (int64_t)fr * ws_rows) = v;
+          __builtin_nontemporal_store(v, (f16x8 *)(prow + (int64_t)fr * ws_rows));
         }
       }
     }

@@ -242,8 +242,8 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
         o[q] = to_f16_sat(x[q]);
       }
       const int64_t m = row0 + 32 * i + row;
-      *(f32x4 *)(X + m * d + n) = x;
-      *(f16x4 *)(Xh + blocked_index(m, n, d)) = o;
+      __builtin_nontemporal_store(x, (f32x4 *)(X + m * d + n));
+      __builtin_nontemporal_store(o, (f16x4 *)(Xh + blocked_index(m, n, d)));
     }
   }
 }
