@@ -26,6 +26,20 @@ Readings taken where the sources are silent (each is also listed in the design d
   - LayerNorm over the full model width with biased variance;
   - the relative-position bucket function below (integer only).
 
+Softmax variant (the paper's own model, Section 2.1: Transformer blocks with "an adaptive temperature
+coefficient ... before softmax", the user sequence cut into N_b sub-sequences that independent blocks
+process, every candidate appended to each sub-sequence, block outputs joined by a "bit-wise gating
+fusion module", task probabilities from the "expert module of the top-level multi-layer
+perceptron").  The paper gives prose only; the readings taken here:
+  - cfg["attn_kind"] == "softmax": the attention weights of a row are softmax over its allowed keys of
+    (alpha <Q_r,K_c> + rab[bucket]) / tau[l,h], tau a positive learned scalar per layer and head
+    (w["temperature"]); everything else in the block is unchanged;
+  - sub-sequence b of N_b is the contiguous slice [floor(b L / N_b), floor((b+1) L / N_b)) of the history,
+    positions restart at 0 inside a slice; block b has its own weights and sees all candidates;
+  - fusion: with H_b [M,d] the candidates' final residual rows of block b and C = [H_0 | ... | H_{N_b-1}],
+    g_b = sigmoid(C Wg_b^T + cg_b) elementwise over the d features ("bit-wise" = per feature), F = sum_b g_b * H_b;
+  - head: T tasks, p_t = sigmoid(<v_t, relu(F A_t^T + a_t)> + c_t) with expert width E.
+
 Parity status: the paper prints no model output, so against the paper itself this oracle is
 "parity unpinned".  It is pinned instead (tests/test_oracle_*.py) by a hand-worked case, by the
 scalar-loop transcription `forward_request_loops` on tiny inputs, by closed forms that reduce to a
@@ -126,16 +140,28 @@ def merged_token_offsets(history_offsets, cand_offsets) -> np.ndarray:
 # ----------------------------------------------------------------------------------------------
 # the forward, vectorised per request
 # ----------------------------------------------------------------------------------------------
+def masked_softmax(z, allow):
+    """Row-wise softmax of z over the entries where allow is True (0 elsewhere); every row of `allow`
+    has at least one True."""
+    z = np.where(allow, np.asarray(z, F64), -np.inf)
+    z = z - z.max(axis=-1, keepdims=True)
+    e = np.where(allow, np.exp(z), 0.0)
+    return e / e.sum(axis=-1, keepdims=True)
+
+
 def forward_request(cfg: dict, w: Dict[str, np.ndarray], hist: np.ndarray, cand: np.ndarray,
-                    stages: Optional[List[dict]] = None) -> np.ndarray:
-    """Scores of one request.  hist [L,d], cand [M,d]; returns [M].
+                    stages: Optional[List[dict]] = None, hidden: bool = False) -> np.ndarray:
+    """Scores of one request.  hist [L,d], cand [M,d]; returns [M] (or, with hidden=True, the
+    candidates' final residual rows [M,d] instead of their scores).
 
     If `stages` is a list, one dict per layer with the tensors U,V,Q,K,O,X (X after the residual)
-    is appended to it.
+    is appended to it.  cfg["attn_kind"] ("silu", the default, or "softmax") selects the attention
+    weights (see the file header).
     """
     d, H, Ly = cfg["d_model"], cfg["n_heads"], cfg["n_layers"]
     nb, D = cfg["n_buckets"], cfg["max_rel_dist"]
     eps, alpha = cfg["ln_eps"], cfg["attn_scale"]
+    softmax = cfg.get("attn_kind", "silu") == "softmax"
     dh = d // H
     L, M = hist.shape[0], cand.shape[0]
     X = np.concatenate([np.asarray(hist, F64).reshape(L, d), np.asarray(cand, F64).reshape(M, d)], 0)
@@ -151,30 +177,76 @@ def forward_request(cfg: dict, w: Dict[str, np.ndarray], hist: np.ndarray, cand:
         for h in range(H):
             sl = slice(h * dh, (h + 1) * dh)
             S = alpha * (Q[:, sl] @ K[:, sl].T) + np.asarray(w["rab"][l, h], F64)[bkt_safe]
-            Wgt = np.where(allow, silu(S), 0.0)
+            if softmax:
+                Wgt = masked_softmax(S / float(w["temperature"][l, h]), allow)
+            else:
+                Wgt = np.where(allow, silu(S), 0.0)
             O[:, sl] = Wgt @ V[:, sl]
         Y = layernorm(O, np.asarray(w["ln_g"][l], F64), np.asarray(w["ln_b"][l], F64), eps) * U
         X = X + Y @ np.asarray(w["w2"][l], F64).T + np.asarray(w["b2"][l], F64)
         if stages is not None:
             stages.append(dict(U=U, V=V, Q=Q, K=K, O=O, X=X.copy()))
+    if hidden:
+        return X[L:].copy()
     return X[L:] @ np.asarray(w["w_s"], F64) + float(w["b_s"])
 
 
 def forward(cfg: dict, w: Dict[str, np.ndarray], history_emb, history_offsets, cand_emb,
-            cand_offsets, stages: Optional[List[List[dict]]] = None) -> np.ndarray:
-    """Scores of a jagged batch, in cand_offsets order.  Requests are independent."""
+            cand_offsets, stages: Optional[List[List[dict]]] = None, hidden: bool = False) -> np.ndarray:
+    """Scores of a jagged batch, in cand_offsets order (hidden=True: the candidates' final residual
+    rows [sum M, d]).  Requests are independent."""
     ho = np.asarray(history_offsets, np.int64)
     co = np.asarray(cand_offsets, np.int64)
     B = len(ho) - 1
     assert len(co) - 1 == B
-    scores = np.zeros(int(co[-1]) if B >= 0 and len(co) else 0, F64)
+    n_out = int(co[-1]) if B >= 0 and len(co) else 0
+    scores = np.zeros((n_out, cfg["d_model"]) if hidden else n_out, F64)
     for i in range(B):
         st = [] if stages is not None else None
         scores[co[i]:co[i + 1]] = forward_request(
-            cfg, w, history_emb[ho[i]:ho[i + 1]], cand_emb[co[i]:co[i + 1]], st)
+            cfg, w, history_emb[ho[i]:ho[i + 1]], cand_emb[co[i]:co[i + 1]], st, hidden)
         if stages is not None:
             stages.append(st)
     return scores
+
+
+# ----------------------------------------------------------------------------------------------
+# sub-sequence blocks, gating fusion and the task head (Section 2.1; readings in the file header)
+# ----------------------------------------------------------------------------------------------
+def sigmoid(x):
+    x = np.asarray(x, dtype=F64)
+    e = np.exp(-np.abs(x))
+    return np.where(x >= 0, 1.0 / (1.0 + e), e / (1.0 + e))
+
+
+def block_slices(L: int, n_blocks: int) -> List[slice]:
+    """Contiguous sub-sequences of a history of L items: block b takes [floor(b L / N_b), floor((b+1) L / N_b))."""
+    return [slice(b * L // n_blocks, (b + 1) * L // n_blocks) for b in range(n_blocks)]
+
+
+def fuse_and_score(head: Dict[str, np.ndarray], hidden_blocks: List[np.ndarray]) -> np.ndarray:
+    """hidden_blocks: N_b arrays [M,d].  Returns task probabilities [M,T].
+    head: wg [N_b][d][N_b*d], cg [N_b][d], a_w [T][E][d], a_b [T][E], v [T][E], c [T]."""
+    Hs = [np.asarray(h, F64) for h in hidden_blocks]
+    C = np.concatenate(Hs, axis=1)
+    F = np.zeros_like(Hs[0])
+    for b, Hb in enumerate(Hs):
+        F += sigmoid(C @ np.asarray(head["wg"][b], F64).T + np.asarray(head["cg"][b], F64)) * Hb
+    T = len(head["c"])
+    out = np.zeros((F.shape[0], T), F64)
+    for t in range(T):
+        E = np.maximum(F @ np.asarray(head["a_w"][t], F64).T + np.asarray(head["a_b"][t], F64), 0.0)
+        out[:, t] = sigmoid(E @ np.asarray(head["v"][t], F64) + float(head["c"][t]))
+    return out
+
+
+def climber_request(cfg: dict, block_weights: List[Dict[str, np.ndarray]], head: Dict[str, np.ndarray],
+                    hist: np.ndarray, cand: np.ndarray) -> np.ndarray:
+    """Task probabilities [M,T] of one request through N_b = len(block_weights) independent blocks."""
+    hist = np.asarray(hist)
+    hs = [forward_request(cfg, wb, hist[sl], cand, hidden=True)
+          for wb, sl in zip(block_weights, block_slices(hist.shape[0], len(block_weights)))]
+    return fuse_and_score(head, hs)
 
 
 # ----------------------------------------------------------------------------------------------
@@ -185,6 +257,7 @@ def forward_request_loops(cfg: dict, w, hist, cand) -> List[float]:
     d, H, Ly = cfg["d_model"], cfg["n_heads"], cfg["n_layers"]
     nb, D = cfg["n_buckets"], cfg["max_rel_dist"]
     eps, alpha = cfg["ln_eps"], cfg["attn_scale"]
+    softmax = cfg.get("attn_kind", "silu") == "softmax"
     dh = d // H
     L, M = len(hist), len(cand)
     N = L + M
@@ -200,20 +273,25 @@ def forward_request_loops(cfg: dict, w, hist, cand) -> List[float]:
         O = [[0.0] * d for _ in range(N)]
         for r in range(N):
             pr = r if r < L else L
-            for c in range(N):
-                if r < L:
-                    ok = c <= r
-                else:
-                    ok = c < L or c == r
-                if not ok:
-                    continue
-                pc = c if c < L else L
-                bk = bucket_scalar(pr - pc, nb, D)
-                for h in range(H):
+            keys = [c for c in range(N) if (c <= r if r < L else (c < L or c == r))]
+            for h in range(H):
+                logit = []
+                for c in keys:
+                    pc = c if c < L else L
+                    bk = bucket_scalar(pr - pc, nb, D)
                     dot = 0.0
                     for k in range(dh):
                         dot += A[r][2 * d + h * dh + k] * A[c][3 * d + h * dh + k]
-                    wgt = s(alpha * dot + float(w["rab"][l][h][bk]))
+                    logit.append(alpha * dot + float(w["rab"][l][h][bk]))
+                if softmax:
+                    tau = float(w["temperature"][l][h])
+                    top = max(v / tau for v in logit)
+                    ex = [math.exp(v / tau - top) for v in logit]
+                    tot = sum(ex)
+                    wgts = [e / tot for e in ex]
+                else:
+                    wgts = [s(v) for v in logit]
+                for c, wgt in zip(keys, wgts):
                     for k in range(dh):
                         O[r][h * dh + k] += wgt * A[c][d + h * dh + k]
         for r in range(N):
