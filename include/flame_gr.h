@@ -51,6 +51,14 @@ typedef enum {
 
 typedef enum { FLAME_GR_F32 = 0, FLAME_GR_BF16 = 1 } flame_gr_dtype;
 
+/* Attention weights of a query row r over its allowed keys c, with logit z_rc = alpha <Q_r,K_c> +
+ * rab[l,h,bucket(p_r-p_c)]:
+ *   FLAME_GR_ATTN_SILU     w_rc = silu(z_rc), pointwise (the block stated at the top of this header);
+ *   FLAME_GR_ATTN_SOFTMAX  w_rc = softmax over c of z_rc / tau[l,h]: the softmax attention with an adaptive
+ *                          temperature coefficient of the paper's own model (Section 2.1), tau > 0 a weight
+ *                          per layer and head. */
+typedef enum { FLAME_GR_ATTN_SILU = 0, FLAME_GR_ATTN_SOFTMAX = 1 } flame_gr_attn_kind;
+
 /* Model shape and capacity.  Fixed for the life of a handle. */
 typedef struct {
   int32_t n_layers;      /* >= 1 */
@@ -69,6 +77,7 @@ typedef struct {
   int32_t n_streams;         /* 0 or 1 = everything on the caller's stream; k > 1 = requests are
                                 partitioned into k cost-balanced groups that run on k internal
                                 streams, joined to the caller's stream by events (Section 3.3) */
+  int32_t attn_kind;         /* flame_gr_attn_kind */
   int32_t kv_cache;          /* 0 = one-pass forward only; 1 = also allocate per-layer U/V/Q/K workspaces
                                 (n_layers times the one-pass amount) so that flame_gr_prefill and
                                 flame_gr_score can keep the history keys and values of every layer */
@@ -84,8 +93,9 @@ typedef struct {
   const void *ln_b;   /* [n_layers][d] */
   const void *w2;     /* [n_layers][d][d] */
   const void *b2;     /* [n_layers][d] */
-  const void *w_s;    /* [d] */
+  const void *w_s;    /* [d]   (may be NULL for flame_gr_forward_hidden) */
   float b_s;
+  const float *temperature; /* [n_layers][n_heads] fp32, > 0; read only with FLAME_GR_ATTN_SOFTMAX */
 } flame_gr_weights;
 
 /* Create a handle on the current HIP device and allocate all workspaces for the given capacity.
@@ -113,6 +123,15 @@ int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *weights,
                      const void *history_emb, const int32_t *history_offsets,
                      const void *cand_emb, const int32_t *cand_offsets,
                      int32_t n_requests, float *scores, void *stream);
+
+/* As flame_gr_forward, but instead of scores the call delivers the candidates' final residual rows
+ * (the input of the score head): hidden is device fp32 [sum M_i][d] in cand_offsets order.  This is
+ * what a stage above the block stack consumes, e.g. the fusion of several sub-sequence blocks
+ * (flame_climber_head).  weights->w_s is not read.  UNSUPPORTED when max_seq_tokens splits a request. */
+int flame_gr_forward_hidden(flame_gr_t *h, const flame_gr_weights *weights,
+                            const void *history_emb, const int32_t *history_offsets,
+                            const void *cand_emb, const int32_t *cand_offsets,
+                            int32_t n_requests, float *hidden, void *stream);
 
 /* Explicit-shape executor (Section 3.3): with the batch shape fixed, the whole forward is recorded
  * once into a HIP graph and later requests of that shape replay it with one call instead of one

@@ -28,6 +28,7 @@ if not os.path.exists(LIB_PATH):
 _lib = C.CDLL(LIB_PATH)
 
 FLAME_GR_F32, FLAME_GR_BF16 = 0, 1
+FLAME_GR_ATTN_SILU, FLAME_GR_ATTN_SOFTMAX = 0, 1
 STATUS = {0: "OK", -1: "INVALID_ARGUMENT", -2: "CAPACITY_EXCEEDED", -3: "HIP_ERROR", -4: "BAD_HANDLE",
           -5: "UNSUPPORTED"}
 KERNEL_KINDS = ("assemble", "bias", "uvqk", "attn", "ln_gate", "outproj", "score")
@@ -38,13 +39,14 @@ class flame_gr_config(C.Structure):
                 ("n_buckets", C.c_int32), ("max_rel_dist", C.c_int32), ("dtype", C.c_int32),
                 ("ln_eps", C.c_float), ("attn_scale", C.c_float),
                 ("max_requests", C.c_int32), ("max_total_tokens", C.c_int32),
-                ("max_seq_tokens", C.c_int32), ("n_streams", C.c_int32), ("kv_cache", C.c_int32)]
+                ("max_seq_tokens", C.c_int32), ("n_streams", C.c_int32), ("attn_kind", C.c_int32),
+                ("kv_cache", C.c_int32)]
 
 
 class flame_gr_weights(C.Structure):
     _fields_ = [("w1", C.c_void_p), ("b1", C.c_void_p), ("rab", C.c_void_p), ("ln_g", C.c_void_p),
                 ("ln_b", C.c_void_p), ("w2", C.c_void_p), ("b2", C.c_void_p), ("w_s", C.c_void_p),
-                ("b_s", C.c_float)]
+                ("b_s", C.c_float), ("temperature", C.c_void_p)]
 
 
 _i32p = C.POINTER(C.c_int32)
@@ -53,6 +55,8 @@ _lib.flame_gr_create.restype = C.c_int
 _lib.flame_gr_forward.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p, C.c_void_p]
 _lib.flame_gr_forward.restype = C.c_int
+_lib.flame_gr_forward_hidden.argtypes = _lib.flame_gr_forward.argtypes
+_lib.flame_gr_forward_hidden.restype = C.c_int
 _lib.flame_gr_capture.argtypes = [C.c_void_p, C.c_int32, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p]
 _lib.flame_gr_capture.restype = C.c_int
@@ -111,7 +115,7 @@ _lib.flame_dso_stats.restype = C.c_int
 DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_wait", "flame_dso_drain", "flame_dso_destroy",
                "flame_dso_last_error", "flame_dso_route", "flame_dso_stats")
 
-EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
+EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_forward_hidden", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
            "flame_gr_last_error",
            "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan", "flame_gr_host_plan_reserved",
            "flame_gr_debug_capture", "flame_gr_debug_stage", "flame_gr_debug_device_mask",
@@ -144,10 +148,12 @@ def _ptr(t) -> Optional[int]:
 
 
 def make_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dtype, *, ln_eps=1e-6, attn_scale=1.0,
-                max_requests=0, max_total_tokens=0, max_seq_tokens=0, n_streams=0, kv_cache=0) -> flame_gr_config:
+                max_requests=0, max_total_tokens=0, max_seq_tokens=0, n_streams=0, kv_cache=0,
+                attn_kind="silu") -> flame_gr_config:
     dt = {"f32": FLAME_GR_F32, "bf16": FLAME_GR_BF16}.get(dtype, dtype)
+    ak = {"silu": FLAME_GR_ATTN_SILU, "softmax": FLAME_GR_ATTN_SOFTMAX}.get(attn_kind, attn_kind)
     return flame_gr_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dt, ln_eps, attn_scale,
-                           max_requests, max_total_tokens, max_seq_tokens, n_streams, int(kv_cache))
+                           max_requests, max_total_tokens, max_seq_tokens, n_streams, ak, int(kv_cache))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -166,7 +172,8 @@ def flame_gr_destroy(h) -> None:
 def pack_weights(w: Dict[str, object]) -> flame_gr_weights:
     """dict of device tensors (+ python float b_s) -> struct of device pointers."""
     return flame_gr_weights(_ptr(w["w1"]), _ptr(w["b1"]), _ptr(w["rab"]), _ptr(w["ln_g"]), _ptr(w["ln_b"]),
-                            _ptr(w["w2"]), _ptr(w["b2"]), _ptr(w["w_s"]), float(w["b_s"]))
+                            _ptr(w["w2"]), _ptr(w["b2"]), _ptr(w.get("w_s")), float(w.get("b_s", 0.0)),
+                            _ptr(w.get("temperature")))
 
 
 def flame_gr_forward(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores, stream=None) -> None:
@@ -226,6 +233,18 @@ def flame_gr_score(h, weights, cand_emb, cand_offsets, scores, stream=None) -> N
     co = _i32(cand_offsets)
     rc = _lib.flame_gr_score(h, C.byref(ws), _ptr(cand_emb), co.ctypes.data_as(_i32p), len(co) - 1, _ptr(scores),
                              C.c_void_p(_stream_ptr(stream)))
+    _check(rc, h)
+
+
+def flame_gr_forward_hidden(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, hidden, stream=None) -> None:
+    """As flame_gr_forward, with the candidates' final residual rows (device fp32 [sum M, d]) as the output."""
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    ho, co = _i32(history_offsets), _i32(cand_offsets)
+    n = len(ho) - 1
+    if len(co) - 1 != n:
+        raise ValueError("offset arrays differ in length")
+    rc = _lib.flame_gr_forward_hidden(h, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
+                                      co.ctypes.data_as(_i32p), n, _ptr(hidden), C.c_void_p(_stream_ptr(stream)))
     _check(rc, h)
 
 
@@ -399,6 +418,8 @@ def to_device(workload, device="cuda:0"):
     dw = {k: up(w[k]) for k in ("w1", "b1", "ln_g", "ln_b", "w2", "b2", "w_s")}
     dw["rab"] = up(w["rab"], torch.float32)
     dw["b_s"] = float(w["b_s"])
+    if "temperature" in w:
+        dw["temperature"] = up(w["temperature"], torch.float32)
     return dw, up(workload.history_emb), up(workload.cand_emb)
 
 
@@ -408,4 +429,5 @@ def config_for(workload, *, n_streams=0, max_seq_tokens=0, slack_requests=0, kv_
     return make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype,
                        ln_eps=c.ln_eps, attn_scale=c.attn_scale,
                        max_requests=workload.n_requests + slack_requests, max_total_tokens=tot + slack_tokens,
-                       max_seq_tokens=max_seq_tokens, n_streams=n_streams, kv_cache=kv_cache)
+                       max_seq_tokens=max_seq_tokens, n_streams=n_streams, kv_cache=kv_cache,
+                       attn_kind=getattr(c, "attn_kind", "silu"))

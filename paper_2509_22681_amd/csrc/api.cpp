@@ -60,6 +60,7 @@ struct flame_gr {
   void *Xb = nullptr, *planes = nullptr, *O = nullptr, *G = nullptr;   // Xb: fp16 copy of X (MFMA path)
   void *W1h = nullptr, *W2h = nullptr, *W2p = nullptr;                   // fp16 copies of the projection matrices (W2p: fragment-major)
   float *bias = nullptr;
+  float *tscale = nullptr;                                               // softmax: logit scale per layer and head
   int32_t *bucket_tab = nullptr;
   // plan staging
   StageLayout lay{};
@@ -125,7 +126,7 @@ float half_bits_to_float(uint16_t b) {
 
 void free_all(flame_gr *h) {
   (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->O); (void)hipFree(h->G);
-  (void)hipFree(h->bias); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
+  (void)hipFree(h->bias); (void)hipFree(h->tscale); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
   (void)hipFree(h->W1h); (void)hipFree(h->W2h); (void)hipFree(h->W2p);
   (void)hipFree(h->cap_planes); (void)hipFree(h->cap_O); (void)hipFree(h->cap_X);
   for (int i = 0; i < kStageSlots; ++i) {
@@ -168,7 +169,7 @@ struct Timed {
 // on its own set of planes, so that the candidate pass finds K and V of the history rows of layer l
 // where the history pass left them.
 void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const void *hist, const void *cand,
-               float *scores, hipStream_t s, PassMode mode) {
+               float *scores, hipStream_t s, PassMode mode, float *hidden = nullptr) {
   const Shape &sh = h->sh;
   const int dt = h->cfg.dtype;
   const int d = sh.d;
@@ -202,6 +203,7 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
     const char *lg = (const char *)w.ln_g + (size_t)l * d * e;
     const char *lb = (const char *)w.ln_b + (size_t)l * d * e;
     const float *bias_l = h->bias + (size_t)l * sh.H * sh.D;
+    const float *tscale_l = h->tscale ? h->tscale + (size_t)l * sh.H : nullptr;
     // In the last layer only candidate rows feed the scores, and history rows never look at
     // candidates: history rows need K and V only, attention and the output projection run on
     // candidate rows only.
@@ -224,8 +226,8 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
       int n_it = G.item_end - G.item_begin;
       if (mode == PASS_HISTORY) { it = hitems + G.hitem_begin; n_it = G.hitem_end - G.hitem_begin; }
       else if (mode == PASS_CANDIDATES || last) { it = citems + G.citem_begin; n_it = G.citem_end - G.citem_begin; }
-      if (dt == FLAME_GR_BF16) launch_attn_bf16(planes, bias_l, h->O, it, n_it, sh, s);
-      else launch_attn_f32((const float *)planes, bias_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
+      if (dt == FLAME_GR_BF16) launch_attn_bf16(planes, bias_l, tscale_l, h->O, it, n_it, sh, s);
+      else launch_attn_f32((const float *)planes, bias_l, tscale_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
     }
     const int32_t *bl = mode == PASS_FULL ? (last ? cl : nullptr) : pass_list;
     const int nb = mode == PASS_FULL ? (last ? n_cblk : n_blk) : pass_n;
@@ -261,7 +263,8 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
   if (mode == PASS_HISTORY) return;
   {
     Timed t(h, KIND_SCORE, s);
-    launch_scores(dt, h->X, w.w_s, w.b_s, blocks, cl, n_cblk, scores, d, s);
+    if (hidden) launch_gather_hidden(h->X, blocks, cl, n_cblk, hidden, d, s);
+    else launch_scores(dt, h->X, w.w_s, w.b_s, blocks, cl, n_cblk, scores, d, s);
   }
 }
 
@@ -276,11 +279,15 @@ void derive_weights(flame_gr *h, const flame_gr_weights *w, hipStream_t s) {
   }
   launch_expand_bias(w->rab, h->bucket_tab, h->bias, h->sh.n_layers * h->sh.H, h->sh.n_buckets, h->sh.D,
                      h->cfg.dtype == FLAME_GR_BF16 ? 0.5f : 1.0f, s);
+  // softmax: exponent = logit / tau.  The MFMA kernel holds halved logits and uses the base-2 exponential.
+  if (h->sh.softmax)
+    launch_logit_scale(w->temperature, h->tscale, h->sh.n_layers * h->sh.H,
+                       h->cfg.dtype == FLAME_GR_BF16 ? 2.0f * 1.4426950408889634f : 1.0f, s);
 }
 
 // Stage h->plan through pinned memory, refresh the derived weights and run `mode` on every stream group.
 int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb, const void *cand_emb, float *scores,
-                 hipStream_t s0, PassMode mode) {
+                 hipStream_t s0, PassMode mode, float *hidden = nullptr) {
   const Plan &P = h->plan;
   // stage the plan: one pinned buffer
   const int slot = h->stage_next;
@@ -313,13 +320,13 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
     derive_weights(h, w, s0);
   }
   if (h->n_groups == 1) {
-    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0, mode);
+    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, s0, mode, hidden);
   } else {
     HIP_TRY(h, hipEventRecord(h->ev_fork, s0));
     for (int g = 0; g < h->n_groups; ++g) {
       if (P.groups[g].blk_end == P.groups[g].blk_begin) continue;
       HIP_TRY(h, hipStreamWaitEvent(h->gstream[g], h->ev_fork, 0));
-      run_group(h, *w, P.groups[g], history_emb, cand_emb, scores, h->gstream[g], mode);
+      run_group(h, *w, P.groups[g], history_emb, cand_emb, scores, h->gstream[g], mode, hidden);
       HIP_TRY(h, hipEventRecord(h->ev_join[g], h->gstream[g]));
       HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_join[g], 0));
     }
@@ -331,8 +338,10 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
   return FLAME_GR_OK;
 }
 
-bool weights_complete(const flame_gr_weights *w) {
-  return w->w1 && w->b1 && w->rab && w->ln_g && w->ln_b && w->w2 && w->b2 && w->w_s;
+// w_s may be absent when the caller asks for hidden rows instead of scores
+bool weights_complete(const flame_gr *h, const flame_gr_weights *w, bool need_score_head = true) {
+  return w->w1 && w->b1 && w->rab && w->ln_g && w->ln_b && w->w2 && w->b2 && (w->w_s || !need_score_head) &&
+         (w->temperature || !h->sh.softmax);
 }
 
 }  // namespace
@@ -361,7 +370,7 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   h->elt = cfg.dtype == FLAME_GR_BF16 ? 2 : 4;
   h->ws_rows = workspace_rows(cfg);
   h->sh = Shape{cfg.d_model, cfg.n_heads, cfg.d_model / cfg.n_heads, cfg.n_layers, cfg.n_buckets,
-                cfg.max_rel_dist, cfg.ln_eps, cfg.attn_scale, h->ws_rows};
+                cfg.max_rel_dist, cfg.ln_eps, cfg.attn_scale, h->ws_rows, cfg.attn_kind == FLAME_GR_ATTN_SOFTMAX ? 1 : 0};
   auto fail = [&](const std::string &m, int code) {
     g_create_error = m;
     free_all(h);
@@ -390,6 +399,7 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   }
   CR(hipMalloc(&h->bias, (size_t)cfg.n_layers * cfg.n_heads * cfg.max_rel_dist * sizeof(float)));
   CR(hipMalloc(&h->bucket_tab, (size_t)cfg.max_rel_dist * sizeof(int32_t)));
+  if (h->sh.softmax) CR(hipMalloc(&h->tscale, (size_t)cfg.n_layers * cfg.n_heads * sizeof(float)));
   // Every workspace starts finite: rows that a batch leaves as padding are read (and multiplied
   // by zero weights) by the tiled kernels.
   CR(hipMemset(h->X, 0, rows * d * sizeof(float)));
@@ -440,30 +450,52 @@ int flame_gr_destroy(flame_gr_t *h) {
   return FLAME_GR_OK;
 }
 
-int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
-                     const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
-                     int32_t n_requests, float *scores, void *stream_v) {
+static int forward_common(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+                          const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
+                          int32_t n_requests, float *scores, float *hidden, void *stream_v) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  const bool want_hidden = scores == nullptr && hidden != nullptr;
   if (!w) return bad("weights is NULL");
   if (n_requests < 0) return bad("n_requests < 0");
   if (n_requests > 0 && (!history_offsets || !cand_offsets)) return bad("offset arrays are NULL");
   Plan plan;
   int rc = build_plan(h->cfg, history_offsets, cand_offsets, n_requests, h->q_tile, h->n_groups, h->ws_rows, plan, h->err);
   if (rc) return rc;
+  if (want_hidden && plan.split) { h->err = "hidden rows are not available for split requests"; return FLAME_GR_UNSUPPORTED; }
   const int64_t sumL = n_requests ? history_offsets[n_requests] : 0, sumM = n_requests ? cand_offsets[n_requests] : 0;
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
-  if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
-  if (plan.total_rows > 0 && !weights_complete(w)) return bad("a weight pointer is NULL");
+  if (sumM > 0 && (!cand_emb || (!scores && !hidden))) return bad("cand_emb or the output array is NULL");
+  if (plan.total_rows > 0 && !weights_complete(h, w, !want_hidden)) return bad("a weight pointer is NULL");
   h->plan = std::move(plan);
   h->cap_valid = false;
   h->kv_valid = false;  // the one-pass forward works in the planes of layer 0
   if (h->plan.total_rows == 0) return FLAME_GR_OK;
-  rc = enqueue_pass(h, w, history_emb, cand_emb, scores, (hipStream_t)stream_v, PASS_FULL);
+  rc = enqueue_pass(h, w, history_emb, cand_emb, scores, (hipStream_t)stream_v, PASS_FULL, want_hidden ? hidden : nullptr);
   if (rc) return rc;
   h->cap_valid = h->capture_layer >= 0 && h->cap_planes;
   return FLAME_GR_OK;
+}
+
+int flame_gr_forward(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+                     const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
+                     int32_t n_requests, float *scores, void *stream_v) {
+  if (live(h) && n_requests > 0 && cand_offsets && cand_offsets[n_requests] > 0 && !scores) {
+    h->err = "cand_emb or scores is NULL";
+    return FLAME_GR_INVALID_ARGUMENT;
+  }
+  return forward_common(h, w, history_emb, history_offsets, cand_emb, cand_offsets, n_requests, scores, nullptr, stream_v);
+}
+
+int flame_gr_forward_hidden(flame_gr_t *h, const flame_gr_weights *w, const void *history_emb,
+                            const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
+                            int32_t n_requests, float *hidden, void *stream_v) {
+  if (live(h) && n_requests > 0 && cand_offsets && cand_offsets[n_requests] > 0 && !hidden) {
+    h->err = "cand_emb or hidden is NULL";
+    return FLAME_GR_INVALID_ARGUMENT;
+  }
+  return forward_common(h, w, history_emb, history_offsets, cand_emb, cand_offsets, n_requests, nullptr, hidden, stream_v);
 }
 
 int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, const void *history_emb,
@@ -485,7 +517,7 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
   if (sumM == 0) return bad("nothing to capture: the batch has no candidates");
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
   if (!cand_emb || !scores) return bad("cand_emb or scores is NULL");
-  if (!weights_complete(w)) return bad("a weight pointer is NULL");
+  if (!weights_complete(h, w)) return bad("a weight pointer is NULL");
   // setup, outside the graph: wait for earlier work on the handle, then upload the plan and derive the weights
   if (h->has_prev) HIP_TRY(h, hipEventSynchronize(h->ev_done));
   CapturedGraph &cg = h->graphs[slot];
@@ -563,7 +595,7 @@ int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   if (rc) return rc;
   const int64_t sumL = n_requests ? history_offsets[n_requests] : 0;
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
-  if (sumL > 0 && !weights_complete(w)) return bad("a weight pointer is NULL");
+  if (sumL > 0 && !weights_complete(h, w)) return bad("a weight pointer is NULL");
   h->plan = std::move(plan);
   h->cap_valid = false;
   h->kv_valid = false;
@@ -593,7 +625,7 @@ int flame_gr_score(flame_gr_t *h, const flame_gr_weights *w, const void *cand_em
   if (rc) return rc;
   const int64_t sumM = n_requests ? cand_offsets[n_requests] : 0;
   if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
-  if (sumM > 0 && !weights_complete(w)) return bad("a weight pointer is NULL");
+  if (sumM > 0 && !weights_complete(h, w)) return bad("a weight pointer is NULL");
   h->plan = std::move(plan);
   h->cap_valid = false;
   if (sumM == 0) return FLAME_GR_OK;

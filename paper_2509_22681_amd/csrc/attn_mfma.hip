@@ -79,8 +79,15 @@ __device__ __forceinline__ f16x8 pack8(const float *v) {
   return r;
 }
 
-template <int DH>
+// SOFTMAX = false: the weights are silu(logit), pointwise.  SOFTMAX = true: the weights of a query row are
+// softmax over its allowed keys of logit / tau (tau per layer and head); the kernel keeps a running maximum and
+// sum per row and rescales its output accumulators when the maximum moves (one pass over the keys).  The logit
+// in the accumulators is halved, so the exponent fed to the base-2 exponential is accumulator * tscale_h[head]
+// with tscale = 2 log2(e) / tau.  The 64 keys of a half tile of one query sit in two lanes (lane and lane ^ 32),
+// which exchange their maxima with one half-swap; their partial sums are only added at the end.
+template <int DH, bool SOFTMAX>
 __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__restrict__ planes, const float *__restrict__ bias_lh,
+                                                           const float *__restrict__ tscale_h,
                                                            half_t *__restrict__ O, const AttnItem *__restrict__ items,
                                                            int H, int d, int D, int64_t ws_rows) {
   constexpr int KS = DH / 16;          // k-steps of the Q K^T product
@@ -133,6 +140,10 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
   for (int b = 0; b < DB; ++b)
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
+  // softmax state of my query row (both lanes of a pair hold the same maximum; each holds the sum over its keys)
+  constexpr float kNeg = -1.0e30f;                  // finite stand-in for -inf: no inf - inf anywhere
+  const float ts = SOFTMAX ? tscale_h[head] : 0.f;
+  float m_run = kNeg, l_run = 0.f;
 
   const int n_tiles = (it.n_kv + KT - 1) / KT;
   const int q_first = it.is_cand ? it.L : it.q_pos;     // position of query row 0 of the workgroup tile
@@ -260,10 +271,44 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
             sacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk[s & 1][j], fq[s], sacc[j], 0, 0, 0);
           __builtin_amdgcn_sched_barrier(0);
         }
-        // ---- P^T = silu(S^T) (the bias is already in the accumulators)
+        // ---- P^T = silu(S^T) (the bias is already in the accumulators), or the softmax numerators
         f16x8 fp[4];
-        bool fast = false;
-        {
+        bool fast = SOFTMAX;
+        if constexpr (SOFTMAX) {
+          float mt = kNeg;
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              float y = sacc[j][e] * ts;
+              if (need_mask) {
+                const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
+                y = kv < n_vis ? y : kNeg;
+              }
+              sacc[j][e] = y;
+              mt = fmaxf(mt, y);
+            }
+          const float m_new = fmaxf(m_run, pair_max(mt));
+          const float sc = __builtin_amdgcn_exp2f(m_run - m_new);
+          m_run = m_new;
+          float ps = 0.f;
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            float w[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+              w[e] = __builtin_amdgcn_exp2f(sacc[j][e] - m_new);
+              ps += w[e];
+            }
+            fp[2 * j] = pack8(w);
+            fp[2 * j + 1] = pack8(w + 8);
+          }
+          l_run = l_run * sc + ps;
+#pragma unroll
+          for (int b = 0; b < DB; ++b)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[b][e] *= sc;
+        } else {
           f16x2 th[2][8];
 #pragma unroll
           for (int j = 0; j < 2; ++j)
@@ -361,10 +406,35 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
       sacc = __builtin_amdgcn_mfma_f32_32x32x16_f16(fk, fq[s], sacc, 0, 0, 0);
     }
     float p[16];
+    if constexpr (SOFTMAX) {
+      // the diagonal element of my query sits in one lane of the pair
+      float ys = kNeg;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
+        ys = kv_local == l32 ? sacc[e] * ts : ys;
+      }
+      const bool mine = ys > kNeg;
+      const float m_new = fmaxf(m_run, pair_max(ys));
+      const float sc = __builtin_amdgcn_exp2f(m_run - m_new);
+      const float pself = mine ? __builtin_amdgcn_exp2f(ys - m_new) : 0.f;
+      m_run = m_new;
+      l_run = l_run * sc + pself;
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[b][e] *= sc;
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
+        p[e] = (kv_local == l32 && row_valid) ? pself : 0.f;
+      }
+    } else {
 #pragma unroll
     for (int e = 0; e < 16; ++e) {
       const int kv_local = 16 * (e >> 3) + 8 * lhalf + (e & 7);
       p[e] = (kv_local == l32 && row_valid) ? silu_half_domain(sacc[e]) : 0.f;
+    }
     }
     const f16x8 fps[2] = {pack8(p), pack8(p + 8)};
 #pragma unroll
@@ -382,6 +452,14 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
   // through LDS (16-byte chunks XOR-swizzled by row; every wavefront is past the barrier that closes the key
   // loop, nobody reads the tile buffers any more) and stores 16 bytes per lane, a whole head row of
   // 2*DH bytes per group of lanes.
+  if constexpr (SOFTMAX) {
+    const float lt = pair_sum(l_run);
+    const float inv = lt > 0.f ? 1.0f / lt : 0.f;
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[b][e] *= inv;
+  }
   {
     constexpr int CPR = DH / 8;                       // 16-byte chunks per patch row
     constexpr int RPI = 64 / CPR;                     // patch rows per store instruction
@@ -410,13 +488,18 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
 
 }  // namespace
 
-void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const AttnItem *items, int n_items,
-                      const Shape &sh, hipStream_t s) {
+void launch_attn_bf16(const void *planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
+                      int n_items, const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   const int grid = n_items * sh.H;
-#define ATTN_CASE(DHV) attn_mfma_kernel<DHV><<<grid, 64 * NW, 0, s>>>((const half_t *)planes, bias_lh, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
-  if (sh.dh == 32) ATTN_CASE(32);
-  else ATTN_CASE(64);
+#define ATTN_CASE(DHV, SM) attn_mfma_kernel<DHV, SM><<<grid, 64 * NW, 0, s>>>((const half_t *)planes, bias_lh, tscale_h, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
+  if (sh.softmax) {
+    if (sh.dh == 32) ATTN_CASE(32, true);
+    else ATTN_CASE(64, true);
+  } else {
+    if (sh.dh == 32) ATTN_CASE(32, false);
+    else ATTN_CASE(64, false);
+  }
 #undef ATTN_CASE
 }
 

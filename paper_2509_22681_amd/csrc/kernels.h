@@ -12,6 +12,7 @@ struct Shape {
   int d, H, dh, n_layers, n_buckets, D;
   float eps, alpha;
   int64_t ws_rows;  // rows of every workspace matrix (plane stride = ws_rows * d)
+  int softmax;      // attention weights: 0 = pointwise SiLU, 1 = softmax with a temperature per layer and head
 };
 
 // ---- shared small kernels (misc.hip) --------------------------------------------------------
@@ -34,6 +35,11 @@ void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, 
 // scores[src_row + i] = <X[row], w_s> + b_s for the valid rows of every candidate block.
 void launch_scores(int dtype, const float *X, const void *w_s, float b_s, const RowBlock *blocks,
                    const int32_t *cand_blocks, int n_cblk, float *scores, int d, hipStream_t s);
+// out[i] = factor / temperature[i] (the per-layer, per-head logit scale of the softmax attention).
+void launch_logit_scale(const float *temperature, float *out, int n, float factor, hipStream_t s);
+// hidden[(src_row + i) * d ..] = X[row] for the valid rows of every candidate block (fp32).
+void launch_gather_hidden(const float *X, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk, float *hidden,
+                          int d, hipStream_t s);
 // mask / bucket of one request evaluated with the device predicate (debug export).
 void launch_debug_mask(int L, int M, const int32_t *bucket_tab, int D, uint8_t *mask, int32_t *bucket,
                        hipStream_t s);
@@ -42,7 +48,9 @@ void launch_debug_mask(int L, int M, const int32_t *bucket_tab, int D, uint8_t *
 // planes[p][row][n] = silu(X W1^T + b1), p = U,V,Q,K; rows = 64-row blocks [blk_first, blk_first+n_blk)
 void launch_uvqk_f32(const float *X, const float *W1, const float *b1, float *planes, int blk_first,
                      int n_blk, const Shape &sh, hipStream_t s);
-void launch_attn_f32(const float *planes, const float *bias_lh, float *O, const AttnItem *items,
+// tscale_h (softmax only): per head, the factor from the logit the kernel forms to the exponent it feeds to
+// its exponential: 1 / tau here (natural exponential of the full logit).
+void launch_attn_f32(const float *planes, const float *bias_lh, const float *tscale_h, float *O, const AttnItem *items,
                      int n_items, int q_tile, const Shape &sh, hipStream_t s);
 // X[row] += G[row] W2^T + b2 for the rows of the listed blocks (blk_list == nullptr: contiguous)
 void launch_outproj_f32(const float *G, const float *W2, const float *b2, float *X,
@@ -55,8 +63,9 @@ void launch_outproj_f32(const float *G, const float *W2, const float *b2, float 
 // plane_mask bit p set = compute plane p (U=1, V=2, Q=4, K=8).
 void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
                       int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s);
-void launch_attn_bf16(const void *planes, const float *bias_lh, void *O, const AttnItem *items, int n_items,
-                      const Shape &sh, hipStream_t s);
+// tscale_h (softmax only): 2 log2(e) / tau per head (the kernel holds halved logits and uses the base-2 exponential).
+void launch_attn_bf16(const void *planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
+                      int n_items, const Shape &sh, hipStream_t s);
 // X[row] += G W2h^T + b2, and Xh[row] = fp16(X[row])
 void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);

@@ -73,7 +73,9 @@ void launch_outproj_f32(const float *G, const float *W2, const float *b2, float 
 // silu(alpha <Q_r,K_c> + bias[p_r - p_c]) for its key, the 64 weights go through LDS, then lane j
 // accumulates sum_c weight_c V_c[j].  Fixed summation order: results are run-to-run identical.
 // ---------------------------------------------------------------------------------------------
+template <bool SOFTMAX>
 __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__ U_V_Q_K, const float *__restrict__ bias_lh,
+                                                       const float *__restrict__ tscale_h,
                                                        float *__restrict__ O, const AttnItem *__restrict__ items,
                                                        int q_tile, int d, int dh, int D, float alpha, int64_t plane_stride) {
   __shared__ float sQ[4][256];
@@ -91,18 +93,33 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
     const int n_vis = visible_history(it.is_cand, q_index, it.L);
     for (int k = lane; k < dh; k += 64) sQ[wave][k] = Qp[qrow * d + k];
     float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    // softmax: running maximum and sum of the row (in units of the scaled logit), a finite stand-in for -inf
+    constexpr float kNeg = -1.0e30f;
+    const float ts = SOFTMAX ? tscale_h[h] : 0.f;
+    float m_run = kNeg, l_run = 0.f;
     // history keys, then (candidates only) the row itself as one more key at distance 0
     const int n_keys = n_vis + (it.is_cand ? 1 : 0);
     for (int c0 = 0; c0 < n_keys; c0 += 64) {
       const int c = c0 + lane;
-      float p = 0.f;
+      float p = 0.f, z = kNeg;
       if (c < n_keys) {
         const bool self = c >= n_vis;
         const int64_t krow = self ? qrow : (int64_t)it.kv_row + c;
         const int delta = self ? 0 : q_index - c;
         float dot = 0.f;
         for (int k = 0; k < dh; ++k) dot = fmaf(sQ[wave][k], Kp[krow * d + k], dot);
-        p = silu_f32(alpha * dot + bias[delta < D ? delta : D - 1]);
+        const float logit = alpha * dot + bias[delta < D ? delta : D - 1];
+        if (SOFTMAX) z = logit * ts;
+        else p = silu_f32(logit);
+      }
+      if (SOFTMAX) {
+        const float m_new = fmaxf(m_run, wave_max(z));
+        const float sc = expf(m_run - m_new);
+        p = c < n_keys ? expf(z - m_new) : 0.f;
+        l_run = l_run * sc + wave_sum(p);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[j] *= sc;
+        m_run = m_new;
       }
       sP[wave][lane] = p;
       const int cn = min(64, n_keys - c0);
@@ -120,16 +137,19 @@ __global__ __launch_bounds__(256) void attn_f32_kernel(const float *__restrict__
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
       const int k = lane + j * 64;
-      if (k < dh) O[qrow * d + h * dh + k] = acc[j];
+      if (k < dh) O[qrow * d + h * dh + k] = SOFTMAX ? acc[j] / l_run : acc[j];
     }
   }
 }
 
-void launch_attn_f32(const float *planes, const float *bias_lh, float *O, const AttnItem *items, int n_items,
-                     int q_tile, const Shape &sh, hipStream_t s) {
+void launch_attn_f32(const float *planes, const float *bias_lh, const float *tscale_h, float *O, const AttnItem *items,
+                     int n_items, int q_tile, const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   dim3 grid(n_items, sh.H);
-  attn_f32_kernel<<<grid, 256, 0, s>>>(planes, bias_lh, O, items, q_tile, sh.d, sh.dh, sh.D, sh.alpha, sh.ws_rows * sh.d);
+  if (sh.softmax)
+    attn_f32_kernel<true><<<grid, 256, 0, s>>>(planes, bias_lh, tscale_h, O, items, q_tile, sh.d, sh.dh, sh.D, sh.alpha, sh.ws_rows * sh.d);
+  else
+    attn_f32_kernel<false><<<grid, 256, 0, s>>>(planes, bias_lh, tscale_h, O, items, q_tile, sh.d, sh.dh, sh.D, sh.alpha, sh.ws_rows * sh.d);
 }
 
 }  // namespace flame

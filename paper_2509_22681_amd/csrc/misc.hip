@@ -89,6 +89,34 @@ void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias
   expand_bias_kernel<<<grid, 256, 0, s>>>(rab, bucket_tab, bias, n_buckets, D, scale);
 }
 
+__global__ __launch_bounds__(256) void logit_scale_kernel(const float *__restrict__ temperature, float *__restrict__ out, int n,
+                                                          float factor) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n) out[i] = factor / temperature[i];
+}
+
+void launch_logit_scale(const float *temperature, float *out, int n, float factor, hipStream_t s) {
+  if (n > 0) logit_scale_kernel<<<(n + 255) / 256, 256, 0, s>>>(temperature, out, n, factor);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The candidates' final residual rows, in candidate order (the input of a fusion / head stage).
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void gather_hidden_kernel(const float *__restrict__ X, const RowBlock *__restrict__ blocks,
+                                                            const int32_t *__restrict__ cand_blocks, float *__restrict__ hidden, int d) {
+  const int b = cand_blocks[blockIdx.x];
+  const RowBlock rb = blocks[b];
+  const int n = rb.n_valid * d;
+  const float *src = X + (int64_t)b * kRowAlign * d;
+  float *dst = hidden + (int64_t)rb.src_row * d;
+  for (int i = threadIdx.x; i < n; i += 256) dst[i] = src[i];
+}
+
+void launch_gather_hidden(const float *X, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk, float *hidden,
+                          int d, hipStream_t s) {
+  if (n_cblk > 0) gather_hidden_kernel<<<n_cblk, 256, 0, s>>>(X, blocks, cand_blocks, hidden, d);
+}
+
 // ---------------------------------------------------------------------------------------------
 // bf16 -> fp16 copy of the projection matrices.  The MFMA path works on fp16 operands: with eight
 // to sixteen layers the 2^-9 rounding of bf16 intermediates alone puts about 1e-2 rms (5e-2 worst

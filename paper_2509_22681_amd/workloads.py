@@ -61,6 +61,7 @@ class GRConfig:
     dtype: str = "bf16"          # "f32" | "bf16": storage type of embeddings and weights
     ln_eps: float = 1e-6
     attn_scale: float = 1.0
+    attn_kind: str = "silu"      # "silu" | "softmax" (softmax: weights carry "temperature" [Lyr,H], fp32)
 
     def to_dict(self) -> dict:
         return asdict(self)
@@ -141,7 +142,8 @@ def _pow2_above(n: int) -> int:
 def _draw(rng, cfg: GRConfig, L, M, *, emb_std=0.1, rab_std=0.02, bias_amp=0.0,
           affine_random=False, name="custom") -> Workload:
     """Draw order: history_emb, cand_emb, then per layer W1 (U,V,Q,K), W2, rab; then w_s;
-    then (only when requested) biases and LayerNorm affine parameters."""
+    then (only when requested) biases and LayerNorm affine parameters; then (softmax attention only)
+    the temperatures, Uniform[0.5, 2]."""
     d, H, Ly, nb = cfg.d_model, cfg.n_heads, cfg.n_layers, cfg.n_buckets
     sL, sM = int(np.sum(L)), int(np.sum(M))
     hist = (emb_std * rng.standard_normal((sL, d))).astype(np.float32)
@@ -178,19 +180,21 @@ def _draw(rng, cfg: GRConfig, L, M, *, emb_std=0.1, rab_std=0.02, bias_amp=0.0,
         w2=_round_storage(w2, dt), b2=_round_storage(b2, dt),
         w_s=_round_storage(w_s, dt), b_s=b_s,
     )
+    if cfg.attn_kind == "softmax":            # drawn last, so that the other values do not depend on the attention kind
+        weights["temperature"] = rng.uniform(0.5, 2.0, (Ly, H)).astype(np.float32)
     return Workload(name, cfg, _offsets(L), _offsets(M), _round_storage(hist, dt),
                     _round_storage(cand, dt), weights)
 
 
 def make_custom(L, M, *, d, H, n_layers, n_buckets, max_rel_dist=None, dtype="f32", seed=0,
                 emb_std=0.1, rab_std=0.02, bias_amp=0.0, affine_random=False,
-                ln_eps=1e-6, attn_scale=1.0, name="custom") -> Workload:
+                ln_eps=1e-6, attn_scale=1.0, attn_kind="silu", name="custom") -> Workload:
     """A workload with explicit per-request lengths; used by stress and edge-case tests."""
     L = np.asarray(L, dtype=np.int64)
     M = np.asarray(M, dtype=np.int64)
     if max_rel_dist is None:
         max_rel_dist = _pow2_above(int(L.max()) if len(L) else 0)
-    cfg = GRConfig(n_layers, d, H, n_buckets, max_rel_dist, dtype, ln_eps, attn_scale)
+    cfg = GRConfig(n_layers, d, H, n_buckets, max_rel_dist, dtype, ln_eps, attn_scale, attn_kind)
     rng = np.random.default_rng(seed)
     return _draw(rng, cfg, L, M, emb_std=emb_std, rab_std=rab_std, bias_amp=bias_amp,
                  affine_random=affine_random, name=name)
