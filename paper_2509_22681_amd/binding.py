@@ -112,6 +112,25 @@ _lib.flame_dso_route.restype = C.c_int
 _lib.flame_dso_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int64)]
 _lib.flame_dso_stats.restype = C.c_int
 
+class flame_climber_head_config(C.Structure):
+    _fields_ = [("n_blocks", C.c_int32), ("d_model", C.c_int32), ("n_tasks", C.c_int32), ("expert_width", C.c_int32)]
+
+
+class flame_climber_head_weights(C.Structure):
+    _fields_ = [("wg", C.c_void_p), ("cg", C.c_void_p), ("a_w", C.c_void_p), ("a_b", C.c_void_p), ("v", C.c_void_p),
+                ("c", C.c_void_p)]
+
+
+_lib.flame_climber_head.argtypes = [C.POINTER(flame_climber_head_config), C.POINTER(flame_climber_head_weights),
+                                    C.POINTER(C.c_void_p), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+_lib.flame_climber_head.restype = C.c_int
+_lib.flame_climber_block_range.argtypes = [C.c_int32, C.c_int32, C.c_int32, _i32p, _i32p]
+_lib.flame_climber_block_range.restype = C.c_int
+_lib.flame_climber_last_error.argtypes = []
+_lib.flame_climber_last_error.restype = C.c_char_p
+
+CLIMBER_EXPORTS = ("flame_climber_head", "flame_climber_block_range", "flame_climber_last_error")
+
 DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_wait", "flame_dso_drain", "flame_dso_destroy",
                "flame_dso_last_error", "flame_dso_route", "flame_dso_stats")
 
@@ -401,6 +420,31 @@ def flame_dso_route(profiles, hist_len: int, d_model: int, n_cand: int, explicit
     if rc != 0:
         raise FlameGRError(rc, "flame_dso_route")
     return [(int(a), int(b)) for a, b in buf[:n.value]]
+
+
+# ---------------------------------------------------------------------------------------------
+# fusion of the sub-sequence blocks and task head (include/flame_climber.h)
+# ---------------------------------------------------------------------------------------------
+def flame_climber_block_range(L: int, n_blocks: int, b: int):
+    lo, hi = C.c_int32(0), C.c_int32(0)
+    rc = _lib.flame_climber_block_range(L, n_blocks, b, C.byref(lo), C.byref(hi))
+    if rc != 0:
+        raise FlameGRError(rc, "flame_climber_block_range")
+    return lo.value, hi.value
+
+
+def flame_climber_head(head: Dict[str, object], hidden, fused, probs, stream=None) -> None:
+    """head: dict of device fp32 tensors wg [Nb,d,Nb*d], cg [Nb,d], a_w [T,E,d], a_b [T,E], v [T,E], c [T];
+    hidden: list of Nb device fp32 tensors [rows, d]; fused [rows, d] workspace; probs [rows, T] output."""
+    nb = len(hidden)
+    rows, d = (int(hidden[0].shape[0]), int(hidden[0].shape[1])) if nb else (0, 0)
+    T, E = int(head["a_w"].shape[0]), int(head["a_w"].shape[1])
+    cfg = flame_climber_head_config(nb, d, T, E)
+    ws = flame_climber_head_weights(*[_ptr(head[k]) for k in ("wg", "cg", "a_w", "a_b", "v", "c")])
+    ptrs = (C.c_void_p * max(nb, 1))(*[_ptr(h) for h in hidden])
+    rc = _lib.flame_climber_head(C.byref(cfg), C.byref(ws), ptrs, rows, _ptr(fused), _ptr(probs), C.c_void_p(_stream_ptr(stream)))
+    if rc != 0:
+        raise FlameGRError(rc, _lib.flame_climber_last_error().decode())
 
 
 # ---------------------------------------------------------------------------------------------

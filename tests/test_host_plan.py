@@ -22,12 +22,12 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     inc = os.path.join(ROOT, "include")
     header = "".join(open(os.path.join(inc, f)).read() for f in sorted(os.listdir(inc)) if f.endswith(".h"))
-    declared = set(re.findall(r"\b(flame_(?:gr|dso)_[a-z_]+)\s*\(", header))
+    declared = set(re.findall(r"\b(flame_(?:gr|dso|climber)_[a-z_]+)\s*\(", header))
     assert {"flame_gr_create", "flame_gr_forward", "flame_gr_destroy", "flame_dso_create", "flame_dso_submit"} <= declared
     lib = ctypes.CDLL(B.LIB_PATH)
     for name in declared:
         assert hasattr(lib, name), name
-    assert declared == set(B.EXPORTS) | set(B.DSO_EXPORTS)
+    assert declared == set(B.EXPORTS) | set(B.DSO_EXPORTS) | set(B.CLIMBER_EXPORTS)
 
 
 @pytest.mark.parametrize("nb,D", [(128, 128), (128, 1024), (128, 4096), (128, 8192), (512, 16384),
@@ -207,3 +207,13 @@ def test_reserved_plan_rejections():
     assert e.value.code == -1
     seg = B.flame_gr_host_plan_reserved(_cfg(kv_cache=1), ho, co, [20, 10])
     assert len(seg) == 2
+
+
+def test_block_ranges_match_the_oracle():
+    for L in (0, 1, 7, 512, 1023, 1024):
+        for nb in (1, 2, 3, 8):
+            got = [B.flame_climber_block_range(L, nb, b) for b in range(nb)]
+            assert got == [(s.start, s.stop) for s in oracle.block_slices(L, nb)]
+    for args in ((10, 0, 0), (10, 2, 2), (-1, 2, 0)):
+        with pytest.raises(B.FlameGRError):
+            B.flame_climber_block_range(*args)
