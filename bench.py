@@ -186,6 +186,91 @@ def mixed_traffic_leg(B, wl, dw, n_requests=320, n_executors=4, hist_len=1024,
     return out
 
 
+def climber_leg(B, steps=10, n_users=64, d=192, H=3, layers=12, n_blocks=2, E=256, T=2):
+    """The paper's own model in the reading of include/flame_climber.h, at the two scenarios of its Table 2
+    (base: sequence 512 + 128 candidates; long: 1024 + 512; 2 blocks x 12 layers): softmax attention with
+    temperature, each block stack on its own handle and stream, then gating fusion and task head.  d = 192 puts
+    the block stacks' flops per request at 4.6e9 (base) and 1.63e10 (long) against the paper's 3.72e9 and 1.64e10.
+    Reports batched throughput (n_users requests per pass), single-request latency, and the deviation of one
+    request from the fp64 oracle."""
+    import torch
+    import oracle
+    from paper_2509_22681_amd import workloads as W
+    out = {"d_model": d, "n_heads": H, "layers_per_block": layers, "blocks": n_blocks, "expert_width": E, "tasks": T,
+           "users_per_pass": n_users}
+    rng = np.random.default_rng(0)
+    head = dict(wg=(rng.standard_normal((n_blocks, d, n_blocks * d)) / np.sqrt(n_blocks * d)).astype(np.float32),
+                cg=np.zeros((n_blocks, d), np.float32),
+                a_w=(rng.standard_normal((T, E, d)) / np.sqrt(d)).astype(np.float32), a_b=np.zeros((T, E), np.float32),
+                v=(rng.standard_normal((T, E)) / np.sqrt(E)).astype(np.float32), c=np.zeros(T, np.float32))
+    head_dev = {k: torch.from_numpy(v).to("cuda:0") for k, v in head.items()}
+    for name, L, M in (("base", 512, 128), ("long", 1024, 512)):
+        wls = [W.make_custom([L] * n_users, [M] * n_users, d=d, H=H, n_layers=layers, n_buckets=128, max_rel_dist=1024,
+                             dtype="bf16", seed=100 + b, attn_kind="softmax", name=f"{name}{b}") for b in range(n_blocks)]
+        base = wls[0]
+        res = {}
+        for users in (n_users, 1):
+            sub = base.subset(range(users))
+            n = int(sub.cand_offsets[-1])
+            handles, args, streams, hidden = [], [], [], []
+            try:
+                for b in range(n_blocks):
+                    lo, hi = B.flame_climber_block_range(L, n_blocks, b)
+                    hist = np.concatenate([sub.history_emb[i * L + lo:i * L + hi] for i in range(users)], 0)
+                    ho = (np.arange(users + 1) * (hi - lo)).astype(np.int32)
+                    wl_b = W.Workload(f"{name}{b}", base.cfg, ho, sub.cand_offsets, hist, sub.cand_emb, wls[b].weights)
+                    handles.append(B.flame_gr_create(B.config_for(wl_b)))
+                    dw, dh, dc = B.to_device(wl_b)
+                    args.append((B.pack_weights(dw), dw, dh, ho, dc))
+                    streams.append(torch.cuda.Stream())
+                    hidden.append(torch.zeros((n, d), device="cuda:0", dtype=torch.float32))
+                fused = torch.empty((n, d), device="cuda:0", dtype=torch.float32)
+                probs = torch.zeros((n, T), device="cuda:0", dtype=torch.float32)
+                main = torch.cuda.current_stream()
+
+                def one_pass():
+                    for b in range(n_blocks):
+                        streams[b].wait_stream(main)
+                        ws, _, dh, ho, dc = args[b]
+                        B.flame_gr_forward_hidden(handles[b], ws, dh, ho, dc, sub.cand_offsets, hidden[b], stream=streams[b])
+                    for b in range(n_blocks):
+                        main.wait_stream(streams[b])
+                    B.flame_climber_head(head_dev, hidden, fused, probs)
+
+                for _ in range(3):
+                    one_pass()
+                torch.cuda.synchronize()
+                if users > 1:
+                    t0 = time.perf_counter()
+                    for _ in range(steps):
+                        one_pass()
+                    torch.cuda.synchronize()
+                    ms = (time.perf_counter() - t0) / steps * 1e3
+                    res["ms_per_pass"] = ms
+                    res["user_item_pairs_per_s"] = n / (ms * 1e-3)
+                    got = probs[:M].cpu().numpy()
+                    want = oracle.climber_request(base.cfg.to_dict(), [w.weights for w in wls], head,
+                                                  base.history_emb[:L], base.cand_emb[:M])
+                    res["max_abs_prob_error_vs_oracle_request0"] = float(np.abs(got - want).max())
+                else:
+                    lat = []
+                    for _ in range(30):
+                        t0 = time.perf_counter()
+                        one_pass()
+                        torch.cuda.synchronize()
+                        lat.append((time.perf_counter() - t0) * 1e3)
+                    res["single_request_latency_ms_p50"] = float(np.percentile(lat, 50))
+                    res["single_request_latency_ms_p99"] = float(np.percentile(lat, 99))
+            finally:
+                torch.cuda.synchronize()
+                for h in handles:
+                    B.flame_gr_destroy(h)
+        Nb, Pb = L // n_blocks + M, (L // n_blocks) * (L // n_blocks + 1) // 2 + M * (L // n_blocks + 1)
+        res["block_stack_flops_per_request"] = float(n_blocks * layers * (10 * Nb * d * d + 4 * Pb * d))
+        out[name] = res
+    return out
+
+
 def two_stage_leg(B, wl, ws, hist, cand, one_pass_scores, steps, warmup):
     """History prefill once (per-layer K/V kept on the device), then `steps` candidate-only score calls against
     it: the two-stage paradigm of the paper's Section 5.  Reported beside the headline, never as `value`."""
@@ -230,6 +315,7 @@ def main():
     ap.add_argument("--no-latency", action="store_true")
     ap.add_argument("--no-two-stage", action="store_true")
     ap.add_argument("--no-mixed-traffic", action="store_true")
+    ap.add_argument("--no-climber", action="store_true")
     ap.add_argument("--executors", type=int, default=4, help="executors of the mixed-traffic orchestrator")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy kernel of this many MiB "
@@ -330,6 +416,8 @@ def main():
         out["two_stage"] = two_stage
     if not args.no_mixed_traffic:
         out["mixed_traffic"] = mixed_traffic_leg(B, wl, dw, n_executors=args.executors)
+    if not args.no_climber:
+        out["climber"] = climber_leg(B)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl)
     print(json.dumps(out))
