@@ -141,9 +141,12 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
 #pragma unroll
     for (int e = 0; e < 16; ++e) oacc[b][e] = 0.f;
   // softmax state of my query row (both lanes of a pair hold the same maximum; each holds the sum over its keys)
-  constexpr float kNeg = -1.0e30f;                  // finite stand-in for -inf: no inf - inf anywhere
+  // Finite stand-ins for -inf, so that no inf - inf can arise: a masked key's raw logit is kNeg; the running
+  // maximum starts below kNeg * tscale for any sensible temperature, so a row whose keys so far were all masked
+  // holds weights exp2(0) that the first real maximum scales to zero (every row sees key 0 of tile 0 or itself).
+  constexpr float kNeg = -1.0e30f;
   const float ts = SOFTMAX ? tscale_h[head] : 0.f;
-  float m_run = kNeg, l_run = 0.f;
+  float m_run = -3.0e38f, l_run = 0.f;
 
   const int n_tiles = (it.n_kv + KT - 1) / KT;
   const int q_first = it.is_cand ? it.L : it.q_pos;     // position of query row 0 of the workgroup tile
@@ -275,39 +278,44 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
         f16x8 fp[4];
         bool fast = SOFTMAX;
         if constexpr (SOFTMAX) {
+          // maximum of the raw (halved) logits first: the temperature scale is positive, so it commutes with the max
           float mt = kNeg;
 #pragma unroll
           for (int j = 0; j < 2; ++j)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-              float y = sacc[j][e] * ts;
               if (need_mask) {
                 const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-                y = kv < n_vis ? y : kNeg;
+                sacc[j][e] = kv < n_vis ? sacc[j][e] : kNeg;
               }
-              sacc[j][e] = y;
-              mt = fmaxf(mt, y);
+              mt = fmaxf(mt, sacc[j][e]);
             }
-          const float m_new = fmaxf(m_run, pair_max(mt));
-          const float sc = __builtin_amdgcn_exp2f(m_run - m_new);
-          m_run = m_new;
+          const float m_new = fmaxf(m_run, pair_max(mt) * ts);
+          // the accumulators are rescaled only when some row of the wavefront has a new maximum (rare after the
+          // first tiles); the branch is uniform over the wavefront
+          if (__builtin_amdgcn_ballot_w64(m_new != m_run) != 0) {
+            const float sc = __builtin_amdgcn_exp2f(m_run - m_new);
+            l_run *= sc;
+#pragma unroll
+            for (int b = 0; b < DB; ++b)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) oacc[b][e] *= sc;
+            m_run = m_new;
+          }
+          const float nm = -m_new;
           float ps = 0.f;
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
             float w[16];
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-              w[e] = __builtin_amdgcn_exp2f(sacc[j][e] - m_new);
+              w[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j][e], ts, nm));
               ps += w[e];
             }
             fp[2 * j] = pack8(w);
             fp[2 * j + 1] = pack8(w + 8);
           }
-          l_run = l_run * sc + ps;
-#pragma unroll
-          for (int b = 0; b < DB; ++b)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[b][e] *= sc;
+          l_run += ps;
         } else {
           f16x2 th[2][8];
 #pragma unroll
