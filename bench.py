@@ -136,8 +136,8 @@ def mixed_traffic_leg(B, wl, dw, n_requests=320, n_executors=4, hist_len=1024,
     """The paper's mixed-traffic experiment (Section 4.2.3, DSO table) on this model: single-user requests with a
     history of 1024 items and a candidate count drawn uniformly from {128, 256, 512, 1024}, host embeddings in,
     host scores out, served in a closed loop by the orchestrator: once with explicit-shape executors (one captured
-    graph per profile on every executor) and once with the implicit-shape baseline (same pool, dynamic-shape eager
-    forward).
+    graph per profile on every executor), once with the implicit-shape baseline (same pool, dynamic-shape eager
+    forward), and with jagged micro-batches (2 executors that gather 4 or 8 requests per jagged forward).
     Latency is host wall-clock from submit to scores delivered."""
     c = wl.cfg
     cfg = B.make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype, ln_eps=c.ln_eps,
@@ -151,11 +151,16 @@ def mixed_traffic_leg(B, wl, dw, n_requests=320, n_executors=4, hist_len=1024,
                  for _ in range(pool)]
     cand_pool = B.host_embedding(W._round_storage(rng.standard_normal((max(profiles) * 2, c.d_model)).astype(np.float32) * std, c.dtype), c.dtype)
     out = {"hist_len": hist_len, "profiles": list(profiles), "requests": n_requests,
-           "executors": n_executors, "user_item_pairs": int(Ms.sum())}
-    for mode, explicit in (("explicit_shape", True), ("implicit_shape", False)):
-        dso = B.flame_dso_create(cfg, dw, hist_len, list(profiles), n_executors, explicit_shapes=explicit)
+           "user_item_pairs": int(Ms.sum())}
+    # executors = streams; how many of them run side by side depends on how the runtime maps the process's
+    # streams onto its four hardware queues, so the per-request modes are run at two pool sizes
+    modes = []
+    for n_ex in sorted({3, n_executors}):
+        modes += [(f"explicit_shape_{n_ex}_executors", 1, n_ex, 1, n_ex), (f"implicit_shape_{n_ex}_executors", 0, n_ex, 1, n_ex)]
+    modes += [("jagged_micro_batch_4", 2, 2, 4, 8), ("jagged_micro_batch_8", 2, 2, 8, 16)]
+    for mode, explicit, n_ex, max_batch, depth in modes:
+        dso = B.flame_dso_create(cfg, dw, hist_len, list(profiles), n_ex, explicit_shapes=explicit, max_batch=max_batch)
         try:
-            depth = n_executors
             res = None
             for rep in range(2):               # first pass warms up
                 lat, inflight = [], []
@@ -180,6 +185,7 @@ def mixed_traffic_leg(B, wl, dw, n_requests=320, n_executors=4, hist_len=1024,
                        "p50_latency_ms": float(np.percentile(lat, 50)), "p99_latency_ms": float(np.percentile(lat, 99)),
                        "requests_per_s": float(n_requests / wall)}
             res.update(B.flame_dso_stats(dso))
+            res.update({"executors": n_ex, "requests_in_flight": depth, "max_batch": max_batch})
             out[mode] = res
         finally:
             B.flame_dso_destroy(dso)

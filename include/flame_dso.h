@@ -11,6 +11,7 @@
  * executors (the "pinned data transfer" of Section 3.1), so a chunk's upload overlaps the compute
  * of the chunks before it on other streams.
  *
+ * (Mode 1 of three; modes 0 and 2 are described at flame_dso_config.)
  * Here an executor is a flame_gr handle with one captured HIP graph per profile (flame_gr_capture,
  * one slot each, all bound to the executor's one set of buffers), a pinned input buffer, a device
  * input buffer, a device and a pinned score buffer, a stream and an event.  Because every executor
@@ -49,7 +50,15 @@ typedef struct {
                                        buffers, but every executor takes any candidate count up to the
                                        largest profile and runs the dynamic-shape flame_gr_forward
                                        (planned and launched kernel by kernel per request); a request
-                                       is split only above the largest profile */
+                                       is split only above the largest profile.
+                                    2: jagged micro-batches, the re-design that jagged kernels allow: requests
+                                       of any candidate counts gather in an executor's pinned buffer and are
+                                       scored by ONE jagged flame_gr_forward when max_batch requests have
+                                       gathered, when the buffer is full, when a gathered ticket is waited
+                                       for, or on flame_dso_flush / flame_dso_drain.  No padding, no
+                                       profiles (they only bound the buffer: max_batch x largest profile
+                                       candidate rows); kernels see batches large enough to fill the chip */
+  int32_t max_batch;             /* mode 2 only: 1..256 requests per micro-batch */
 } flame_dso_config;
 
 /* Build all executors on the current device: model->max_requests / max_total_tokens / n_streams /
@@ -77,6 +86,9 @@ int flame_dso_submit(flame_dso_t *dso, const void *history_emb, const void *cand
 /* Block until every chunk of `ticket` has completed and its scores are in the caller's array.
  * Waiting twice for a ticket, or for one already retired by executor reuse, returns at once. */
 int flame_dso_wait(flame_dso_t *dso, int64_t ticket);
+
+/* Mode 2: send the gathering micro-batch to the GPU now (no-op otherwise or when nothing gathers). */
+int flame_dso_flush(flame_dso_t *dso);
 
 /* Wait for everything submitted so far. */
 int flame_dso_drain(flame_dso_t *dso);

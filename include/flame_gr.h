@@ -138,9 +138,12 @@ int flame_gr_forward_hidden(flame_gr_t *h, const flame_gr_weights *weights,
  * launch per kernel.  A handle holds up to FLAME_GR_MAX_GRAPHS such graphs (`slot`), e.g. one per
  * candidate-count profile, all working in the handle's one set of workspaces.
  *
- * flame_gr_capture takes the arguments of flame_gr_forward (no stream: it synchronises the handle's
- * earlier work, uploads the plan into tables owned by the slot, derives the weight copies and records
- * the kernels on an internal stream; nothing is scored yet).  The graph is bound to the shape (the
+ * flame_gr_capture takes the arguments of flame_gr_forward: it synchronises the handle's earlier
+ * work, uploads the plan into tables owned by the slot, derives the weight copies and records the
+ * kernels; nothing is scored yet.  record_stream is the hipStream_t to record on (it is synchronised
+ * and idle when the call returns; the legacy default stream cannot record) or NULL for a stream
+ * that the handle creates for the purpose: a caller that counts its streams against the hardware
+ * queues passes the stream it will replay on.  The graph is bound to the shape (the
  * offsets) and to the device buffers history_emb, cand_emb, scores and the weight pointers: the
  * caller refreshes the contents of history_emb / cand_emb in place before each replay.  The derived
  * weight copies belong to the handle and are rewritten by every capture and every eager call from the
@@ -156,7 +159,7 @@ int flame_gr_forward_hidden(flame_gr_t *h, const flame_gr_weights *weights,
 int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *weights,
                      const void *history_emb, const int32_t *history_offsets,
                      const void *cand_emb, const int32_t *cand_offsets,
-                     int32_t n_requests, float *scores);
+                     int32_t n_requests, float *scores, void *record_stream);
 int flame_gr_replay(flame_gr_t *h, int32_t slot, void *stream);
 
 /* Two-stage scoring with a history key/value cache: the paradigm that Section 5 leaves for future

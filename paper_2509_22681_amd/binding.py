@@ -58,7 +58,7 @@ _lib.flame_gr_forward.restype = C.c_int
 _lib.flame_gr_forward_hidden.argtypes = _lib.flame_gr_forward.argtypes
 _lib.flame_gr_forward_hidden.restype = C.c_int
 _lib.flame_gr_capture.argtypes = [C.c_void_p, C.c_int32, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
-                                  C.c_int32, C.c_void_p]
+                                  C.c_int32, C.c_void_p, C.c_void_p]
 _lib.flame_gr_capture.restype = C.c_int
 _lib.flame_gr_replay.argtypes = [C.c_void_p, C.c_int32, C.c_void_p]
 _lib.flame_gr_replay.restype = C.c_int
@@ -91,7 +91,7 @@ _lib.flame_gr_debug_profile_read.restype = C.c_int
 
 class flame_dso_config(C.Structure):
     _fields_ = [("hist_len", C.c_int32), ("n_profiles", C.c_int32), ("profiles", _i32p),
-                ("n_executors", C.c_int32), ("explicit_shapes", C.c_int32)]
+                ("n_executors", C.c_int32), ("explicit_shapes", C.c_int32), ("max_batch", C.c_int32)]
 
 
 _lib.flame_dso_create.argtypes = [C.POINTER(flame_gr_config), C.POINTER(flame_gr_weights), C.POINTER(flame_dso_config),
@@ -103,6 +103,8 @@ _lib.flame_dso_wait.argtypes = [C.c_void_p, C.c_int64]
 _lib.flame_dso_wait.restype = C.c_int
 _lib.flame_dso_drain.argtypes = [C.c_void_p]
 _lib.flame_dso_drain.restype = C.c_int
+_lib.flame_dso_flush.argtypes = [C.c_void_p]
+_lib.flame_dso_flush.restype = C.c_int
 _lib.flame_dso_destroy.argtypes = [C.c_void_p]
 _lib.flame_dso_destroy.restype = C.c_int
 _lib.flame_dso_last_error.argtypes = [C.c_void_p]
@@ -131,7 +133,7 @@ _lib.flame_climber_last_error.restype = C.c_char_p
 
 CLIMBER_EXPORTS = ("flame_climber_head", "flame_climber_block_range", "flame_climber_last_error")
 
-DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_wait", "flame_dso_drain", "flame_dso_destroy",
+DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_wait", "flame_dso_drain", "flame_dso_flush", "flame_dso_destroy",
                "flame_dso_last_error", "flame_dso_route", "flame_dso_stats")
 
 EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_forward_hidden", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
@@ -218,7 +220,8 @@ def _stream_ptr(stream) -> int:
     return getattr(stream, "cuda_stream", stream)
 
 
-def flame_gr_capture(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores, slot: int = 0) -> None:
+def flame_gr_capture(h, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores, slot: int = 0,
+                     record_stream=None) -> None:
     """Record the forward of this fixed batch (shape, buffers) into graph `slot` of the handle."""
     ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
     ho, co = _i32(history_offsets), _i32(cand_offsets)
@@ -226,7 +229,8 @@ def flame_gr_capture(h, weights, history_emb, history_offsets, cand_emb, cand_of
     if len(co) - 1 != n:
         raise ValueError("offset arrays differ in length")
     rc = _lib.flame_gr_capture(h, slot, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
-                               co.ctypes.data_as(_i32p), n, _ptr(scores))
+                               co.ctypes.data_as(_i32p), n, _ptr(scores),
+                               C.c_void_p(getattr(record_stream, "cuda_stream", record_stream) or 0))
     _check(rc, h)
 
 
@@ -352,10 +356,11 @@ def _dso_check(rc: int, dso=None):
 
 
 def flame_dso_create(cfg: flame_gr_config, weights, hist_len: int, profiles, n_executors: int,
-                     explicit_shapes: bool = True) -> C.c_void_p:
+                     explicit_shapes=True, max_batch: int = 1) -> C.c_void_p:
+    """explicit_shapes: True/1 graph executors, False/0 eager dynamic shapes, 2 jagged micro-batches of max_batch."""
     ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
     prof = _i32(profiles)
-    dc = flame_dso_config(hist_len, len(prof), prof.ctypes.data_as(_i32p), n_executors, int(explicit_shapes))
+    dc = flame_dso_config(hist_len, len(prof), prof.ctypes.data_as(_i32p), n_executors, int(explicit_shapes), max_batch)
     out = C.c_void_p()
     _dso_check(_lib.flame_dso_create(C.byref(cfg), C.byref(ws), C.byref(dc), C.byref(out)))
     return out
@@ -386,6 +391,10 @@ def flame_dso_submit(dso, history_emb: np.ndarray, cand_emb: np.ndarray, scores:
 
 def flame_dso_wait(dso, ticket: int) -> None:
     _dso_check(_lib.flame_dso_wait(dso, ticket), dso)
+
+
+def flame_dso_flush(dso) -> None:
+    _dso_check(_lib.flame_dso_flush(dso), dso)
 
 
 def flame_dso_drain(dso) -> None:

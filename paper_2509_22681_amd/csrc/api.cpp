@@ -500,7 +500,7 @@ int flame_gr_forward_hidden(flame_gr_t *h, const flame_gr_weights *w, const void
 
 int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, const void *history_emb,
                      const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
-                     int32_t n_requests, float *scores) {
+                     int32_t n_requests, float *scores, void *record_stream) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
@@ -526,7 +526,11 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
   h->cap_valid = false;
   if (cg.exec) { HIP_TRY(h, hipGraphExecDestroy(cg.exec)); cg.exec = nullptr; }
   if (!cg.tables) HIP_TRY(h, hipMalloc((void **)&cg.tables, h->lay.total));
-  if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
+  hipStream_t cs = (hipStream_t)record_stream;
+  if (!cs) {
+    if (!h->cap_stream) HIP_TRY(h, hipStreamCreateWithFlags(&h->cap_stream, hipStreamNonBlocking));
+    cs = h->cap_stream;
+  }
   h->plan = std::move(plan);
   const Plan &P = h->plan;
   auto upload = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
@@ -536,18 +540,18 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
   HIP_TRY(h, upload(h->lay.items, P.items.data(), P.items.size() * sizeof(AttnItem)));
   HIP_TRY(h, upload(h->lay.cand_items, P.cand_items.data(), P.cand_items.size() * sizeof(AttnItem)));
   HIP_TRY(h, upload(h->lay.cand_blocks, P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t)));
-  derive_weights(h, w, h->cap_stream);
-  HIP_TRY(h, hipStreamSynchronize(h->cap_stream));
+  derive_weights(h, w, cs);
+  HIP_TRY(h, hipStreamSynchronize(cs));
   // the layer sequence, recorded instead of run (kernel launches only: no copies, no memsets), reading this slot's tables
   const bool prof = h->profiling;
   char *const eager_tables = h->stage_dev;
   h->profiling = false;
   h->stage_dev = cg.tables;
   hipGraph_t graph = nullptr;
-  hipError_t e = hipStreamBeginCapture(h->cap_stream, hipStreamCaptureModeThreadLocal);
+  hipError_t e = hipStreamBeginCapture(cs, hipStreamCaptureModeThreadLocal);
   if (e == hipSuccess) {
-    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, h->cap_stream, PASS_FULL);
-    e = hipStreamEndCapture(h->cap_stream, &graph);
+    run_group(h, *w, P.groups[0], history_emb, cand_emb, scores, cs, PASS_FULL);
+    e = hipStreamEndCapture(cs, &graph);
   }
   h->stage_dev = eager_tables;
   h->profiling = prof;

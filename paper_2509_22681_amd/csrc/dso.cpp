@@ -1,6 +1,11 @@
 // Request orchestrator (flame_dso.h): explicit-shape executors with captured graphs, an executor
 // index queue, descending-size split routing, pinned staging (Sections 3.1 and 3.3 of the paper).
 //
+// Three modes: explicit shapes (one captured graph per profile on every executor), implicit shapes (the paper's
+// baseline: eager dynamic-shape forward per request), and jagged micro-batches (several pending requests of any
+// candidate counts scored by one jagged forward: what the jagged kernels make possible in place of shape
+// profiles).
+//
 // Single host thread, no threads of its own: completion is tracked with one event per executor,
 // and an executor's index goes back to the queue when its event is found complete (on wait, drain,
 // or when a submit finds the queue empty).
@@ -24,7 +29,10 @@ struct Pending { int64_t ticket = -1; float *dst = nullptr; int32_t m = 0; };
 
 struct Executor {
   flame_gr_t *h = nullptr;
-  int32_t cap = 0;          // candidate rows of the buffers (the largest profile)
+  int32_t cap = 0;          // candidate rows of the buffers (largest profile x requests per batch)
+  int32_t n_req = 0, n_cand = 0;          // jagged mode: requests and candidate rows gathered so far
+  std::vector<Pending> batch;             // jagged mode: what the gathered requests are owed (reserved at create)
+  std::vector<int32_t> hoff, coff;        // jagged mode: offsets of the gathered batch (reserved at create)
   hipStream_t stream = nullptr;
   hipEvent_t done = nullptr;
   char *pin_in = nullptr, *dev_in = nullptr;
@@ -89,6 +97,9 @@ struct flame_dso {
   flame_gr_config model{};
   flame_gr_weights weights{};
   bool explicit_shapes = true;
+  bool jagged = false;
+  int32_t max_batch = 1;
+  int gathering = -1;       // jagged mode: executor that collects the next batch, -1 if none
   int32_t L = 0, d = 0;
   size_t elt = 2;
   std::vector<int32_t> profiles;
@@ -117,11 +128,54 @@ int retire(flame_dso *d, int idx) {
   Executor &e = d->ex[idx];
   if (!e.busy) return FLAME_GR_OK;
   DSO_HIP(d, hipEventSynchronize(e.done));
-  std::memcpy(e.pending.dst, e.pin_scores, (size_t)e.pending.m * sizeof(float));
+  if (d->jagged) {
+    int32_t at = 0;
+    for (const Pending &p : e.batch) {
+      std::memcpy(p.dst, e.pin_scores + at, (size_t)p.m * sizeof(float));
+      at += p.m;
+    }
+    e.batch.clear();
+    e.n_req = e.n_cand = 0;
+  } else {
+    std::memcpy(e.pending.dst, e.pin_scores, (size_t)e.pending.m * sizeof(float));
+  }
   e.busy = false;
   e.pending = Pending();
   d->busy_q.erase(std::find(d->busy_q.begin(), d->busy_q.end(), idx));
   d->free_q.push_back(idx);
+  return FLAME_GR_OK;
+}
+
+// Jagged mode: send the gathered batch of executor idx to the GPU as one jagged forward.
+int flush(flame_dso *d, int idx) {
+  Executor &e = d->ex[idx];
+  d->gathering = -1;
+  if (e.n_req == 0) { d->free_q.push_front(idx); return FLAME_GR_OK; }
+  const size_t row = (size_t)d->d * d->elt;
+  const size_t hist_region = (size_t)d->max_batch * d->L * row;
+  e.busy = true;
+  d->busy_q.push_back(idx);
+  ++d->stats[1];
+  d->stats[2] += e.n_cand;
+  if (d->L > 0) DSO_HIP(d, hipMemcpyAsync(e.dev_in, e.pin_in, (size_t)e.n_req * d->L * row, hipMemcpyHostToDevice, e.stream));
+  DSO_HIP(d, hipMemcpyAsync(e.dev_in + hist_region, e.pin_in + hist_region, (size_t)e.n_cand * row, hipMemcpyHostToDevice, e.stream));
+  int rc = flame_gr_forward(e.h, &d->weights, e.dev_in, e.hoff.data(), e.dev_in + hist_region, e.coff.data(), e.n_req,
+                            e.dev_scores, e.stream);
+  if (rc) { d->err = std::string("executor: ") + flame_gr_last_error(e.h); return rc; }
+  DSO_HIP(d, hipMemcpyAsync(e.pin_scores, e.dev_scores, (size_t)e.n_cand * sizeof(float), hipMemcpyDeviceToHost, e.stream));
+  DSO_HIP(d, hipEventRecord(e.done, e.stream));
+  return FLAME_GR_OK;
+}
+
+// A free executor, waiting for the one handed out earliest if none is free.
+int acquire(flame_dso *d, int *idx) {
+  if (d->free_q.empty()) {
+    ++d->stats[3];
+    int rc = retire(d, d->busy_q.front());
+    if (rc) return rc;
+  }
+  *idx = d->free_q.front();
+  d->free_q.pop_front();
   return FLAME_GR_OK;
 }
 
@@ -170,12 +224,16 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
   if (!profiles_ok(cfg->profiles, cfg->n_profiles)) return bad("profiles must be 1..16 strictly ascending positive counts");
   if (cfg->hist_len < 0) return bad("hist_len < 0");
   if (cfg->n_executors < 1 || cfg->n_executors > 256) return bad("n_executors must be in [1, 256]");
-  if (cfg->explicit_shapes && cfg->n_profiles > FLAME_GR_MAX_GRAPHS) return bad("more profiles than graph slots per executor");
+  if (cfg->explicit_shapes < 0 || cfg->explicit_shapes > 2) return bad("explicit_shapes must be 0, 1 or 2");
+  if (cfg->explicit_shapes == 1 && cfg->n_profiles > FLAME_GR_MAX_GRAPHS) return bad("more profiles than graph slots per executor");
+  if (cfg->explicit_shapes == 2 && (cfg->max_batch < 1 || cfg->max_batch > 256)) return bad("max_batch must be in [1, 256]");
   flame_dso *d = new (std::nothrow) flame_dso();
   if (!d) { g_dso_create_error = "out of host memory"; return FLAME_GR_HIP_ERROR; }
   d->model = *model;
   d->weights = *weights;
-  d->explicit_shapes = cfg->explicit_shapes != 0;
+  d->explicit_shapes = cfg->explicit_shapes == 1;
+  d->jagged = cfg->explicit_shapes == 2;
+  d->max_batch = d->jagged ? cfg->max_batch : 1;
   d->L = cfg->hist_len;
   d->d = model->d_model;
   d->elt = model->dtype == FLAME_GR_BF16 ? 2 : 4;
@@ -197,16 +255,19 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
   for (int k = 0; k < cfg->n_executors; ++k) {
     d->ex.emplace_back();
     Executor &e = d->ex.back();
-    e.cap = d->profiles.back();
+    e.cap = d->profiles.back() * d->max_batch;
+    e.batch.reserve(d->max_batch);
+    e.hoff.reserve(d->max_batch + 1);
+    e.coff.reserve(d->max_batch + 1);
     flame_gr_config c = *model;
-    c.max_requests = 1;
-    c.max_total_tokens = d->L + e.cap;
+    c.max_requests = d->max_batch;
+    c.max_total_tokens = d->max_batch * d->L + e.cap;
     c.max_seq_tokens = 0;
     c.n_streams = 0;
     c.kv_cache = 0;
     int rc = flame_gr_create(&c, &e.h);
     if (rc) return fail(rc, std::string("executor create: ") + flame_gr_last_error(nullptr));
-    const size_t in_bytes = (size_t)(d->L + e.cap) * row;
+    const size_t in_bytes = ((size_t)d->max_batch * d->L + e.cap) * row;
     CR(hipStreamCreateWithFlags(&e.stream, hipStreamNonBlocking));
     CR(hipEventCreateWithFlags(&e.done, hipEventDisableTiming));
     CR(hipHostMalloc((void **)&e.pin_in, in_bytes, hipHostMallocDefault));
@@ -219,7 +280,7 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
     if (d->explicit_shapes)
       for (int p = 0; p < cfg->n_profiles; ++p) {      // one graph per profile, all on this executor's buffers
         const int32_t hoff[2] = {0, d->L}, coff[2] = {0, d->profiles[p]};
-        rc = flame_gr_capture(e.h, p, weights, e.dev_in, hoff, e.dev_in + (size_t)d->L * row, coff, 1, e.dev_scores);
+        rc = flame_gr_capture(e.h, p, weights, e.dev_in, hoff, e.dev_in + (size_t)d->L * row, coff, 1, e.dev_scores, e.stream);
         if (rc) return fail(rc, std::string("executor capture: ") + flame_gr_last_error(e.h));
       }
     d->free_q.push_back(k);
@@ -245,15 +306,44 @@ int flame_dso_submit(flame_dso_t *d, const void *history_emb, const void *cand_e
   const size_t hist_bytes = (size_t)d->L * row;
   int32_t taken = 0;
   ++d->stats[0];
+  if (d->jagged) {
+    // every piece (the whole request unless it exceeds the largest profile) joins the gathering batch
+    const size_t hist_region = (size_t)d->max_batch * hist_bytes;
+    for (const Piece &pc : pieces) {
+      if (d->gathering >= 0 && d->ex[d->gathering].n_cand + pc.count > d->ex[d->gathering].cap) {
+        int rc = flush(d, d->gathering);
+        if (rc) return rc;
+      }
+      if (d->gathering < 0) {
+        int rc = acquire(d, &d->gathering);
+        if (rc) return rc;
+        Executor &g = d->ex[d->gathering];
+        g.hoff.assign(1, 0);
+        g.coff.assign(1, 0);
+      }
+      Executor &e = d->ex[d->gathering];
+      if (hist_bytes) std::memcpy(e.pin_in + (size_t)e.n_req * hist_bytes, history_emb, hist_bytes);
+      std::memcpy(e.pin_in + hist_region + (size_t)e.n_cand * row, (const char *)cand_emb + (size_t)taken * row, (size_t)pc.count * row);
+      e.batch.push_back(Pending{t, scores + taken, pc.count});
+      ++e.n_req;
+      e.n_cand += pc.count;
+      e.hoff.push_back(e.n_req * d->L);
+      e.coff.push_back(e.n_cand);
+      taken += pc.count;
+      if (e.n_req == d->max_batch) {
+        int rc = flush(d, d->gathering);
+        if (rc) return rc;
+      }
+    }
+    *ticket = t;
+    return FLAME_GR_OK;
+  }
   for (const Piece &pc : pieces) {
-    if (d->free_q.empty()) {
-      // every executor is in flight: the one handed out earliest comes back first
-      ++d->stats[3];
-      int rc = retire(d, d->busy_q.front());
+    int idx;
+    {
+      int rc = acquire(d, &idx);
       if (rc) return rc;
     }
-    const int idx = d->free_q.front();
-    d->free_q.pop_front();
     Executor &e = d->ex[idx];
     const int32_t m = pc.count;
     if (hist_bytes) std::memcpy(e.pin_in, history_emb, hist_bytes);
@@ -284,8 +374,19 @@ int flame_dso_wait(flame_dso_t *d, int64_t ticket) {
   if (!live(d)) return FLAME_GR_BAD_HANDLE;
   d->err.clear();
   if (ticket < 1 || ticket >= d->next_ticket) { d->err = "unknown ticket"; return FLAME_GR_INVALID_ARGUMENT; }
+  auto holds = [&](const Executor &e) {
+    if (!d->jagged) return e.pending.ticket == ticket;
+    for (const Pending &p : e.batch)
+      if (p.ticket == ticket) return true;
+    return false;
+  };
+  // a request that still sits in the gathering batch goes to the GPU now
+  if (d->gathering >= 0 && holds(d->ex[d->gathering])) {
+    int rc = flush(d, d->gathering);
+    if (rc) return rc;
+  }
   for (int i = 0; i < (int)d->ex.size(); ++i)
-    if (d->ex[i].busy && d->ex[i].pending.ticket == ticket) {
+    if (d->ex[i].busy && holds(d->ex[i])) {
       int rc = retire(d, i);
       if (rc) return rc;
     }
@@ -295,11 +396,21 @@ int flame_dso_wait(flame_dso_t *d, int64_t ticket) {
 int flame_dso_drain(flame_dso_t *d) {
   if (!live(d)) return FLAME_GR_BAD_HANDLE;
   d->err.clear();
+  if (d->gathering >= 0) {
+    int rc = flush(d, d->gathering);
+    if (rc) return rc;
+  }
   for (int i = 0; i < (int)d->ex.size(); ++i) {
     int rc = retire(d, i);
     if (rc) return rc;
   }
   return FLAME_GR_OK;
+}
+
+int flame_dso_flush(flame_dso_t *d) {
+  if (!live(d)) return FLAME_GR_BAD_HANDLE;
+  d->err.clear();
+  return d->gathering >= 0 ? flush(d, d->gathering) : (int)FLAME_GR_OK;
 }
 
 int flame_dso_stats(const flame_dso_t *d, int64_t *out) {

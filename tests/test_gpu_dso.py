@@ -144,7 +144,7 @@ def _requests(wl_cfg, L, Ms, seed, dtype):
     return out
 
 
-@pytest.mark.parametrize("dtype,explicit", [("bf16", True), ("bf16", False), ("f32", True)])
+@pytest.mark.parametrize("dtype,explicit", [("bf16", True), ("bf16", False), ("f32", True), ("bf16", 2), ("f32", 2)])
 def test_orchestrator_scores_every_request(B, dtype, explicit):
     import torch
     shape = dict(d=64, H=2, layers=2)
@@ -153,7 +153,7 @@ def test_orchestrator_scores_every_request(B, dtype, explicit):
     reqs = _requests(shape, L, Ms, seed=21, dtype=dtype)
     dw, _, _ = B.to_device(reqs[0])
     cfg = B.config_for(reqs[0])
-    dso = B.flame_dso_create(cfg, dw, L, profiles, n_executors=3, explicit_shapes=explicit)
+    dso = B.flame_dso_create(cfg, dw, L, profiles, n_executors=3, explicit_shapes=explicit, max_batch=3)
     try:
         outs = [np.full(M, np.nan, np.float32) for M in Ms]
         tickets = []
@@ -163,7 +163,11 @@ def test_orchestrator_scores_every_request(B, dtype, explicit):
             B.flame_dso_wait(dso, t)
         B.flame_dso_wait(dso, tickets[0])
         st = B.flame_dso_stats(dso)
-        assert st["requests"] == len(Ms) and st["chunks"] >= len(Ms) and st["waits_for_a_busy_executor"] > 0
+        assert st["requests"] == len(Ms)
+        if explicit == 2:       # micro-batches of up to 3 requests: fewer forwards than requests, no padded rows
+            assert st["chunks"] < len(Ms) and st["candidate_rows_computed"] == sum(Ms)
+        else:
+            assert st["chunks"] >= len(Ms) and st["waits_for_a_busy_executor"] > 0
         worst = 0.0
         for r, o in zip(reqs, outs):
             assert np.isfinite(o).all()
@@ -173,7 +177,10 @@ def test_orchestrator_scores_every_request(B, dtype, explicit):
         # a request served in one exact chunk equals the eager forward of that request bit for bit
         for k in (0, 1, 2):
             eager, _ = run_gpu(B, reqs[k])
-            assert np.array_equal(outs[k], eager)
+            if dtype == "f32" and explicit == 2:      # fp32 kernels: equal up to the order of a few sums
+                assert np.allclose(outs[k], eager, rtol=1e-5, atol=1e-6)
+            else:
+                assert np.array_equal(outs[k], eager)
         with pytest.raises(B.FlameGRError) as e:
             B.flame_dso_wait(dso, 10 ** 6)
         assert e.value.code == -1
@@ -183,8 +190,10 @@ def test_orchestrator_scores_every_request(B, dtype, explicit):
         # still serving after the rejected calls, and a drain delivers everything outstanding
         again = np.full(Ms[4], np.nan, np.float32)
         B.flame_dso_submit(dso, B.host_embedding(reqs[4].history_emb, dtype), B.host_embedding(reqs[4].cand_emb, dtype), again)
+        if explicit == 2:
+            B.flame_dso_flush(dso)
         B.flame_dso_drain(dso)
-        assert np.array_equal(again, outs[4])
+        assert np.allclose(again, outs[4], rtol=1e-5, atol=1e-6) if dtype == "f32" else np.array_equal(again, outs[4])
     finally:
         B.flame_dso_destroy(dso)
 
@@ -194,7 +203,8 @@ def test_orchestrator_rejects_bad_configurations(B):
     dw, _, _ = B.to_device(wl)
     cfg = B.config_for(wl)
     for kw in (dict(profiles=[], n_executors=1), dict(profiles=[8, 4], n_executors=1),
-               dict(profiles=[4], n_executors=0), dict(profiles=[4], n_executors=257)):
+               dict(profiles=[4], n_executors=0), dict(profiles=[4], n_executors=257),
+               dict(profiles=[4], n_executors=1, explicit_shapes=3), dict(profiles=[4], n_executors=1, explicit_shapes=2, max_batch=0)):
         with pytest.raises(B.FlameGRError) as e:
             B.flame_dso_create(cfg, dw, 10, **kw)
         assert e.value.code == -1
