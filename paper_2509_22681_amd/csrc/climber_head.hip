@@ -1,7 +1,7 @@
 // Fusion of the sub-sequence blocks and the task head of the paper's model (flame_climber.h):
 //   g_b = sigmoid([H_0 | ... | H_{Nb-1}] Wg_b^T + cg_b),  F = sum_b g_b * H_b,
 //   p_t = sigmoid(<v_t, relu(F A_t^T + a_t)> + c_t).
-// fp32 FMA kernels with LDS tiling (64 x 64 output tile, 16-deep k chunks, 256 threads each owning a
+// fp32 FMA kernels with LDS tiling (64 x 64 output tile, 64-deep k chunks, 256 threads each owning a
 // 4 x 4 patch): correct and allocation-free, not tuned - at the paper's shapes this stage is a few
 // per cent of the block stacks' work.
 #include <hip/hip_runtime.h>
@@ -16,12 +16,45 @@ struct HiddenPtrs { const float *h[kMaxBlocks]; };
 
 __device__ __forceinline__ float sigmoid_f32(float x) { return 1.0f / (1.0f + expf(-x)); }
 
-// F[r][f] for a 64 x 64 tile: for every block b one GEMM over k = 0 .. Nb*d-1 whose A operand is gathered
-// from the Nb hidden matrices, closed by the gate and the product with H_b.
+constexpr int KC = 64;   // k chunk: deep enough that a workgroup's chain of dependent global loads stays short
+
+// One k chunk of a 64 x 64 tile product: sA/sW hold [k][row] and [k][column]; every thread owns a 4 x 4 patch.
+__device__ __forceinline__ void tile_fma(const float (*sA)[64 + 1], const float (*sW)[64 + 1], int tx, int ty, float (&acc)[4][4]) {
+#pragma unroll 8
+  for (int k = 0; k < KC; ++k) {
+    float a[4], w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) { a[i] = sA[k][ty * 4 + i]; w[i] = sW[k][tx * 4 + i]; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
+  }
+}
+
+// Fill one operand chunk: rows r0 .. r0+63 of a row-major matrix with row pitch `pitch`, columns k0 .. k0+63
+// (zero outside n_rows / n_cols).  Thread (kk = tid & 63, rq = tid >> 6) takes column kk of rows rq, rq+4, ...:
+// 16 independent loads per thread, 256 contiguous bytes per row and wavefront.
+__device__ __forceinline__ void fill_chunk(float (*dst)[64 + 1], const float *__restrict__ src, int64_t r0, int64_t n_rows,
+                                           int64_t pitch, int k0, int n_cols) {
+  const int kk = threadIdx.x & 63, rq = threadIdx.x >> 6;
+  const bool kin = k0 + kk < n_cols;
+  float v[16];
+#pragma unroll
+  for (int q = 0; q < 16; ++q) {
+    const int64_t r = r0 + rq + 4 * q;
+    v[q] = (kin && r < n_rows) ? src[r * pitch + k0 + kk] : 0.f;
+  }
+#pragma unroll
+  for (int q = 0; q < 16; ++q) dst[kk][rq + 4 * q] = v[q];
+}
+
+// F[r][f] for a 64 x 64 tile: for every block b one GEMM over the concatenation [H_0 | ... | H_{Nb-1}] (walked
+// source block by source block), closed by the gate and the product with H_b.
 __global__ __launch_bounds__(256) void fuse_kernel(HiddenPtrs H, int n_blocks, const float *__restrict__ wg,
                                                    const float *__restrict__ cg, float *__restrict__ F, int64_t rows, int d) {
-  __shared__ float sA[16][64 + 1];
-  __shared__ float sW[16][64 + 1];
+  __shared__ float sA[KC][64 + 1];
+  __shared__ float sW[KC][64 + 1];
   const int64_t row0 = (int64_t)blockIdx.x * 64;
   const int f0 = blockIdx.y * 64;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -30,30 +63,14 @@ __global__ __launch_bounds__(256) void fuse_kernel(HiddenPtrs H, int n_blocks, c
   for (int b = 0; b < n_blocks; ++b) {
     const float *W = wg + (int64_t)b * d * K;          // [d][K]
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < K; k0 += 16) {
-      for (int i = threadIdx.x; i < 64 * 16; i += 256) {
-        const int r = i >> 4, k = k0 + (i & 15);
-        float a = 0.f, w = 0.f;
-        if (k < K) {
-          if (row0 + r < rows) a = H.h[k / d][(row0 + r) * d + k % d];
-          if (f0 + r < d) w = W[(int64_t)(f0 + r) * K + k];
-        }
-        sA[i & 15][r] = a;
-        sW[i & 15][r] = w;
+    for (int sb = 0; sb < n_blocks; ++sb)
+      for (int k0 = 0; k0 < d; k0 += KC) {
+        fill_chunk(sA, H.h[sb], row0, rows, d, k0, d);
+        fill_chunk(sW, W + (int64_t)sb * d, f0, d, K, k0, d);
+        __syncthreads();
+        tile_fma(sA, sW, tx, ty, acc);
+        __syncthreads();
       }
-      __syncthreads();
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        float a[4], w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { a[i] = sA[k][ty * 4 + i]; w[i] = sW[k][tx * 4 + i]; }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
-      }
-      __syncthreads();
-    }
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
@@ -80,9 +97,8 @@ __global__ __launch_bounds__(256) void expert_kernel(const float *__restrict__ F
                                                      const float *__restrict__ a_b, const float *__restrict__ v,
                                                      const float *__restrict__ c, float *__restrict__ probs, int64_t rows,
                                                      int d, int E, int T) {
-  __shared__ float sA[16][64 + 1];
-  __shared__ float sW[16][64 + 1];
-  __shared__ float sR[64][16 + 1];
+  __shared__ float sA[KC][64 + 1];
+  __shared__ float sW[KC][64 + 1];
   const int64_t row0 = (int64_t)blockIdx.x * 64;
   const int t = blockIdx.y;
   const int tx = threadIdx.x & 15, ty = threadIdx.x >> 4;
@@ -90,23 +106,11 @@ __global__ __launch_bounds__(256) void expert_kernel(const float *__restrict__ F
   float part[4] = {0.f, 0.f, 0.f, 0.f};
   for (int e0 = 0; e0 < E; e0 += 64) {
     float acc[4][4] = {};
-    for (int k0 = 0; k0 < d; k0 += 16) {
-      for (int i = threadIdx.x; i < 64 * 16; i += 256) {
-        const int r = i >> 4, k = k0 + (i & 15);
-        sA[i & 15][r] = (k < d && row0 + r < rows) ? F[(row0 + r) * d + k] : 0.f;
-        sW[i & 15][r] = (k < d && e0 + r < E) ? W[(int64_t)(e0 + r) * d + k] : 0.f;
-      }
+    for (int k0 = 0; k0 < d; k0 += KC) {
+      fill_chunk(sA, F, row0, rows, d, k0, d);
+      fill_chunk(sW, W, e0, E, d, k0, d);
       __syncthreads();
-#pragma unroll
-      for (int k = 0; k < 16; ++k) {
-        float a[4], w[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) { a[i] = sA[k][ty * 4 + i]; w[i] = sW[k][tx * 4 + i]; }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], w[j], acc[i][j]);
-      }
+      tile_fma(sA, sW, tx, ty, acc);
       __syncthreads();
     }
 #pragma unroll
@@ -119,6 +123,8 @@ __global__ __launch_bounds__(256) void expert_kernel(const float *__restrict__ F
       }
     }
   }
+  // sum over the 16 threads of a row, through a slice of sA (free by now)
+  float (*sR)[16 + 1] = (float (*)[16 + 1])&sA[0][0];
 #pragma unroll
   for (int i = 0; i < 4; ++i) sR[ty * 4 + i][tx] = part[i];
   __syncthreads();
