@@ -78,9 +78,9 @@ typedef struct {
                                 partitioned into k cost-balanced groups that run on k internal
                                 streams, joined to the caller's stream by events (Section 3.3) */
   int32_t attn_kind;         /* flame_gr_attn_kind */
-  int32_t kv_cache;          /* 0 = one-pass forward only; 1 = also allocate per-layer U/V/Q/K workspaces
-                                (n_layers times the one-pass amount) so that flame_gr_prefill and
-                                flame_gr_score can keep the history keys and values of every layer */
+  int32_t kv_cache;          /* 0 = one-pass forward only; 1 = also allocate a K and a V plane per layer so
+                                that flame_gr_prefill and flame_gr_score can keep the history keys and
+                                values of every layer */
 } flame_gr_config;
 
 /* Model weights: device pointers, caller-owned, read-only, element type = config.dtype unless
@@ -178,8 +178,9 @@ int flame_gr_replay(flame_gr_t *h, int32_t slot, void *stream);
  *                    capacity checks of create apply to L_i + cand_capacity[i], and a request is
  *                    never split: L_i + cand_capacity[i] above a non-zero max_seq_tokens is
  *                    UNSUPPORTED)
- * The cache belongs to the handle and is replaced by the next flame_gr_prefill; a
- * flame_gr_forward on the same handle invalidates it. */
+ * The cache (K and V of every layer: 2 x n_layers x rows x d fp16 elements beside the one-pass
+ * workspaces) belongs to the handle and is replaced by the next flame_gr_prefill; one-pass forwards
+ * and replays on the same handle leave it intact. */
 int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *weights, const void *history_emb,
                      const int32_t *history_offsets, const int32_t *cand_capacity, int32_t n_requests,
                      void *stream);

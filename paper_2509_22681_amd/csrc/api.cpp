@@ -78,8 +78,9 @@ struct flame_gr {
   // explicit-shape executor: the one-pass forward of one fixed batch, captured as a HIP graph
   hipStream_t cap_stream = nullptr;
   CapturedGraph graphs[kMaxGraphs];
-  // two-stage path: what the last prefill cached (layer l keeps its planes at planes + l * plane_set_bytes)
-  size_t plane_set_bytes = 0;
+  // two-stage path: what the last prefill cached (layer l keeps V and K at kv + l * 2 * plane_bytes)
+  size_t plane_bytes = 0;
+  char *kv = nullptr;
   bool kv_valid = false;
   std::vector<int32_t> kv_hoff, kv_cap;
   // debug capture
@@ -125,7 +126,7 @@ float half_bits_to_float(uint16_t b) {
 }
 
 void free_all(flame_gr *h) {
-  (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->O); (void)hipFree(h->G);
+  (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->kv); (void)hipFree(h->O); (void)hipFree(h->G);
   (void)hipFree(h->bias); (void)hipFree(h->tscale); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
   (void)hipFree(h->W1h); (void)hipFree(h->W2h); (void)hipFree(h->W2p);
   (void)hipFree(h->cap_planes); (void)hipFree(h->cap_O); (void)hipFree(h->cap_X);
@@ -195,7 +196,14 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
   for (int l = 0; l < sh.n_layers; ++l) {
     const bool capture = mode == PASS_FULL && h->capture_layer == l;
     const bool last = (l == sh.n_layers - 1) && !capture;
-    char *planes = (char *)h->planes + (mode == PASS_FULL ? 0 : (size_t)l * h->plane_set_bytes);
+    // one-pass: the four planes of the handle, reused by every layer; two-stage: U and Q there, V and K in the
+    // layer's own pair of planes, where the candidate pass finds the history rows that the history pass left
+    char *planes = (char *)h->planes;
+    PlanePtrs pp{planes, planes + h->plane_bytes, planes + 2 * h->plane_bytes, planes + 3 * h->plane_bytes};
+    if (mode != PASS_FULL) {
+      pp.v = h->kv + (size_t)l * 2 * h->plane_bytes;
+      pp.k = h->kv + ((size_t)l * 2 + 1) * h->plane_bytes;
+    }
     const char *w1 = (const char *)(dt == FLAME_GR_BF16 ? h->W1h : w.w1) + (size_t)l * 4 * d * d * e;
     const char *b1 = (const char *)w.b1 + (size_t)l * 4 * d * e;
     const char *w2 = (const char *)(dt == FLAME_GR_BF16 ? h->W2h : w.w2) + (size_t)l * d * d * e;
@@ -210,10 +218,10 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
     if (dt == FLAME_GR_BF16) {
       Timed t(h, KIND_UVQK, s);
       if (mode == PASS_FULL && last) {
-        launch_uvqk_bf16(h->Xb, w1, b1, planes, nullptr, n_blk, G.blk_begin, 0xA, sh, s);  // V, K: all rows
-        launch_uvqk_bf16(h->Xb, w1, b1, planes, cl, n_cblk, 0, 0x5, sh, s);                // U, Q: candidates
+        launch_uvqk_bf16(h->Xb, w1, b1, pp, nullptr, n_blk, G.blk_begin, 0xA, sh, s);  // V, K: all rows
+        launch_uvqk_bf16(h->Xb, w1, b1, pp, cl, n_cblk, 0, 0x5, sh, s);                // U, Q: candidates
       } else {
-        launch_uvqk_bf16(h->Xb, w1, b1, planes, pass_list, pass_n, pass_first, mode == PASS_HISTORY && last ? 0xA : 0xF, sh, s);
+        launch_uvqk_bf16(h->Xb, w1, b1, pp, pass_list, pass_n, pass_first, mode == PASS_HISTORY && last ? 0xA : 0xF, sh, s);
       }
     } else {
       Timed t(h, KIND_UVQK, s);
@@ -226,7 +234,7 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
       int n_it = G.item_end - G.item_begin;
       if (mode == PASS_HISTORY) { it = hitems + G.hitem_begin; n_it = G.hitem_end - G.hitem_begin; }
       else if (mode == PASS_CANDIDATES || last) { it = citems + G.citem_begin; n_it = G.citem_end - G.citem_begin; }
-      if (dt == FLAME_GR_BF16) launch_attn_bf16(planes, bias_l, tscale_l, h->O, it, n_it, sh, s);
+      if (dt == FLAME_GR_BF16) launch_attn_bf16(pp, bias_l, tscale_l, h->O, it, n_it, sh, s);
       else launch_attn_f32((const float *)planes, bias_l, tscale_l, (float *)h->O, it, n_it, h->q_tile, sh, s);
     }
     const int32_t *bl = mode == PASS_FULL ? (last ? cl : nullptr) : pass_list;
@@ -386,9 +394,9 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   CR(hipGetDevice(&h->device));
   const size_t rows = (size_t)h->ws_rows, d = (size_t)cfg.d_model, e = h->elt;
   CR(hipMalloc(&h->X, rows * d * sizeof(float)));
-  h->plane_set_bytes = 4 * rows * d * e;
-  const size_t n_plane_sets = cfg.kv_cache ? (size_t)cfg.n_layers : 1;
-  CR(hipMalloc(&h->planes, n_plane_sets * h->plane_set_bytes));
+  h->plane_bytes = rows * d * e;
+  CR(hipMalloc(&h->planes, 4 * h->plane_bytes));
+  if (cfg.kv_cache) CR(hipMalloc((void **)&h->kv, (size_t)cfg.n_layers * 2 * h->plane_bytes));
   CR(hipMalloc(&h->O, rows * d * e));
   CR(hipMalloc(&h->G, rows * d * e));
   if (cfg.dtype == FLAME_GR_BF16) {
@@ -403,7 +411,8 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   // Every workspace starts finite: rows that a batch leaves as padding are read (and multiplied
   // by zero weights) by the tiled kernels.
   CR(hipMemset(h->X, 0, rows * d * sizeof(float)));
-  CR(hipMemset(h->planes, 0, n_plane_sets * h->plane_set_bytes));
+  CR(hipMemset(h->planes, 0, 4 * h->plane_bytes));
+  if (h->kv) CR(hipMemset(h->kv, 0, (size_t)cfg.n_layers * 2 * h->plane_bytes));
   CR(hipMemset(h->O, 0, rows * d * e));
   CR(hipMemset(h->G, 0, rows * d * e));
   if (h->Xb) CR(hipMemset(h->Xb, 0, rows * d * e));
@@ -470,7 +479,6 @@ static int forward_common(flame_gr_t *h, const flame_gr_weights *w, const void *
   if (plan.total_rows > 0 && !weights_complete(h, w, !want_hidden)) return bad("a weight pointer is NULL");
   h->plan = std::move(plan);
   h->cap_valid = false;
-  h->kv_valid = false;  // the one-pass forward works in the planes of layer 0
   if (h->plan.total_rows == 0) return FLAME_GR_OK;
   rc = enqueue_pass(h, w, history_emb, cand_emb, scores, (hipStream_t)stream_v, PASS_FULL, want_hidden ? hidden : nullptr);
   if (rc) return rc;
@@ -522,7 +530,6 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
   if (h->has_prev) HIP_TRY(h, hipEventSynchronize(h->ev_done));
   CapturedGraph &cg = h->graphs[slot];
   cg.valid = false;
-  h->kv_valid = false;
   h->cap_valid = false;
   if (cg.exec) { HIP_TRY(h, hipGraphExecDestroy(cg.exec)); cg.exec = nullptr; }
   if (!cg.tables) HIP_TRY(h, hipMalloc((void **)&cg.tables, h->lay.total));
@@ -577,7 +584,6 @@ int flame_gr_replay(flame_gr_t *h, int32_t slot, void *stream_v) {
   HIP_TRY(h, hipGraphLaunch(h->graphs[slot].exec, s0));
   HIP_TRY(h, hipEventRecord(h->ev_done, s0));
   h->has_prev = true;
-  h->kv_valid = false;  // the replay works in the planes of layer 0
   h->cap_valid = false;
   return FLAME_GR_OK;
 }

@@ -86,7 +86,7 @@ __device__ __forceinline__ f16x8 pack8(const float *v) {
 // with tscale = 2 log2(e) / tau.  The 64 keys of a half tile of one query sit in two lanes (lane and lane ^ 32),
 // which exchange their maxima with one half-swap; their partial sums are only added at the end.
 template <int DH, bool SOFTMAX>
-__global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__restrict__ planes, const float *__restrict__ bias_lh,
+__global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes, const float *__restrict__ bias_lh,
                                                            const float *__restrict__ tscale_h,
                                                            half_t *__restrict__ O, const AttnItem *__restrict__ items,
                                                            int H, int d, int D, int64_t ws_rows) {
@@ -112,10 +112,9 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int l32 = lane & 31, lhalf = lane >> 5;
 
-  const int64_t plane = ws_rows * d;
-  const half_t *Vt = planes + 1 * plane + (int64_t)head * DH * ws_rows;   // [DH][ws_rows]
-  const half_t *Qp = planes + 2 * plane + head * DH;                      // [row][d]
-  const half_t *Kp = planes + 3 * plane + head * DH;
+  const half_t *Vt = (const half_t *)planes.v + (int64_t)head * DH * ws_rows;   // [DH][ws_rows]
+  const half_t *Qp = (const half_t *)planes.q + head * DH;                      // [row][d]
+  const half_t *Kp = (const half_t *)planes.k + head * DH;
   const float *bias = bias_lh + (int64_t)head * D;
 
   // this wavefront's 32 query rows
@@ -496,11 +495,11 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(const half_t *__r
 
 }  // namespace
 
-void launch_attn_bf16(const void *planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
+void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
                       int n_items, const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   const int grid = n_items * sh.H;
-#define ATTN_CASE(DHV, SM) attn_mfma_kernel<DHV, SM><<<grid, 64 * NW, 0, s>>>((const half_t *)planes, bias_lh, tscale_h, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
+#define ATTN_CASE(DHV, SM) attn_mfma_kernel<DHV, SM><<<grid, 64 * NW, 0, s>>>(planes, bias_lh, tscale_h, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
   if (sh.softmax) {
     if (sh.dh == 32) ATTN_CASE(32, true);
     else ATTN_CASE(64, true);

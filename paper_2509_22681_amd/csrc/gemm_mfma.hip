@@ -63,7 +63,7 @@ __device__ __forceinline__ int sigma32(int m) { return ((m & 4) << 2) | ((m >> 3
 template <int BN, int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     const half_t *__restrict__ A, const half_t *__restrict__ W, const bf16_t *__restrict__ bias,
-    half_t *__restrict__ planes, float *__restrict__ X, half_t *__restrict__ Xh,
+    PlanePtrs planes, float *__restrict__ X, half_t *__restrict__ Xh,
     const int32_t *__restrict__ blk_list, int blk_first, int n_blk, int n_row_tiles, int n_col_tiles, int K, int d,
     int64_t ws_rows, PlaneSel sel, float alpha, bool a_blocked) {
   constexpr int WN = BN / 2;            // wavefront patch: 128 rows x WN columns
@@ -259,7 +259,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     // whole 128-byte lines per output row.
     __builtin_amdgcn_s_barrier();                     // every wavefront has finished reading the ring
     char *pb = smem + wave * (128 * WN * 2);
-    half_t *P = planes + (int64_t)plane * ws_rows * d;
+    half_t *P = (half_t *)(plane == 0 ? planes.u : plane == 1 ? planes.v : plane == 2 ? planes.q : planes.k);
     if (!feature_major) {
       // patch[128 tokens][WN features]; lane holds token 32i + l32, features 32j + 16*lhalf + 0..15
       // (the bias is already in the accumulators).  Q leaves this kernel multiplied by alpha / 2: the
@@ -359,7 +359,7 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 
 }  // namespace
 
-void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
+void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, PlanePtrs planes, const int32_t *blk_list,
                       int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s) {
   if (n_blk <= 0 || !(plane_mask & 0xF)) return;
   PlaneSel sel{};
@@ -369,12 +369,12 @@ void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *pla
   if (sh.d % 128 == 0) {
     const int col_tiles = sel.n * (sh.d / 128);
     gemm_mfma_kernel<128, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
-                                                                   (half_t *)planes, nullptr, nullptr, blk_list, blk_first, n_blk,
+                                                                   planes, nullptr, nullptr, blk_list, blk_first, n_blk,
                                                                    row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha, true);
   } else {
     const int col_tiles = sel.n * (sh.d / 64);
     gemm_mfma_kernel<64, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
-                                                                  (half_t *)planes, nullptr, nullptr, blk_list, blk_first, n_blk,
+                                                                  planes, nullptr, nullptr, blk_list, blk_first, n_blk,
                                                                   row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha, true);
   }
 }
@@ -386,12 +386,12 @@ void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *
   const int row_tiles = (n_blk + RB - 1) / RB;
   if (sh.d % 128 == 0) {
     const int col_tiles = sh.d / 128;
-    gemm_mfma_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X,
+    gemm_mfma_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, PlanePtrs{}, X,
                                                                    (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
                                                                    sh.d, sh.d, sh.ws_rows, sel, 1.0f, false);
   } else {
     const int col_tiles = sh.d / 64;
-    gemm_mfma_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, nullptr, X,
+    gemm_mfma_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, PlanePtrs{}, X,
                                                                   (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
                                                                   sh.d, sh.d, sh.ws_rows, sel, 1.0f, false);
   }

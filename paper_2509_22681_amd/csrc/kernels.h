@@ -56,15 +56,19 @@ void launch_attn_f32(const float *planes, const float *bias_lh, const float *tsc
 void launch_outproj_f32(const float *G, const float *W2, const float *b2, float *X,
                         const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
+// The four activation planes of a layer (MFMA path), each [ws_rows][d] fp16 (V feature-major [d][ws_rows]).  The
+// one-pass forward keeps them in one allocation; the two-stage path points v and k at the layer's cache.
+struct PlanePtrs { void *u, *v, *q, *k; };
+
 // ---- bf16-storage path (gemm_mfma.hip, attn_mfma.hip): fp16 MFMA kernels, fp32 accumulation --------
 // Activations (Xh, planes, O, G) and the converted matrices W1h/W2h are fp16; biases stay bf16.
 // Xh, W1h and W2h are k-tile blocked (device_common.h: blocked_index); planes, O and G are row-major.
 // U, Q, K planes row-major [row][d]; the V plane is written transposed, Vt[n][row] (row stride ws_rows).
 // plane_mask bit p set = compute plane p (U=1, V=2, Q=4, K=8).
-void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, void *planes, const int32_t *blk_list,
+void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, PlanePtrs planes, const int32_t *blk_list,
                       int n_blk, int blk_first, int plane_mask, const Shape &sh, hipStream_t s);
 // tscale_h (softmax only): 2 log2(e) / tau per head (the kernel holds halved logits and uses the base-2 exponential).
-void launch_attn_bf16(const void *planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
+void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
                       int n_items, const Shape &sh, hipStream_t s);
 // X[row] += G W2h^T + b2, and Xh[row] = fp16(X[row])
 void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
