@@ -28,6 +28,9 @@
  *     "host" pointers are ordinary host memory.  The caller owns every pointer it passes; the
  *     library owns the handle and its workspaces.
  *   - A handle is used by one host thread at a time.
+ *   - With dtype FLAME_GR_BF16 every embedding and weight pointer must be 16-byte aligned (the kernels
+ *     read 8 elements at a time; rows are multiples of 128 bytes because d % 64 == 0); a misaligned
+ *     pointer is INVALID_ARGUMENT.
  */
 #ifndef FLAME_GR_H
 #define FLAME_GR_H

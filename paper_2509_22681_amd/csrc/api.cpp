@@ -4,6 +4,7 @@
 // streams, created once; the request path allocates nothing.
 #include <hip/hip_runtime.h>
 
+#include <cstdint>
 #include <cstring>
 #include <new>
 #include <utility>
@@ -346,6 +347,14 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
   return FLAME_GR_OK;
 }
 
+// The MFMA path reads embeddings and weights 16 bytes at a time.
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+bool pointers_aligned(const flame_gr *h, const flame_gr_weights *w, const void *hist, const void *cand) {
+  if (h->cfg.dtype != FLAME_GR_BF16) return true;
+  return aligned16(hist) && aligned16(cand) && aligned16(w->w1) && aligned16(w->b1) && aligned16(w->ln_g) && aligned16(w->ln_b) &&
+         aligned16(w->w2) && aligned16(w->b2) && aligned16(w->w_s);
+}
+
 // w_s may be absent when the caller asks for hidden rows instead of scores
 bool weights_complete(const flame_gr *h, const flame_gr_weights *w, bool need_score_head = true) {
   return w->w1 && w->b1 && w->rab && w->ln_g && w->ln_b && w->w2 && w->b2 && (w->w_s || !need_score_head) &&
@@ -477,6 +486,7 @@ static int forward_common(flame_gr_t *h, const flame_gr_weights *w, const void *
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
   if (sumM > 0 && (!cand_emb || (!scores && !hidden))) return bad("cand_emb or the output array is NULL");
   if (plan.total_rows > 0 && !weights_complete(h, w, !want_hidden)) return bad("a weight pointer is NULL");
+  if (!pointers_aligned(h, w, history_emb, cand_emb)) return bad("bf16 embeddings and weights must be 16-byte aligned");
   h->plan = std::move(plan);
   h->cap_valid = false;
   if (h->plan.total_rows == 0) return FLAME_GR_OK;
@@ -526,6 +536,7 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
   if (!cand_emb || !scores) return bad("cand_emb or scores is NULL");
   if (!weights_complete(h, w)) return bad("a weight pointer is NULL");
+  if (!pointers_aligned(h, w, history_emb, cand_emb)) return bad("bf16 embeddings and weights must be 16-byte aligned");
   // setup, outside the graph: wait for earlier work on the handle, then upload the plan and derive the weights
   if (h->has_prev) HIP_TRY(h, hipEventSynchronize(h->ev_done));
   CapturedGraph &cg = h->graphs[slot];
@@ -606,6 +617,7 @@ int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *w, const void *histo
   const int64_t sumL = n_requests ? history_offsets[n_requests] : 0;
   if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
   if (sumL > 0 && !weights_complete(h, w)) return bad("a weight pointer is NULL");
+  if (!pointers_aligned(h, w, history_emb, nullptr)) return bad("bf16 embeddings and weights must be 16-byte aligned");
   h->plan = std::move(plan);
   h->cap_valid = false;
   h->kv_valid = false;
@@ -636,6 +648,7 @@ int flame_gr_score(flame_gr_t *h, const flame_gr_weights *w, const void *cand_em
   const int64_t sumM = n_requests ? cand_offsets[n_requests] : 0;
   if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
   if (sumM > 0 && !weights_complete(h, w)) return bad("a weight pointer is NULL");
+  if (!pointers_aligned(h, w, nullptr, cand_emb)) return bad("bf16 embeddings and weights must be 16-byte aligned");
   h->plan = std::move(plan);
   h->cap_valid = false;
   if (sumM == 0) return FLAME_GR_OK;

@@ -264,6 +264,10 @@ def test_empty_and_degenerate_batches(B):
         with pytest.raises(B.FlameGRError) as e:
             B.flame_gr_forward(h, dw, None, np.array([0, 5], np.int32), cand, np.array([0, 3], np.int32), scores)
         assert e.value.code == -1
+        with pytest.raises(B.FlameGRError) as e:             # bf16 rows are read 16 bytes at a time
+            B.flame_gr_forward(h, dw, hist.view(-1)[1:1 + 4 * 64].view(4, 64), np.array([0, 4], np.int32), cand,
+                               np.array([0, 3], np.int32), scores)
+        assert e.value.code == -1
         # the handle still works after the rejected calls
         scores.fill_(float("nan"))
         B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
