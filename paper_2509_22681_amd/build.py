@@ -9,7 +9,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflame_gr.so")
 SOURCES = ["api.cpp", "plan.cpp", "dso.cpp", "misc.hip", "kernels_f32.hip", "gemm_mfma.hip", "attn_mfma.hip", "k3_mfma.hip", "climber_head.hip"]
-# packed fp32 VALU instructions are switched off on purpose (build flags)
+# packed fp32 VALU instructions are switched off on purpose: the compiler forms them by itself from plain float
+# code and some of their forms have given wrong results on this hardware
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950", "-Wall", "-Wno-unused-function",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          ]

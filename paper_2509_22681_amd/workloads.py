@@ -208,11 +208,15 @@ WORKLOADS = {
     "jagged":     dict(B=64,  L=("uniform", 256, 2048), M=("zipf", 1.2, 16, 1024),  d=512, H=8, layers=8,  n_buckets=128, dtype="bf16"),
     "long":       dict(B=16,  L=8192,                   M=512,                      d=512, H=8, layers=8,  n_buckets=512, dtype="bf16"),
     "production": dict(B=128, L=("uniform", 1024, 4096), M=("zipf", 1.1, 32, 2000), d=512, H=8, layers=16, n_buckets=128, dtype="bf16"),
+    # the production shape with the softmax-with-temperature attention of the paper's own model (same lengths and
+    # values: the temperatures are drawn last)
+    "production_softmax": dict(B=128, L=("uniform", 1024, 4096), M=("zipf", 1.1, 32, 2000), d=512, H=8, layers=16, n_buckets=128,
+                               dtype="bf16", attn_kind="softmax"),
 }
 
 
 def make_workload(name: str, seed: int = 0, lengths_only: bool = False) -> Optional[Workload]:
-    """One of the five named benchmark workloads.
+    """One of the named benchmark workloads (the five of the benchmark definition and the softmax variant of the last).
 
     Lengths: L_i constant or Uniform[lo, hi] (inclusive); M_i constant or an unbounded Zipf(s)
     draw clipped to [lo, hi].  Lengths are drawn first (L then M) from default_rng(seed), then the
@@ -226,7 +230,8 @@ def make_workload(name: str, seed: int = 0, lengths_only: bool = False) -> Optio
     L = np.full(B, Ls, np.int64) if isinstance(Ls, int) else rng.integers(Ls[1], Ls[2] + 1, B)
     M = np.full(B, Ms, np.int64) if isinstance(Ms, int) else np.clip(rng.zipf(Ms[1], B), Ms[2], Ms[3])
     L_hi = Ls if isinstance(Ls, int) else Ls[2]
-    cfg = GRConfig(s["layers"], s["d"], s["H"], s["n_buckets"], _pow2_above(L_hi), s["dtype"])
+    cfg = GRConfig(s["layers"], s["d"], s["H"], s["n_buckets"], _pow2_above(L_hi), s["dtype"],
+                   attn_kind=s.get("attn_kind", "silu"))
     if lengths_only:
         return Workload(name, cfg, _offsets(L), _offsets(M), np.zeros((0, s["d"]), np.float32),
                         np.zeros((0, s["d"]), np.float32), {})

@@ -36,6 +36,7 @@ SAMPLED = {
     "jagged": None,
     "long": [0, 11],
     "production": "spread",     # smallest, median and largest request by cost, plus two seeded picks
+    "production_softmax": "spread",
 }
 
 
