@@ -76,7 +76,7 @@ def cpu_baseline(wl, budget_s=12.0):
     }
 
 
-def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128):
+def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128, latency_mode=0):
     """Requests submitted one per call in a closed loop over `concurrency` executors (handles), each with its
     own stream (the executor pool of Section 3.3): per-request latency from submission to scores ready
     (HIP events on the executor's stream, recorded right before the call and right after its last kernel),
@@ -87,7 +87,8 @@ def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128)
     L, M = wl.L, wl.M
     c = wl.cfg
     cfg = B.make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype, ln_eps=c.ln_eps,
-                        attn_scale=c.attn_scale, max_requests=1, max_total_tokens=int((L + M).max()))
+                        attn_scale=c.attn_scale, max_requests=1, max_total_tokens=int((L + M).max()),
+                        latency_mode=latency_mode)
     ws = B.pack_weights(dw)
     ho, co = wl.history_offsets, wl.cand_offsets
     E = max(1, concurrency)
@@ -126,7 +127,7 @@ def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128)
         for h in handles:
             B.flame_gr_destroy(h)
     lat = np.array(lat)
-    return {"concurrency": E, "p50_ms": float(np.percentile(lat, 50)), "p99_ms": float(np.percentile(lat, 99)),
+    return {"concurrency": E, "attention_latency_configuration": bool(latency_mode), "p50_ms": float(np.percentile(lat, 50)), "p99_ms": float(np.percentile(lat, 99)),
             "mean_ms": float(lat.mean()), "requests": len(idx),
             "scores_per_s": float(M[idx].sum() / wall)}
 
@@ -415,8 +416,11 @@ def main():
     }
     if not args.no_latency:
         # request mode: one executor (pure per-request compute latency), then eight executors in a closed loop
-        out["request_latency"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=1)
+        # (handles created with latency_mode = 1: the attention kernel's configuration for batches that do not
+        # fill the chip; the same loop on throughput-configured handles is reported beside it)
+        out["request_latency"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=1, latency_mode=1)
         out["p50_request_latency_ms"] = out["request_latency"]["p50_ms"]
+        out["request_latency_throughput_configuration"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=1)
         out["request_latency_8_executors"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=8)
     if two_stage is not None:
         out["two_stage"] = two_stage

@@ -84,6 +84,12 @@ typedef struct {
   int32_t kv_cache;          /* 0 = one-pass forward only; 1 = also allocate a K and a V plane per layer so
                                 that flame_gr_prefill and flame_gr_score can keep the history keys and
                                 values of every layer */
+  int32_t latency_mode;      /* 0 = kernels configured for throughput (batches that fill the chip);
+                                1 = the MFMA attention kernel in its latency configuration, for handles that
+                                serve one or a few requests per call: pairs of wavefronts split the keys of a
+                                query tile, which halves the chain of dependent key tiles that bounds a small
+                                batch's run time.  Partial sums are grouped differently: scores agree with
+                                mode 0 to rounding (same error bars), not bit for bit.  No effect on fp32 handles */
 } flame_gr_config;
 
 /* Model weights: device pointers, caller-owned, read-only, element type = config.dtype unless

@@ -387,7 +387,8 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   h->elt = cfg.dtype == FLAME_GR_BF16 ? 2 : 4;
   h->ws_rows = workspace_rows(cfg);
   h->sh = Shape{cfg.d_model, cfg.n_heads, cfg.d_model / cfg.n_heads, cfg.n_layers, cfg.n_buckets,
-                cfg.max_rel_dist, cfg.ln_eps, cfg.attn_scale, h->ws_rows, cfg.attn_kind == FLAME_GR_ATTN_SOFTMAX ? 1 : 0};
+                cfg.max_rel_dist, cfg.ln_eps, cfg.attn_scale, h->ws_rows, cfg.attn_kind == FLAME_GR_ATTN_SOFTMAX ? 1 : 0,
+                cfg.latency_mode ? 1 : 0};
   auto fail = [&](const std::string &m, int code) {
     g_create_error = m;
     free_all(h);

@@ -47,14 +47,10 @@ namespace flame {
 
 namespace {
 
-constexpr int QT = kAttnQTileBf16;  // query rows per workgroup
-constexpr int NW = QT / 32;         // wavefronts per workgroup, 32 query rows each
-static_assert(QT == 128, "4 wavefronts of 32 query rows");
-constexpr int KT = 64;              // keys per LDS stage
+constexpr int QT = kAttnQTileBf16;  // query rows per workgroup: four groups of 32 (one 32-row MFMA block each)
+static_assert(QT == 128, "4 groups of 32 query rows");
 constexpr int NSTAGE = 3;           // LDS stages (ring)
 constexpr int KH = 64;              // keys per half tile (one pass of the register-level loop)
-constexpr int BW = QT + KT;         // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u], u = 0..190
-static_assert(BW <= 64 * NW, "one 64-slot window request per wavefront");
 
 // SiLU for small arguments.  silu(x) - x/2 is even: silu(x) = x/2 + x^2 r(x^2) with
 // r(u) ~ a1 + a3 u + a5 u^2 (weighted least-squares fit of (silu(x) - x/2)/x^2 on [-2, 2], approximation
@@ -85,11 +81,23 @@ __device__ __forceinline__ f16x8 pack8(const float *v) {
 // in the accumulators is halved, so the exponent fed to the base-2 exponential is accumulator * tscale_h[head]
 // with tscale = 2 log2(e) / tau.  The 64 keys of a half tile of one query sit in two lanes (lane and lane ^ 32),
 // which exchange their maxima with one half-swap; their partial sums are only added at the end.
-template <int DH, bool SOFTMAX>
-__global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes, const float *__restrict__ bias_lh,
+//
+// KSPLIT = false is the throughput configuration described at the top: 4 wavefronts, key tiles of 64, three
+// workgroups per CU.  KSPLIT = true is the latency configuration for batches too small to fill the chip, where a
+// workgroup sits alone on its CU and its run time is the chain of key tiles of its longest row: 8 wavefronts, key
+// tiles of 128, and each group of 32 query rows is served by a PAIR of wavefronts that take one 64-key half of every
+// tile each (two wavefronts per SIMD, so one's MFMAs run under the other's VALU work) and add their partial outputs
+// through LDS at the end, in a fixed order.  The chain is half as many steps and the sums are grouped differently,
+// so the two configurations agree to rounding, not bit for bit.
+template <int DH, bool SOFTMAX, bool KSPLIT>
+__global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_kernel(PlanePtrs planes, const float *__restrict__ bias_lh,
                                                            const float *__restrict__ tscale_h,
                                                            half_t *__restrict__ O, const AttnItem *__restrict__ items,
                                                            int H, int d, int D, int64_t ws_rows) {
+  constexpr int NW = KSPLIT ? 8 : 4;   // wavefronts per workgroup
+  constexpr int KT = KSPLIT ? 128 : 64;   // keys per LDS stage
+  constexpr int BW = QT + KT;          // bias window per key tile: slot u holds bias[q_first + QT-1 - k0 - u]
+  static_assert(BW <= 64 * NW, "one 64-slot window request per wavefront");
   constexpr int KS = DH / 16;          // k-steps of the Q K^T product
   constexpr int DB = DH / 32;          // 32-row blocks of O^T
   constexpr int KCH = DH / 8;          // 16-byte chunks per K row (8 or 4)
@@ -102,8 +110,11 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes,
   constexpr int STAGE = K_BYTES + V_BYTES + W_BYTES;
   static_assert(K_BYTES % 1024 == 0 && V_BYTES % 1024 == 0 && STAGE % 256 == 0, "stage parts start on 256-byte boundaries");
   static_assert(QT * DH * 2 <= NSTAGE * STAGE, "output patches fit in the tile buffers");
-  // the stages; the output patches of the wavefronts reuse them once the key loop is over
-  __shared__ __attribute__((aligned(256))) char lds[NSTAGE * STAGE];
+  // the stages; the output patches of the wavefronts reuse them once the key loop is over.  The latency
+  // configuration needs more than the 64 KB a static array may have and takes its stages from dynamic LDS.
+  extern __shared__ __attribute__((aligned(256))) char lds_dynamic[];
+  __shared__ __attribute__((aligned(256))) char lds_static[KSPLIT ? 256 : NSTAGE * STAGE];
+  char *const lds = KSPLIT ? lds_dynamic : lds_static;
 
   const int head = blockIdx.x % H;
   const AttnItem it = items[blockIdx.x / H];
@@ -117,8 +128,10 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes,
   const half_t *Kp = (const half_t *)planes.k + head * DH;
   const float *bias = bias_lh + (int64_t)head * D;
 
-  // this wavefront's 32 query rows
-  const int q_local0 = wave * 32;
+  // this wavefront's 32 query rows and (latency configuration) its half of every key tile
+  const int q_group = KSPLIT ? wave >> 1 : wave;
+  const int k_half = KSPLIT ? wave & 1 : 0;
+  const int q_local0 = q_group * 32;
   const bool wave_active = q_local0 < it.n_q;
   const int my_q_local = q_local0 + l32;
   const bool row_valid = my_q_local < it.n_q;
@@ -232,7 +245,7 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes,
     st = st + 1 >= NSTAGE ? 0 : st + 1;
     __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
 #pragma unroll 1
-    for (int u = 0; u < KT / KH; ++u) {
+    for (int u = KSPLIT ? k_half : 0; u < (KSPLIT ? k_half + 1 : KT / KH); ++u) {
     const int k0 = t * KT + u * KH;
     if (wave_active && k0 < wave_vis_max) {
       const char *kb = sb + u * (KH * DH * 2);                 // K rows of this half tile
@@ -399,6 +412,43 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes,
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated requests of the tail have landed
   __builtin_amdgcn_s_barrier();          // everybody has left the last tile: the stages become output patches
 
+  // ---- latency configuration: the wavefront with the second key half hands its partial output (and its softmax
+  // state) to its partner through LDS, behind the output patches; the partner goes on alone.
+  if constexpr (KSPLIT) {
+    constexpr int PART = DB * 16 * 64 * 4;            // bytes of one wavefront's accumulators
+    char *area = lds + 4 * (32 * DH * 2) + q_group * (PART + 512);
+    if (k_half == 1) {
+#pragma unroll
+      for (int b = 0; b < DB; ++b)
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+          const f32x4 v = {oacc[b][4 * g], oacc[b][4 * g + 1], oacc[b][4 * g + 2], oacc[b][4 * g + 3]};
+          *(f32x4 *)(area + ((b * 4 + g) * 64 + lane) * 16) = v;
+        }
+      if constexpr (SOFTMAX) *(float2 *)(area + PART + lane * 8) = float2{m_run, l_run};
+    }
+    __builtin_amdgcn_s_barrier();
+    if (k_half == 1) return;
+    float s_mine = 1.f, s_other = 1.f;
+    if constexpr (SOFTMAX) {
+      const float2 ml = *(const float2 *)(area + PART + lane * 8);
+      const float m_new = fmaxf(m_run, ml.x);
+      s_mine = __builtin_amdgcn_exp2f(m_run - m_new);
+      s_other = __builtin_amdgcn_exp2f(ml.x - m_new);
+      l_run = l_run * s_mine + ml.y * s_other;
+      m_run = m_new;
+    }
+#pragma unroll
+    for (int b = 0; b < DB; ++b)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        const f32x4 v = *(const f32x4 *)(area + ((b * 4 + g) * 64 + lane) * 16);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+          oacc[b][4 * g + i] = SOFTMAX ? oacc[b][4 * g + i] * s_mine + v[i] * s_other : oacc[b][4 * g + i] + v[i];
+      }
+  }
+
   // ---- candidates: the row itself is one more key, at distance 0.  The wavefront multiplies its 32
   // candidate rows against themselves and keeps the diagonal.
   if (it.is_cand && wave_active) {
@@ -470,7 +520,7 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes,
   {
     constexpr int CPR = DH / 8;                       // 16-byte chunks per patch row
     constexpr int RPI = 64 / CPR;                     // patch rows per store instruction
-    char *pb = lds + wave * (32 * DH * 2);
+    char *pb = lds + q_group * (32 * DH * 2);
     auto pkey = [](int row) { return CPR == 8 ? (row >> 1) & 7 : (row >> 2) & 3; };   // spreads 16 rows over 256 bytes
 #pragma unroll
     for (int b = 0; b < DB; ++b)
@@ -495,11 +545,32 @@ __global__ __launch_bounds__(64 * NW, 3) void attn_mfma_kernel(PlanePtrs planes,
 
 }  // namespace
 
+// The latency configuration needs its LDS limit raised once per kernel instance (a function attribute, no allocation).
+template <int DH, bool SM>
+static void launch_key_split(int grid, PlanePtrs planes, const float *bias_lh, const float *tscale_h, half_t *O,
+                             const AttnItem *items, const Shape &sh, hipStream_t s) {
+  constexpr int lds_bytes = NSTAGE * (2 * 128 * DH * 2 + 8 * 256);
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<DH, SM, true>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
+  (void)attr;
+  attn_mfma_kernel<DH, SM, true><<<grid, 512, lds_bytes, s>>>(planes, bias_lh, tscale_h, O, items, sh.H, sh.d, sh.D, sh.ws_rows);
+}
+
 void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
                       int n_items, const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   const int grid = n_items * sh.H;
-#define ATTN_CASE(DHV, SM) attn_mfma_kernel<DHV, SM><<<grid, 64 * NW, 0, s>>>(planes, bias_lh, tscale_h, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
+  if (sh.key_split) {
+    if (sh.softmax) {
+      if (sh.dh == 32) launch_key_split<32, true>(grid, planes, bias_lh, tscale_h, (half_t *)O, items, sh, s);
+      else launch_key_split<64, true>(grid, planes, bias_lh, tscale_h, (half_t *)O, items, sh, s);
+    } else {
+      if (sh.dh == 32) launch_key_split<32, false>(grid, planes, bias_lh, tscale_h, (half_t *)O, items, sh, s);
+      else launch_key_split<64, false>(grid, planes, bias_lh, tscale_h, (half_t *)O, items, sh, s);
+    }
+    return;
+  }
+#define ATTN_CASE(DHV, SM) attn_mfma_kernel<DHV, SM, false><<<grid, 256, 0, s>>>(planes, bias_lh, tscale_h, (half_t *)O, items, sh.H, sh.d, sh.D, sh.ws_rows)
   if (sh.softmax) {
     if (sh.dh == 32) ATTN_CASE(32, true);
     else ATTN_CASE(64, true);
