@@ -39,16 +39,26 @@ __global__ __launch_bounds__(256) void pack_w2_kernel(const bf16_t *__restrict__
   }
 }
 
-// NBW: 32-feature blocks per wavefront (d = 128 * NBW)
-template <int NBW>
-__global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restrict__ O, const half_t *__restrict__ U,
+// NWV wavefronts per workgroup, NBW 32-feature blocks per wavefront: d = 32 * NBW * NWV (four wavefronts for
+// d = 128, 256, 512; three for d = 96, 192, 384).  The 64 rows of the block are dealt out RPW per wavefront in
+// phase 1 (with three wavefronts the last one has rows to spare, which it skips).
+template <int NWV, int NBW>
+__global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__restrict__ O, const half_t *__restrict__ U,
                                                           const bf16_t *__restrict__ gamma, const bf16_t *__restrict__ beta,
                                                           const half_t *__restrict__ W2p, const bf16_t *__restrict__ b2,
                                                           float *__restrict__ X, half_t *__restrict__ Xh,
                                                           const RowBlock *__restrict__ blocks, const int32_t *__restrict__ blk_list,
                                                           int blk_first, float eps) {
-  constexpr int d = 128 * NBW;
+  constexpr int d = 32 * NBW * NWV;
+  constexpr int RB4 = 4;                         // rows per batch of phase 1
+  constexpr int RPW = (kRowAlign + NWV * RB4 - 1) / (NWV * RB4) * RB4;   // rows per wavefront in phase 1 (16, or 24 of which 64 exist)
+  constexpr bool EVEN = RPW * NWV == kRowAlign;
   constexpr int NCHUNK = d / 8;                  // 16-byte chunks per row
+  // Swizzle key of the gated rows in LDS.  A row of d fp16 is NCHUNK chunks; the MFMA operand reads take one chunk
+  // column of 16 consecutive rows.  With NCHUNK a multiple of 16 the row pitch is a multiple of 256 bytes and the
+  // low four row bits spread those reads over the 16 slots; with NCHUNK = 24 (d = 192, pitch 384 bytes: odd and
+  // even rows already sit 128 bytes apart) three bits of row / 2 do, and the XOR stays inside a group of 8 chunks.
+  auto gkey = [](int r) { return NCHUNK % 16 == 0 ? r & 15 : (r >> 1) & 7; };
   constexpr int CPL = (NCHUNK + 63) / 64;        // chunks per lane in phase 1
   extern __shared__ __attribute__((aligned(16))) char smem[];   // sG: 64 rows x d fp16, swizzled
 
@@ -73,7 +83,6 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
   // Rows are taken four at a time, and the loads of the next four are issued before the current
   // four are normalised: with one row in flight per wavefront the kernel would run at the latency,
   // not the bandwidth, of HBM.
-  constexpr int RB4 = 4;
   f16x8 ov[2][RB4][CPL], uv[2][RB4][CPL];
   auto issue = [&](int set, int batch) {
 #pragma unroll
@@ -82,7 +91,8 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
       for (int c = 0; c < CPL; ++c) {
         const int ch = lane + 64 * c;
         if (ch < NCHUNK) {
-          const int64_t off = (row0 + wave * 16 + batch * RB4 + q) * d + ch * 8;
+          const int rr = wave * RPW + batch * RB4 + q;
+          const int64_t off = (row0 + (EVEN || rr < kRowAlign ? rr : kRowAlign - 1)) * d + ch * 8;
           ov[set][q][c] = *(const f16x8 *)(O + off);
           uv[set][q][c] = *(const f16x8 *)(U + off);
         }
@@ -90,9 +100,9 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
   };
   issue(0, 0);
 #pragma unroll
-  for (int batch = 0; batch < 16 / RB4; ++batch) {
+  for (int batch = 0; batch < RPW / RB4; ++batch) {
     const int set = batch & 1;
-    if (batch + 1 < 16 / RB4) issue(set ^ 1, batch + 1);
+    if (batch + 1 < RPW / RB4) issue(set ^ 1, batch + 1);
     __builtin_amdgcn_sched_barrier(0);
     // the four rows go through each step together, so that their reduction chains overlap
     float v[RB4][CPL][8], mu[RB4], rstd[RB4];
@@ -125,7 +135,8 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
     for (int q = 0; q < RB4; ++q) rstd[q] = rsqrtf(wave_sum(rstd[q]) * (1.0f / d) + eps);
 #pragma unroll
     for (int q = 0; q < RB4; ++q) {
-      const int r = wave * 16 + batch * RB4 + q;
+      const int r = wave * RPW + batch * RB4 + q;
+      if (!EVEN && r >= kRowAlign) continue;       // a spare row of the last wavefront
       const bool pad = r >= n_valid;               // padding rows carry a zero branch so that they stay finite
 #pragma unroll
       for (int c = 0; c < CPL; ++c) {
@@ -135,7 +146,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
           for (int k = 0; k < 8; ++k)
             o[k] = pad ? (half_t)0.f : to_f16_sat(((v[q][c][k] - mu[q]) * rstd[q] * g[c][k] + bt[c][k]) * (float)uv[set][q][c][k]);
-          *(f16x8 *)(smem + r * (d * 2) + ((ch ^ (r & 15)) << 4)) = o;
+          *(f16x8 *)(smem + r * (d * 2) + ((ch ^ gkey(r)) << 4)) = o;
         }
       }
     }
@@ -166,7 +177,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int r = 32 * i + l32;
-    fa[0][i] = *(const f16x8 *)(smem + r * (d * 2) + ((lhalf ^ (r & 15)) << 4));
+    fa[0][i] = *(const f16x8 *)(smem + r * (d * 2) + ((lhalf ^ gkey(r)) << 4));
   }
   __builtin_amdgcn_sched_barrier(0);
   for (int ks0 = 0; ks0 < NKS; ks0 += PD) {
@@ -181,7 +192,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int r = 32 * i + l32;
-        fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ (r & 15)) << 4));
+        fa[nxt][i] = *(const f16x8 *)(smem + r * (d * 2) + (((2 * kn + lhalf) ^ gkey(r)) << 4));
       }
       __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
@@ -250,7 +261,7 @@ __global__ __launch_bounds__(256, 2) void k3_fused_kernel(const half_t *__restri
 
 }  // namespace
 
-bool k3_fused_supported(int d) { return d == 128 || d == 256 || d == 512; }
+bool k3_fused_supported(int d) { return d == 128 || d == 192 || d == 256 || d == 384 || d == 512; }
 
 void launch_pack_w2(const void *W2, void *W2p, int d, int n_layers, hipStream_t s) {
   const int64_t total = (int64_t)d * d / 8 * n_layers;
@@ -263,11 +274,13 @@ void launch_k3_fused(const void *O, const void *U, const void *gamma, const void
                      const Shape &sh, hipStream_t s) {
   if (n_blk <= 0) return;
   const size_t lds = (size_t)kRowAlign * sh.d * 2;
-#define K3_CASE(NB) k3_fused_kernel<NB><<<n_blk, 256, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
+#define K3_CASE(NWV, NB) k3_fused_kernel<NWV, NB><<<n_blk, 64 * NWV, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
     (const half_t *)W2p_layer, (const bf16_t *)b2, X, (half_t *)Xh, blocks, blk_list, blk_first, sh.eps)
-  if (sh.d == 512) K3_CASE(4);
-  else if (sh.d == 256) K3_CASE(2);
-  else K3_CASE(1);
+  if (sh.d == 512) K3_CASE(4, 4);
+  else if (sh.d == 384) K3_CASE(3, 4);
+  else if (sh.d == 256) K3_CASE(4, 2);
+  else if (sh.d == 192) K3_CASE(3, 2);
+  else K3_CASE(4, 1);
 #undef K3_CASE
 }
 

@@ -76,7 +76,7 @@ void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
 // K3 fused (k3_mfma.hip): LayerNorm * U gate + output projection + residual in one kernel, for
-// d in {128, 256, 512}; W2p is the fragment-major packed fp16 copy of W2 written by launch_pack_w2.
+// d in {128, 192, 256, 384, 512}; W2p is the fragment-major packed fp16 copy of W2 written by launch_pack_w2.
 bool k3_fused_supported(int d);
 void launch_pack_w2(const void *W2, void *W2p, int d, int n_layers, hipStream_t s);
 void launch_k3_fused(const void *O, const void *U, const void *gamma, const void *beta, const void *W2p_layer, const void *b2,

@@ -95,11 +95,13 @@ STRESS = {
     "S3": dict(L=[700], M=[130], d=128, H=2, nb=16, D=1024),
     # several ragged requests around the tile sizes
     "S4": dict(L=[65, 127, 129, 3, 257, 300], M=[1, 63, 65, 200, 255, 257], d=128, H=2, nb=32, D=128),
-    # d not a multiple of 128 (64-wide GEMM tiles, unfused LN-gate + output projection) with head width 64,
+    # d not a multiple of 128 (64-wide GEMM tiles, three-wavefront instance of the fused K3) with head width 64,
     # and an attention scale that is no power of two
     "S5": dict(L=[200, 77, 0], M=[33, 100, 9], d=192, H=3, nb=32, D=256, attn_scale=0.3),
     # head width 32 on the 128-wide GEMM tiles and the fused K3 (d = 256, 8 heads), three layers
     "S6": dict(L=[150, 64], M=[70, 128], d=256, H=8, nb=16, D=256, layers=3, attn_scale=0.75),
+    # d = 384: 128-wide GEMM tiles with the three-wavefront instance of the fused K3
+    "S7": dict(L=[90, 200], M=[65, 10], d=384, H=6, nb=16, D=256),
 }
 
 

@@ -51,7 +51,7 @@ def gpu_out(B, wl, hidden=False, **cfg_kw):
         B.flame_gr_destroy(h)
 
 
-@pytest.mark.parametrize("case", ["S1", "S2", "S3", "S4", "S5", "S6"])
+@pytest.mark.parametrize("case", list(STRESS))
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_softmax_scores_and_hidden_rows(B, case, dtype):
     wl = soft(dtype=dtype, name=case, **STRESS[case])
