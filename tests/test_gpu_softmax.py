@@ -160,3 +160,18 @@ def test_softmax_needs_temperatures(B):
     with pytest.raises(B.FlameGRError) as e:
         B.flame_gr_create(cfg)
     assert e.value.code == -1
+
+
+def test_softmax_production_size(B):
+    """The production shape (128 requests, 16 layers, d = 512) with softmax attention, on sampled requests whose
+    oracle scores are stored fixtures (tests/oracle_cache.py writes them, from the oracle alone)."""
+    from tests.oracle_cache import request_scores, sample_requests
+    wl = W.make_workload("production_softmax")
+    g = gpu_out(B, wl)
+    assert np.isfinite(g).all()
+    co = wl.cand_offsets
+    worst = 0.0
+    for i in sample_requests(wl, "production_softmax"):
+        worst = max(worst, score_err(g[co[i]:co[i + 1]], request_scores(wl, i)))
+    print(f"production, softmax attention: max score error {worst:.3e}")
+    assert worst <= TOL_HOT["bf16"]
