@@ -421,6 +421,7 @@ def main():
         out["request_latency"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=1, latency_mode=1)
         out["p50_request_latency_ms"] = out["request_latency"]["p50_ms"]
         out["request_latency_throughput_configuration"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=1)
+        out["request_latency_4_executors"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=4)
         out["request_latency_8_executors"] = request_mode_latency(B, wl, dw, hist, cand, concurrency=8)
     if two_stage is not None:
         out["two_stage"] = two_stage
