@@ -560,7 +560,7 @@ void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscal
                       int n_items, const Shape &sh, hipStream_t s) {
   if (n_items <= 0) return;
   const int grid = n_items * sh.H;
-  if (sh.key_split) {
+  if (sh.latency) {
     if (sh.softmax) {
       if (sh.dh == 32) launch_key_split<32, true>(grid, planes, bias_lh, tscale_h, (half_t *)O, items, sh, s);
       else launch_key_split<64, true>(grid, planes, bias_lh, tscale_h, (half_t *)O, items, sh, s);

@@ -13,7 +13,7 @@ struct Shape {
   float eps, alpha;
   int64_t ws_rows;  // rows of every workspace matrix (plane stride = ws_rows * d)
   int softmax;      // attention weights: 0 = pointwise SiLU, 1 = softmax with a temperature per layer and head
-  int key_split;    // MFMA attention: 0 = throughput configuration, 1 = latency configuration (pairs of wavefronts split the keys)
+  int latency;      // MFMA attention: 0 = throughput configuration, 1 = latency configuration (pairs of wavefronts split the keys)
 };
 
 // ---- shared small kernels (misc.hip) --------------------------------------------------------
