@@ -42,7 +42,11 @@ __global__ __launch_bounds__(256) void pack_w2_kernel(const bf16_t *__restrict__
 // NWV wavefronts per workgroup, NBW 32-feature blocks per wavefront: d = 32 * NBW * NWV (four wavefronts for
 // d = 128, 256, 512; three for d = 96, 192, 384).  The 64 rows of the block are dealt out RPW per wavefront in
 // phase 1 (with three wavefronts the last one has rows to spare, which it skips).
-template <int NWV, int NBW>
+// CS workgroups share a row block (blockIdx.y): each repeats phase 1 and takes 1/CS of every wavefront's feature
+// blocks through phases 2 and 3.  CS = 2 is for launches with few row blocks, where a workgroup sits alone on its
+// CU and its run time, not the chip's bandwidth, is what counts; every output element is computed exactly as with
+// CS = 1.
+template <int NWV, int NBW, int CS>
 __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__restrict__ O, const half_t *__restrict__ U,
                                                           const bf16_t *__restrict__ gamma, const bf16_t *__restrict__ beta,
                                                           const half_t *__restrict__ W2p, const bf16_t *__restrict__ b2,
@@ -155,11 +159,14 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
   __syncthreads();
 
   // ---- phase 2: acc[token][feature] over k; features of this wavefront: wave*32*NBW .. +32*NBW-1
-  f32x16 acc[2][NBW];
+  static_assert(NBW % CS == 0, "feature blocks of a wavefront divide among the workgroups of a row block");
+  constexpr int NB2 = NBW / CS;                  // feature blocks per wavefront in this workgroup
+  const int fb0 = wave * NBW + (CS > 1 ? (int)blockIdx.y * NB2 : 0);   // first of them
+  f32x16 acc[2][NB2];
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int j = 0; j < NBW; ++j)
+    for (int j = 0; j < NB2; ++j)
 #pragma unroll
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
   constexpr int NKS = d / 16;
@@ -168,12 +175,12 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
   // back to their first use); the activations come from LDS, one step ahead.
   constexpr int PD = 4;
   static_assert(NKS % PD == 0, "k-steps are walked in groups of the ring depth");
-  const half_t *wp = W2p + ((int64_t)(wave * NBW) * 64 + lane) * 8;      // + (ks * (d/32) + j) * 512
-  f16x8 fw[PD][NBW], fa[2][2];
+  const half_t *wp = W2p + ((int64_t)fb0 * 64 + lane) * 8;      // + (ks * (d/32) + j) * 512
+  f16x8 fw[PD][NB2], fa[2][2];
 #pragma unroll
   for (int p = 0; p < PD - 1; ++p)
 #pragma unroll
-    for (int j = 0; j < NBW; ++j) fw[p][j] = *(const f16x8 *)(wp + ((int64_t)p * (d / 32) + j) * 512);
+    for (int j = 0; j < NB2; ++j) fw[p][j] = *(const f16x8 *)(wp + ((int64_t)p * (d / 32) + j) * 512);
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
     const int r = 32 * i + l32;
@@ -188,7 +195,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
       const int kw = ks + PD - 1 < NKS ? ks + PD - 1 : NKS - 1;
       const int kn = ks + 1 < NKS ? ks + 1 : ks;
 #pragma unroll
-      for (int j = 0; j < NBW; ++j) fw[(u + PD - 1) % PD][j] = *(const f16x8 *)(wp + ((int64_t)kw * (d / 32) + j) * 512);
+      for (int j = 0; j < NB2; ++j) fw[(u + PD - 1) % PD][j] = *(const f16x8 *)(wp + ((int64_t)kw * (d / 32) + j) * 512);
 #pragma unroll
       for (int i = 0; i < 2; ++i) {
         const int r = 32 * i + l32;
@@ -198,7 +205,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int j = 0; j < NBW; ++j)
+        for (int j = 0; j < NB2; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fw[u][j], fa[cur][i], acc[i][j], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
     }
@@ -210,7 +217,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
   // private slice of the now free LDS (16-byte chunks XOR-swizzled by row) and then walks it row by
   // row: 16 bytes per lane, whole lines of X, 64-byte runs of the blocked fp16 copy.
   __syncthreads();                                  // every wavefront has finished reading G
-  constexpr int WF = 32 * NBW;                      // features per wavefront
+  constexpr int WF = 32 * NB2;                      // features per wavefront (in this workgroup)
   constexpr int CPR = WF / 4;                       // 16-byte fp32 chunks per patch row
   constexpr int RPI = 64 / CPR;                     // patch rows per instruction
   constexpr int NIT = 32 / RPI;
@@ -218,7 +225,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
   // chunk XOR key: 16 consecutive rows of one chunk column use each of the 16 slots of 256 bytes once
   auto pkey = [](int row) { return CPR == 8 ? (row >> 1) & 7 : row & 15; };
   const int rl = lane / CPR, cc = lane % CPR;
-  const int n = wave * WF + 4 * cc;                 // this lane's 4 features in the read-out
+  const int n = fb0 * 32 + 4 * cc;                  // this lane's 4 features in the read-out
   f32x4 bvf;
   {
     const bf16x4 bv = *(const bf16x4 *)(b2 + n);
@@ -233,7 +240,7 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
 #pragma unroll
     for (int t = 0; t < XB; ++t) xr[t] = *(const f32x4 *)(xrow + (int64_t)t * RPI * d);
 #pragma unroll
-    for (int j = 0; j < NBW; ++j)
+    for (int j = 0; j < NB2; ++j)
 #pragma unroll
       for (int gq = 0; gq < 4; ++gq) {
         const int c = 8 * j + 2 * gq + lhalf;
@@ -274,13 +281,15 @@ void launch_k3_fused(const void *O, const void *U, const void *gamma, const void
                      const Shape &sh, hipStream_t s) {
   if (n_blk <= 0) return;
   const size_t lds = (size_t)kRowAlign * sh.d * 2;
-#define K3_CASE(NWV, NB) k3_fused_kernel<NWV, NB><<<n_blk, 64 * NWV, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
+  // few row blocks: two workgroups per block (see the kernel), as long as the launch still fits the chip once over
+  const bool split = n_blk <= 128;
+#define K3_CASE(NWV, NB, CSV) k3_fused_kernel<NWV, NB, CSV><<<dim3(n_blk, CSV), 64 * NWV, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
     (const half_t *)W2p_layer, (const bf16_t *)b2, X, (half_t *)Xh, blocks, blk_list, blk_first, sh.eps)
-  if (sh.d == 512) K3_CASE(4, 4);
-  else if (sh.d == 384) K3_CASE(3, 4);
-  else if (sh.d == 256) K3_CASE(4, 2);
-  else if (sh.d == 192) K3_CASE(3, 2);
-  else K3_CASE(4, 1);
+  if (sh.d == 512) { if (split) K3_CASE(4, 4, 2); else K3_CASE(4, 4, 1); }
+  else if (sh.d == 384) { if (split) K3_CASE(3, 4, 2); else K3_CASE(3, 4, 1); }
+  else if (sh.d == 256) { if (split) K3_CASE(4, 2, 2); else K3_CASE(4, 2, 1); }
+  else if (sh.d == 192) { if (split) K3_CASE(3, 2, 2); else K3_CASE(3, 2, 1); }
+  else K3_CASE(4, 1, 1);
 #undef K3_CASE
 }
 
