@@ -285,8 +285,9 @@ void launch_k3_fused(const void *O, const void *U, const void *gamma, const void
   const bool split = n_blk <= 128;
 #define K3_CASE(NWV, NB, CSV) k3_fused_kernel<NWV, NB, CSV><<<dim3(n_blk, CSV), 64 * NWV, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
     (const half_t *)W2p_layer, (const bf16_t *)b2, X, (half_t *)Xh, blocks, blk_list, blk_first, sh.eps)
-  if (sh.d == 512) { if (split) K3_CASE(4, 4, 2); else K3_CASE(4, 4, 1); }
-  else if (sh.d == 384) { if (split) K3_CASE(3, 4, 2); else K3_CASE(3, 4, 1); }
+  const bool split4 = n_blk <= 64;
+  if (sh.d == 512) { if (split4) K3_CASE(4, 4, 4); else if (split) K3_CASE(4, 4, 2); else K3_CASE(4, 4, 1); }
+  else if (sh.d == 384) { if (split4) K3_CASE(3, 4, 4); else if (split) K3_CASE(3, 4, 2); else K3_CASE(3, 4, 1); }
   else if (sh.d == 256) { if (split) K3_CASE(4, 2, 2); else K3_CASE(4, 2, 1); }
   else if (sh.d == 192) { if (split) K3_CASE(3, 2, 2); else K3_CASE(3, 2, 1); }
   else K3_CASE(4, 1, 1);
