@@ -402,6 +402,7 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
     if (e_ != hipSuccess) return fail(std::string(#expr) + ": " + hipGetErrorString(e_), FLAME_GR_HIP_ERROR); \
   } while (0)
   CR(hipGetDevice(&h->device));
+  if (h->sh.latency && cfg.dtype == FLAME_GR_BF16) CR(attn_latency_setup(h->sh));
   const size_t rows = (size_t)h->ws_rows, d = (size_t)cfg.d_model, e = h->elt;
   CR(hipMalloc(&h->X, rows * d * sizeof(float)));
   h->plane_bytes = rows * d * e;

@@ -545,15 +545,28 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
 
 }  // namespace
 
-// The latency configuration needs its LDS limit raised once per kernel instance (a function attribute, no allocation).
+// The latency configuration needs its LDS limit raised once per kernel instance (a function attribute, no
+// allocation); handles in latency mode do it when they are created, outside any stream capture.
+template <int DH>
+constexpr int key_split_lds_bytes() { return NSTAGE * (2 * 128 * DH * 2 + 8 * 256); }
+
+template <int DH, bool SM>
+static hipError_t key_split_setup() {
+  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<DH, SM, true>),
+                                                     hipFuncAttributeMaxDynamicSharedMemorySize, key_split_lds_bytes<DH>());
+  return attr;
+}
+
 template <int DH, bool SM>
 static void launch_key_split(int grid, PlanePtrs planes, const float *bias_lh, const float *tscale_h, half_t *O,
                              const AttnItem *items, const Shape &sh, hipStream_t s) {
-  constexpr int lds_bytes = NSTAGE * (2 * 128 * DH * 2 + 8 * 256);
-  static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void *>(&attn_mfma_kernel<DH, SM, true>),
-                                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
-  (void)attr;
-  attn_mfma_kernel<DH, SM, true><<<grid, 512, lds_bytes, s>>>(planes, bias_lh, tscale_h, O, items, sh.H, sh.d, sh.D, sh.ws_rows);
+  (void)key_split_setup<DH, SM>();
+  attn_mfma_kernel<DH, SM, true><<<grid, 512, key_split_lds_bytes<DH>(), s>>>(planes, bias_lh, tscale_h, O, items, sh.H, sh.d, sh.D, sh.ws_rows);
+}
+
+hipError_t attn_latency_setup(const Shape &sh) {
+  if (sh.softmax) return sh.dh == 32 ? key_split_setup<32, true>() : key_split_setup<64, true>();
+  return sh.dh == 32 ? key_split_setup<32, false>() : key_split_setup<64, false>();
 }
 
 void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,

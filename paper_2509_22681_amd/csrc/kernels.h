@@ -71,6 +71,8 @@ void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, PlanePtrs
 // tscale_h (softmax only): 2 log2(e) / tau per head (the kernel holds halved logits and uses the base-2 exponential).
 void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscale_h, void *O, const AttnItem *items,
                       int n_items, const Shape &sh, hipStream_t s);
+// Prepares the latency configuration of the attention kernel for this shape (raises its LDS limit); once per handle.
+hipError_t attn_latency_setup(const Shape &sh);
 // X[row] += G W2h^T + b2, and Xh[row] = fp16(X[row])
 void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);

@@ -68,3 +68,23 @@ def test_latency_mode_is_ignored_by_fp32_handles(B):
     with pytest.raises(B.FlameGRError) as e:
         B.flame_gr_create(cfg)
     assert e.value.code == -1
+
+
+def test_latency_mode_graph_replay(B):
+    """A handle in latency mode can be captured right after its creation (its kernels' launch attributes are set
+    at create, not inside the capture) and replays what its eager forward computes."""
+    import torch
+    wl = stress(dtype="bf16", name="S6", hot=True, **STRESS["S6"])
+    want = gpu_out(B, wl, latency_mode=1)
+    h = B.flame_gr_create(B.config_for(wl, latency_mode=1))
+    try:
+        dw, hist, cand = B.to_device(wl)
+        out = torch.zeros(int(wl.cand_offsets[-1]), device="cuda:0")
+        B.flame_gr_capture(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, out)
+        for _ in range(2):
+            out.zero_()
+            B.flame_gr_replay(h)
+            torch.cuda.synchronize()
+            assert np.array_equal(out.cpu().numpy(), want)
+    finally:
+        B.flame_gr_destroy(h)
