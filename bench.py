@@ -196,7 +196,7 @@ def mixed_traffic_leg(B, wl, dw, n_requests=320, n_executors=4, hist_len=1024,
 def climber_leg(B, steps=10, n_users=64, d=192, H=3, layers=12, n_blocks=2, E=256, T=2):
     """The paper's own model in the reading of include/flame_climber.h, at the two scenarios of its Table 2
     (base: sequence 512 + 128 candidates; long: 1024 + 512; 2 blocks x 12 layers): softmax attention with
-    temperature, each block stack on its own handle and stream, then gating fusion and task head.  d = 192 puts
+    temperature, each block stack on its own handle, then gating fusion and task head.  d = 192 puts
     the block stacks' flops per request at 4.6e9 (base) and 1.63e10 (long) against the paper's 3.72e9 and 1.64e10.
     Reports batched throughput (n_users requests per pass), single-request latency, and the deviation of one
     request from the fp64 oracle."""
@@ -235,13 +235,21 @@ def climber_leg(B, steps=10, n_users=64, d=192, H=3, layers=12, n_blocks=2, E=25
                 probs = torch.zeros((n, T), device="cuda:0", dtype=torch.float32)
                 main = torch.cuda.current_stream()
 
+                # a pass of many users fills the chip block by block: one stream (two streams are faster only when the
+                # runtime happens to put them on different hardware queues); a single request does not fill it, and
+                # its block stacks run side by side on two streams
+                side = users == 1
+
                 def one_pass():
                     for b in range(n_blocks):
-                        streams[b].wait_stream(main)
+                        if side:
+                            streams[b].wait_stream(main)
                         ws, _, dh, ho, dc = args[b]
-                        B.flame_gr_forward_hidden(handles[b], ws, dh, ho, dc, sub.cand_offsets, hidden[b], stream=streams[b])
-                    for b in range(n_blocks):
-                        main.wait_stream(streams[b])
+                        B.flame_gr_forward_hidden(handles[b], ws, dh, ho, dc, sub.cand_offsets, hidden[b],
+                                                  stream=streams[b] if side else main)
+                    if side:
+                        for b in range(n_blocks):
+                            main.wait_stream(streams[b])
                     B.flame_climber_head(head_dev, hidden, fused, probs)
 
                 for _ in range(3):
