@@ -290,18 +290,24 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
         f16x8 fp[4];
         bool fast = SOFTMAX;
         if constexpr (SOFTMAX) {
-          // maximum of the raw (halved) logits first: the temperature scale is positive, so it commutes with the max
-          float mt = kNeg;
+          // maximum of the raw (halved) logits first: the temperature scale is positive, so it commutes with the max.
+          // Maxima and sums are taken in four independent chains (the 32 values of a lane would otherwise form one
+          // chain of dependent instructions).
+          if (need_mask) {
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              if (need_mask) {
+              for (int e = 0; e < 16; ++e) {
                 const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
                 sacc[j][e] = kv < n_vis ? sacc[j][e] : kNeg;
               }
-              mt = fmaxf(mt, sacc[j][e]);
-            }
+          }
+          float mx[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) mx[c] = fmaxf(sacc[0][c], sacc[1][c]);
+#pragma unroll
+          for (int e = 4; e < 16; ++e) mx[e & 3] = fmaxf(mx[e & 3], fmaxf(sacc[0][e], sacc[1][e]));
+          const float mt = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
           const float m_new = fmaxf(m_run, pair_max(mt) * ts);
           // the accumulators are rescaled only when some row of the wavefront has a new maximum (rare after the
           // first tiles); the branch is uniform over the wavefront
@@ -315,18 +321,18 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
             m_run = m_new;
           }
           const float nm = -m_new;
-          float ps = 0.f;
+          float psum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
           for (int j = 0; j < 2; ++j) {
             float w[16];
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-              w[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j][e], ts, nm));
-              ps += w[e];
-            }
+            for (int e = 0; e < 16; ++e) w[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j][e], ts, nm));
+#pragma unroll
+            for (int e = 0; e < 16; ++e) psum[e & 3] += w[e];
             fp[2 * j] = pack8(w);
             fp[2 * j + 1] = pack8(w + 8);
           }
+          const float ps = (psum[0] + psum[1]) + (psum[2] + psum[3]);
           l_run += ps;
         } else {
           f16x2 th[2][8];
