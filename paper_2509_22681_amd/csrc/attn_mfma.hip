@@ -343,11 +343,13 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
               const f16x2 yh = f16x2{(half_t)sacc[j][2 * i], (half_t)sacc[j][2 * i + 1]};
               th[j][i] = yh * yh;
             }
-          f16x2 m = th[0][0];
+          // maximum as a tree: four independent chains, then two levels
+          f16x2 mq[4];
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+          for (int c = 0; c < 4; ++c) mq[c] = __builtin_elementwise_max(th[0][c], th[1][c]);
 #pragma unroll
-            for (int i = 0; i < 8; ++i) m = __builtin_elementwise_max(m, th[j][i]);
+          for (int i = 4; i < 8; ++i) mq[i & 3] = __builtin_elementwise_max(mq[i & 3], __builtin_elementwise_max(th[0][i], th[1][i]));
+          const f16x2 m = __builtin_elementwise_max(__builtin_elementwise_max(mq[0], mq[1]), __builtin_elementwise_max(mq[2], mq[3]));
           const bool bad = !((float)m[0] <= kPolyT2 && (float)m[1] <= kPolyT2);     // NaN counts as bad
           fast = __builtin_amdgcn_ballot_w64(bad) == 0;
           if (fast) {
