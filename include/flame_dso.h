@@ -83,6 +83,13 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
 int flame_dso_submit(flame_dso_t *dso, const void *history_emb, const void *cand_emb, int32_t n_cand,
                      float *scores, int64_t *ticket);
 
+/* Mode 2 only: as flame_dso_submit for a request whose history has hist_len items, 0 <= hist_len <= the
+ * hist_len of create (which then is the capacity per request of an executor's buffers): jagged kernels take
+ * any mix of history lengths in one micro-batch.  UNSUPPORTED in modes 0 and 1, CAPACITY_EXCEEDED beyond
+ * the capacity. */
+int flame_dso_submit_jagged(flame_dso_t *dso, const void *history_emb, int32_t hist_len, const void *cand_emb,
+                            int32_t n_cand, float *scores, int64_t *ticket);
+
 /* Block until every chunk of `ticket` has completed and its scores are in the caller's array.
  * Waiting twice for a ticket, or for one already retired by executor reuse, returns at once. */
 int flame_dso_wait(flame_dso_t *dso, int64_t ticket);

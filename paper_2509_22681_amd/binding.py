@@ -99,6 +99,8 @@ _lib.flame_dso_create.argtypes = [C.POINTER(flame_gr_config), C.POINTER(flame_gr
 _lib.flame_dso_create.restype = C.c_int
 _lib.flame_dso_submit.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int64)]
 _lib.flame_dso_submit.restype = C.c_int
+_lib.flame_dso_submit_jagged.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p, C.POINTER(C.c_int64)]
+_lib.flame_dso_submit_jagged.restype = C.c_int
 _lib.flame_dso_wait.argtypes = [C.c_void_p, C.c_int64]
 _lib.flame_dso_wait.restype = C.c_int
 _lib.flame_dso_drain.argtypes = [C.c_void_p]
@@ -133,7 +135,7 @@ _lib.flame_climber_last_error.restype = C.c_char_p
 
 CLIMBER_EXPORTS = ("flame_climber_head", "flame_climber_block_range", "flame_climber_last_error")
 
-DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_wait", "flame_dso_drain", "flame_dso_flush", "flame_dso_destroy",
+DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_submit_jagged", "flame_dso_wait", "flame_dso_drain", "flame_dso_flush", "flame_dso_destroy",
                "flame_dso_last_error", "flame_dso_route", "flame_dso_stats")
 
 EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_forward_hidden", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
@@ -386,6 +388,20 @@ def flame_dso_submit(dso, history_emb: np.ndarray, cand_emb: np.ndarray, scores:
     t = C.c_int64(0)
     hp = history_emb.ctypes.data if history_emb is not None and history_emb.size else None
     _dso_check(_lib.flame_dso_submit(dso, hp, cand_emb.ctypes.data, int(cand_emb.shape[0]), scores.ctypes.data, C.byref(t)), dso)
+    return t.value
+
+
+def flame_dso_submit_jagged(dso, history_emb: np.ndarray, cand_emb: np.ndarray, scores: np.ndarray) -> int:
+    """Mode 2: a request whose history length is history_emb.shape[0] (at most the capacity given at create)."""
+    if not (cand_emb.flags.c_contiguous and scores.flags.c_contiguous and scores.dtype == np.float32):
+        raise ValueError("cand_emb and scores must be contiguous, scores float32")
+    L = int(history_emb.shape[0]) if history_emb is not None else 0
+    if L and not history_emb.flags.c_contiguous:
+        raise ValueError("history_emb must be contiguous")
+    t = C.c_int64(0)
+    hp = history_emb.ctypes.data if L else None
+    _dso_check(_lib.flame_dso_submit_jagged(dso, hp, L, cand_emb.ctypes.data, int(cand_emb.shape[0]), scores.ctypes.data,
+                                            C.byref(t)), dso)
     return t.value
 
 

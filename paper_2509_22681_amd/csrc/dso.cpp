@@ -30,7 +30,7 @@ struct Pending { int64_t ticket = -1; float *dst = nullptr; int32_t m = 0; };
 struct Executor {
   flame_gr_t *h = nullptr;
   int32_t cap = 0;          // candidate rows of the buffers (largest profile x requests per batch)
-  int32_t n_req = 0, n_cand = 0;          // jagged mode: requests and candidate rows gathered so far
+  int32_t n_req = 0, n_cand = 0, n_hist = 0;   // jagged mode: requests, candidate rows and history rows gathered so far
   std::vector<Pending> batch;             // jagged mode: what the gathered requests are owed (reserved at create)
   std::vector<int32_t> hoff, coff;        // jagged mode: offsets of the gathered batch (reserved at create)
   hipStream_t stream = nullptr;
@@ -135,7 +135,7 @@ int retire(flame_dso *d, int idx) {
       at += p.m;
     }
     e.batch.clear();
-    e.n_req = e.n_cand = 0;
+    e.n_req = e.n_cand = e.n_hist = 0;
   } else {
     std::memcpy(e.pending.dst, e.pin_scores, (size_t)e.pending.m * sizeof(float));
   }
@@ -157,7 +157,7 @@ int flush(flame_dso *d, int idx) {
   d->busy_q.push_back(idx);
   ++d->stats[1];
   d->stats[2] += e.n_cand;
-  if (d->L > 0) DSO_HIP(d, hipMemcpyAsync(e.dev_in, e.pin_in, (size_t)e.n_req * d->L * row, hipMemcpyHostToDevice, e.stream));
+  if (e.n_hist > 0) DSO_HIP(d, hipMemcpyAsync(e.dev_in, e.pin_in, (size_t)e.n_hist * row, hipMemcpyHostToDevice, e.stream));
   DSO_HIP(d, hipMemcpyAsync(e.dev_in + hist_region, e.pin_in + hist_region, (size_t)e.n_cand * row, hipMemcpyHostToDevice, e.stream));
   int rc = flame_gr_forward(e.h, &d->weights, e.dev_in, e.hoff.data(), e.dev_in + hist_region, e.coff.data(), e.n_req,
                             e.dev_scores, e.stream);
@@ -291,24 +291,23 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
   return FLAME_GR_OK;
 }
 
-int flame_dso_submit(flame_dso_t *d, const void *history_emb, const void *cand_emb, int32_t n_cand, float *scores,
-                     int64_t *ticket) {
-  if (!live(d)) return FLAME_GR_BAD_HANDLE;
+static int submit_request(flame_dso_t *d, const void *history_emb, int32_t hist_len, const void *cand_emb, int32_t n_cand,
+                          float *scores, int64_t *ticket) {
   d->err.clear();
   auto bad = [&](const char *m) { d->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
   if (n_cand < 1) return bad("n_cand must be >= 1");
   if (!cand_emb || !scores || !ticket) return bad("cand_emb, scores or ticket is NULL");
-  if (d->L > 0 && !history_emb) return bad("history_emb is NULL");
+  if (hist_len > 0 && !history_emb) return bad("history_emb is NULL");
   std::vector<Piece> pieces;
-  route(d->profiles, d->L, d->d, d->explicit_shapes, n_cand, pieces);
+  route(d->profiles, hist_len, d->d, d->explicit_shapes, n_cand, pieces);
   const int64_t t = d->next_ticket++;
   const size_t row = (size_t)d->d * d->elt;
-  const size_t hist_bytes = (size_t)d->L * row;
+  const size_t hist_bytes = (size_t)hist_len * row;
   int32_t taken = 0;
   ++d->stats[0];
   if (d->jagged) {
     // every piece (the whole request unless it exceeds the largest profile) joins the gathering batch
-    const size_t hist_region = (size_t)d->max_batch * hist_bytes;
+    const size_t hist_region = (size_t)d->max_batch * d->L * row;
     for (const Piece &pc : pieces) {
       if (d->gathering >= 0 && d->ex[d->gathering].n_cand + pc.count > d->ex[d->gathering].cap) {
         int rc = flush(d, d->gathering);
@@ -322,12 +321,13 @@ int flame_dso_submit(flame_dso_t *d, const void *history_emb, const void *cand_e
         g.coff.assign(1, 0);
       }
       Executor &e = d->ex[d->gathering];
-      if (hist_bytes) std::memcpy(e.pin_in + (size_t)e.n_req * hist_bytes, history_emb, hist_bytes);
+      if (hist_bytes) std::memcpy(e.pin_in + (size_t)e.n_hist * row, history_emb, hist_bytes);
       std::memcpy(e.pin_in + hist_region + (size_t)e.n_cand * row, (const char *)cand_emb + (size_t)taken * row, (size_t)pc.count * row);
       e.batch.push_back(Pending{t, scores + taken, pc.count});
       ++e.n_req;
       e.n_cand += pc.count;
-      e.hoff.push_back(e.n_req * d->L);
+      e.n_hist += hist_len;
+      e.hoff.push_back(e.n_hist);
       e.coff.push_back(e.n_cand);
       taken += pc.count;
       if (e.n_req == d->max_batch) {
@@ -368,6 +368,20 @@ int flame_dso_submit(flame_dso_t *d, const void *history_emb, const void *cand_e
   }
   *ticket = t;
   return FLAME_GR_OK;
+}
+
+int flame_dso_submit(flame_dso_t *d, const void *history_emb, const void *cand_emb, int32_t n_cand, float *scores,
+                     int64_t *ticket) {
+  if (!live(d)) return FLAME_GR_BAD_HANDLE;
+  return submit_request(d, history_emb, d->L, cand_emb, n_cand, scores, ticket);
+}
+
+int flame_dso_submit_jagged(flame_dso_t *d, const void *history_emb, int32_t hist_len, const void *cand_emb, int32_t n_cand,
+                            float *scores, int64_t *ticket) {
+  if (!live(d)) return FLAME_GR_BAD_HANDLE;
+  if (!d->jagged) { d->err = "histories of other lengths need the jagged micro-batch mode"; return FLAME_GR_UNSUPPORTED; }
+  if (hist_len < 0 || hist_len > d->L) { d->err = "hist_len must be in [0, the hist_len given at create]"; return FLAME_GR_CAPACITY_EXCEEDED; }
+  return submit_request(d, history_emb, hist_len, cand_emb, n_cand, scores, ticket);
 }
 
 int flame_dso_wait(flame_dso_t *d, int64_t ticket) {

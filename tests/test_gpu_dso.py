@@ -213,3 +213,34 @@ def test_orchestrator_rejects_bad_configurations(B):
     with pytest.raises(B.FlameGRError) as e:
         B.flame_dso_create(bad, dw, 10, [4], 1)
     assert e.value.code == -1
+
+
+def test_micro_batches_of_mixed_history_lengths(B):
+    """Mode 2 with flame_dso_submit_jagged: requests of different history and candidate lengths share micro-batches;
+    every request's scores equal those of its own eager forward (a request never sees its batch)."""
+    wl = stress([200, 10, 64, 333, 0, 129], [40, 300, 1, 17, 5, 64], 64, 2, "bf16", nb=16, D=512, name="mixed")
+    dw, _, _ = B.to_device(wl)
+    ref, _ = run_gpu(B, wl)
+    ho, co = wl.history_offsets, wl.cand_offsets
+    dso = B.flame_dso_create(B.config_for(wl), dw, 400, [128, 300], n_executors=2, explicit_shapes=2, max_batch=4)
+    try:
+        outs = [np.full(int(co[i + 1] - co[i]), np.nan, np.float32) for i in range(wl.n_requests)]
+        tickets = [B.flame_dso_submit_jagged(dso, B.host_embedding(wl.history_emb[ho[i]:ho[i + 1]], "bf16"),
+                                             B.host_embedding(wl.cand_emb[co[i]:co[i + 1]], "bf16"), outs[i])
+                   for i in range(wl.n_requests)]
+        for t in tickets:
+            B.flame_dso_wait(dso, t)
+        for i in range(wl.n_requests):
+            assert np.array_equal(outs[i], ref[co[i]:co[i + 1]]), i
+        with pytest.raises(B.FlameGRError) as e:                      # a history beyond the capacity
+            B.flame_dso_submit_jagged(dso, np.zeros((401, 64), np.uint16), np.zeros((1, 64), np.uint16), np.zeros(1, np.float32))
+        assert e.value.code == -2
+    finally:
+        B.flame_dso_destroy(dso)
+    dso = B.flame_dso_create(B.config_for(wl), dw, 400, [128, 300], n_executors=1, explicit_shapes=0)
+    try:
+        with pytest.raises(B.FlameGRError) as e:                      # only the micro-batch mode takes other lengths
+            B.flame_dso_submit_jagged(dso, np.zeros((10, 64), np.uint16), np.zeros((1, 64), np.uint16), np.zeros(1, np.float32))
+        assert e.value.code == -5
+    finally:
+        B.flame_dso_destroy(dso)
