@@ -1,9 +1,11 @@
 // Fusion of the sub-sequence blocks and the task head of the paper's model (flame_climber.h):
 //   g_b = sigmoid([H_0 | ... | H_{Nb-1}] Wg_b^T + cg_b),  F = sum_b g_b * H_b,
 //   p_t = sigmoid(<v_t, relu(F A_t^T + a_t)> + c_t).
-// fp32 FMA kernels with LDS tiling (64 x 64 output tile, 64-deep k chunks, 256 threads each owning a
-// 4 x 4 patch): correct and allocation-free, not tuned - at the paper's shapes this stage is a few
-// per cent of the block stacks' work.
+// Both products run on the fp32 matrix instruction (32 x 32 x 2, fp32 operands and accumulator, the same
+// arithmetic as a chain of FMAs) whenever d is a multiple of 32 and the operands are 16-byte aligned: a
+// wavefront owns a 32 x 32 output tile and feeds the instruction straight from global memory, one 16-byte
+// load per operand and lane for four instructions, no LDS staging.  Other shapes take fp32 FMA kernels with
+// LDS tiling (64 x 64 output tile, 64-deep k chunks, 256 threads each owning a 4 x 4 patch).
 #include <hip/hip_runtime.h>
 
 #include "../../include/flame_climber.h"
@@ -137,6 +139,206 @@ __global__ __launch_bounds__(256) void expert_kernel(const float *__restrict__ F
   }
 }
 
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+// The fp32 matrix instruction computes acc[i][j] += sum over its two k slots of A[i][k] W[j][k] for 32 rows i and
+// 32 rows j: lane l supplies row l & 31 of both operands, k slot l >> 5.  A lane reads 4 consecutive floats of
+// its row at offset 4 * (l >> 5) of every group of 8: the two lane halves then hold the k slots {8s + t} and
+// {8s + 4 + t} of instruction t of step s.  Accumulator element e of a lane is output row
+// 8 * (e / 4) + 4 * (l >> 5) + e % 4, column l & 31.
+__device__ __forceinline__ void mfma_step(const float4 a, const float4 w, f32x16 &acc) {
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.x, w.x, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.y, w.y, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.z, w.z, acc, 0, 0, 0);
+  acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a.w, w.w, acc, 0, 0, 0);
+}
+
+// Both kernels below stream ALL their steps (every gate block, every group of expert units) through one ring of
+// PD float4 pairs per lane: as soon as step s has been issued, its slot is refilled with the operands of step
+// s + PD, across the boundaries between products, so the memory latency is paid once per kernel and not once
+// per product.  Refilling after the use (not before) lets old and new value share registers; the request
+// cursor stops at the last step instead of being guarded, so the loop body has no branch; the scheduling
+// barriers keep the compiler from moving the requests down to their first use.  Products end on a multiple of
+// PD steps (d a multiple of 8 * PD).
+constexpr int PD = 4;
+
+// Fusion on the matrix instruction: workgroup = 32 rows x (4 wavefronts x 32 features).  Rows and features
+// past the end are clamped for the loads and dropped at the store.  No barrier: a wavefront with no feature
+// tile leaves at once.
+__global__ __launch_bounds__(256) void fuse_mfma_kernel(HiddenPtrs H, int n_blocks, const float *__restrict__ wg,
+                                                        const float *__restrict__ cg, float *__restrict__ F, int64_t rows, int d) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, l32 = lane & 31, lh = lane >> 5;
+  const int f0 = (blockIdx.y * 4 + wave) * 32;
+  if (f0 >= d) return;
+  const int64_t row0 = (int64_t)blockIdx.x * 32;
+  const int64_t aoff = min(row0 + l32, rows - 1) * d + 4 * lh;
+  const int wrow = min(f0 + l32, d - 1);
+  const int K = n_blocks * d;
+  const int sd = d >> 3;             // steps per source block
+  const int spb = n_blocks * sd;     // steps per gate block
+  const int total = n_blocks * spb;
+  const float *wbase = wg + (int64_t)wrow * K + 4 * lh;
+  const int64_t wpitch = (int64_t)d * K;
+  // request cursor: gate block pb, source block psb, step pk in the source block, step pr in the gate block
+  int pb = 0, psb = 0, pk = 0, pr = 0, pq = 0;
+  const float *hp = H.h[0] + aoff;
+  const float *wp = wbase;
+  auto fetch = [&](float4 &a, float4 &w) {
+    a = *(const float4 *)(hp + 8 * pk);
+    w = *(const float4 *)(wp + 8 * pr);
+    if (pq < total - 1) {
+      ++pq;
+      ++pr;
+      if (++pk == sd) {
+        pk = 0;
+        if (++psb == n_blocks) {
+          psb = 0;
+          pr = 0;
+          ++pb;
+          wp = wbase + pb * wpitch;
+        }
+        hp = H.h[psb] + aoff;
+      }
+    }
+  };
+  // operands of the gate of block cb: its bias and this lane's 16 elements of H_cb, requested a product ahead
+  const int f = f0 + l32;
+  const bool fin = f < d;
+  float hb[16], bias;
+  auto fetch_gate = [&](int cb) {
+    bias = cg[cb * d + wrow];
+    const float *Hb = H.h[cb];
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+      const int64_t r = min(row0 + 8 * (e >> 2) + 4 * lh + (e & 3), rows - 1);
+      hb[e] = Hb[r * d + wrow];
+    }
+  };
+  float4 a[PD], w[PD];
+#pragma unroll
+  for (int p = 0; p < PD; ++p) fetch(a[p], w[p]);
+  fetch_gate(0);
+  f32x16 fused = {}, acc = {};
+  int cb = 0, left = spb;
+  for (int s0 = 0; s0 < total; s0 += PD) {
+#pragma unroll
+    for (int p = 0; p < PD; ++p) {
+      mfma_step(a[p], w[p], acc);
+      __builtin_amdgcn_sched_barrier(0);
+      fetch(a[p], w[p]);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    left -= PD;
+    if (left == 0) {
+#pragma unroll
+      for (int e = 0; e < 16; ++e) {
+        fused[e] = fmaf(sigmoid_f32(acc[e] + bias), hb[e], fused[e]);
+        acc[e] = 0.f;
+      }
+      // the next gate's operands reuse hb's registers: requested after the use above, and without a branch
+      // (after the last gate the request repeats itself), so that the barrier holds them in place
+      __builtin_amdgcn_sched_barrier(0);
+      cb = min(cb + 1, n_blocks - 1);
+      fetch_gate(cb);
+      left = spb;
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) {
+    const int64_t r = row0 + 8 * (e >> 2) + 4 * lh + (e & 3);
+    if (fin && r < rows) F[r * d + f] = fused[e];
+  }
+}
+
+// Task head on the matrix instruction: workgroup = 32 rows of one task; wavefront w takes the expert units
+// [32 (w + 4 j), +32) and keeps <v, relu(.)> of its 16 rows over its units in registers.  The sum over the
+// units of a row (32 lanes x 4 wavefronts) goes through LDS in a fixed order.
+__global__ __launch_bounds__(256) void expert_mfma_kernel(const float *__restrict__ F, const float *__restrict__ a_w,
+                                                          const float *__restrict__ a_b, const float *__restrict__ v,
+                                                          const float *__restrict__ c, float *__restrict__ probs, int64_t rows,
+                                                          int d, int E, int T) {
+  __shared__ float red[4][32][32 + 1];
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), l32 = lane & 31, lh = lane >> 5;
+  const int64_t row0 = (int64_t)blockIdx.x * 32;
+  const int t = blockIdx.y;
+  const float *pa = F + min(row0 + l32, rows - 1) * d + 4 * lh;
+  const int sd = d >> 3;
+  const int nseg = wave * 32 < E ? (E - wave * 32 + 127) / 128 : 0;   // groups of 32 units this wavefront owns
+  const int total = nseg * sd;
+  float part[16];
+#pragma unroll
+  for (int e = 0; e < 16; ++e) part[e] = 0.f;
+  if (nseg > 0) {
+    auto unit_of = [&](int j) { return min(wave * 32 + 128 * j + l32, E - 1); };
+    auto wrow_of = [&](int j) { return a_w + ((int64_t)t * E + unit_of(j)) * d + 4 * lh; };
+    int pj = 0, pk = 0, pq = 0;
+    const float *wp = wrow_of(0);
+    auto fetch = [&](float4 &a, float4 &w) {
+      a = *(const float4 *)(pa + 8 * pk);
+      w = *(const float4 *)(wp + 8 * pk);
+      if (pq < total - 1) {
+        ++pq;
+        if (++pk == sd) {
+          pk = 0;
+          wp = wrow_of(++pj);
+        }
+      }
+    };
+    float ab, ve;
+    bool live;   // units past E are computed on clamped operands and weighted 0
+    auto fetch_unit = [&](int j) {
+      ab = a_b[t * E + unit_of(j)];
+      ve = v[t * E + unit_of(j)];
+      live = wave * 32 + 128 * j + l32 < E;
+    };
+    float4 a[PD], w[PD];
+#pragma unroll
+    for (int p = 0; p < PD; ++p) fetch(a[p], w[p]);
+    fetch_unit(0);
+    f32x16 acc = {};
+    int cj = 0, left = sd;
+    for (int s0 = 0; s0 < total; s0 += PD) {
+#pragma unroll
+      for (int p = 0; p < PD; ++p) {
+        mfma_step(a[p], w[p], acc);
+        __builtin_amdgcn_sched_barrier(0);
+        fetch(a[p], w[p]);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      left -= PD;
+      if (left == 0) {
+        const float vl = live ? ve : 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+          part[e] = fmaf(fmaxf(acc[e] + ab, 0.f), vl, part[e]);
+          acc[e] = 0.f;
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        cj = min(cj + 1, nseg - 1);
+        fetch_unit(cj);
+        left = sd;
+      }
+    }
+  }
+#pragma unroll
+  for (int e = 0; e < 16; ++e) red[wave][8 * (e >> 2) + 4 * lh + (e & 3)][l32] = part[e];
+  __syncthreads();
+  // thread (row = tid / 8, seg = tid % 8) sums columns [4 seg, +4) of the four wavefronts, then the 8 threads of a row
+  const int rr = threadIdx.x >> 3, seg = threadIdx.x & 7;
+  float s = 0.f;
+#pragma unroll
+  for (int w = 0; w < 4; ++w)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) s += red[w][rr][seg * 4 + q];
+  s += __shfl_xor(s, 1);
+  s += __shfl_xor(s, 2);
+  s += __shfl_xor(s, 4);
+  const int64_t r = row0 + rr;
+  if (seg == 0 && r < rows) probs[r * T + t] = sigmoid_f32(s + c[t]);
+}
+
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
 thread_local const char *g_head_error = "";
 
 }  // namespace
@@ -162,6 +364,17 @@ int flame_climber_head(const flame_climber_head_config *cfg, const flame_climber
     H.h[b] = hidden[b];
   }
   hipStream_t s = (hipStream_t)stream;
+  bool mfma = cfg->d_model % (8 * PD) == 0 && aligned16(w->wg) && aligned16(w->a_w) && aligned16(fused);
+  for (int b = 0; b < cfg->n_blocks; ++b) mfma = mfma && aligned16(hidden[b]);
+  if (mfma) {
+    const unsigned tiles32 = (unsigned)((n_rows + 31) / 32);
+    fuse_mfma_kernel<<<dim3(tiles32, (cfg->d_model + 127) / 128), 256, 0, s>>>(H, cfg->n_blocks, w->wg, w->cg, fused, n_rows, cfg->d_model);
+    expert_mfma_kernel<<<dim3(tiles32, cfg->n_tasks), 256, 0, s>>>(fused, w->a_w, w->a_b, w->v, w->c, probs, n_rows, cfg->d_model,
+                                                                   cfg->expert_width, cfg->n_tasks);
+    const hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { g_head_error = hipGetErrorString(e); return FLAME_GR_HIP_ERROR; }
+    return FLAME_GR_OK;
+  }
   const unsigned row_tiles = (unsigned)((n_rows + 63) / 64);
   fuse_kernel<<<dim3(row_tiles, (cfg->d_model + 63) / 64), 256, 0, s>>>(H, cfg->n_blocks, w->wg, w->cg, fused, n_rows, cfg->d_model);
   expert_kernel<<<dim3(row_tiles, cfg->n_tasks), 256, 0, s>>>(fused, w->a_w, w->a_b, w->v, w->c, probs, n_rows, cfg->d_model,

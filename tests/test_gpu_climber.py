@@ -85,7 +85,8 @@ def climber_oracle(base, block_weights, head):
 def test_head_alone_on_ragged_shapes(B):
     import torch
     rng = np.random.default_rng(4)
-    for nb, d, T, E, rows in [(3, 40, 3, 70, 131), (1, 64, 1, 1, 1), (2, 128, 2, 256, 700), (8, 8, 5, 9, 65)]:
+    for nb, d, T, E, rows in [(3, 40, 3, 70, 131), (1, 64, 1, 1, 1), (2, 128, 2, 256, 700), (8, 8, 5, 9, 65),
+                              (2, 192, 2, 160, 97), (2, 36, 2, 33, 70), (3, 12, 1, 130, 33)]:
         Hs = [rng.standard_normal((rows, d)).astype(np.float32) * 1.5 for _ in range(nb)]
         hw = head_weights(nb, d, T, E, nb)
         want = oracle.fuse_and_score(hw, Hs)
