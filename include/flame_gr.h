@@ -25,7 +25,8 @@
  *     or prints.  flame_gr_last_error gives a message for the most recent failure on a handle
  *     (or, with a NULL handle, for the most recent failing flame_gr_create on this thread).
  *   - "device" pointers are HIP device memory on the device that was current at create time;
- *     "host" pointers are ordinary host memory.  The caller owns every pointer it passes; the
+ *     "host" pointers are ordinary host memory.  Calls that enqueue work for a handle while another
+ *     device is current are INVALID_ARGUMENT.  The caller owns every pointer it passes; the
  *     library owns the handle and its workspaces.
  *   - A handle is used by one host thread at a time.
  *   - With dtype FLAME_GR_BF16 every embedding and weight pointer must be 16-byte aligned (the kernels

@@ -108,6 +108,14 @@ namespace {
 
 bool live(const flame_gr *h) { return h && h->magic == kMagic; }
 
+// A handle's buffers live on the device that was current at create: work for it is enqueued there only.
+bool on_own_device(flame_gr *h) {
+  int dev = -1;
+  if (hipGetDevice(&dev) == hipSuccess && dev == h->device) return true;
+  h->err = "the handle was created on another device than the current one";
+  return false;
+}
+
 // IEEE binary16 -> float on the host (debug export only)
 float half_bits_to_float(uint16_t b) {
   const uint32_t sign = (uint32_t)(b & 0x8000u) << 16;
@@ -475,6 +483,7 @@ static int forward_common(flame_gr_t *h, const flame_gr_weights *w, const void *
                           int32_t n_requests, float *scores, float *hidden, void *stream_v) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
+  if (!on_own_device(h)) return FLAME_GR_INVALID_ARGUMENT;
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
   const bool want_hidden = scores == nullptr && hidden != nullptr;
   if (!w) return bad("weights is NULL");
@@ -523,6 +532,7 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
                      int32_t n_requests, float *scores, void *record_stream) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
+  if (!on_own_device(h)) return FLAME_GR_INVALID_ARGUMENT;
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
   if (slot < 0 || slot >= kMaxGraphs) return bad("graph slot out of range");
   if (h->n_groups != 1) { h->err = "capture needs a handle without internal stream groups (n_streams <= 1)"; return FLAME_GR_UNSUPPORTED; }
@@ -590,6 +600,7 @@ int flame_gr_capture(flame_gr_t *h, int32_t slot, const flame_gr_weights *w, con
 int flame_gr_replay(flame_gr_t *h, int32_t slot, void *stream_v) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
+  if (!on_own_device(h)) return FLAME_GR_INVALID_ARGUMENT;
   if (slot < 0 || slot >= kMaxGraphs) { h->err = "graph slot out of range"; return FLAME_GR_INVALID_ARGUMENT; }
   if (!h->graphs[slot].valid) { h->err = "no captured forward in this slot"; return FLAME_GR_INVALID_ARGUMENT; }
   hipStream_t s0 = (hipStream_t)stream_v;
@@ -606,6 +617,7 @@ int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *w, const void *histo
                      void *stream_v) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
+  if (!on_own_device(h)) return FLAME_GR_INVALID_ARGUMENT;
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
   if (!h->cfg.kv_cache) { h->err = "handle was created without kv_cache"; return FLAME_GR_UNSUPPORTED; }
   if (!w) return bad("weights is NULL");
@@ -637,6 +649,7 @@ int flame_gr_score(flame_gr_t *h, const flame_gr_weights *w, const void *cand_em
                    int32_t n_requests, float *scores, void *stream_v) {
   if (!live(h)) return FLAME_GR_BAD_HANDLE;
   h->err.clear();
+  if (!on_own_device(h)) return FLAME_GR_INVALID_ARGUMENT;
   auto bad = [&](const char *m) { h->err = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
   if (!h->cfg.kv_cache) { h->err = "handle was created without kv_cache"; return FLAME_GR_UNSUPPORTED; }
   if (!h->kv_valid) return bad("no valid prefill on this handle");
