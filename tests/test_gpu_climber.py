@@ -97,6 +97,22 @@ def test_head_alone_on_ragged_shapes(B):
         torch.cuda.synchronize()
         err = np.abs(probs.cpu().numpy() - want).max()
         assert err <= 2e-6, (nb, d, T, E, rows, err)
+    # hidden rows that are not 16-byte aligned take the kernels that load single floats: same result
+    nb, d, T, E, rows = 2, 64, 2, 48, 77
+    Hs = [rng.standard_normal((rows, d)).astype(np.float32) for _ in range(nb)]
+    hw = head_weights(nb, d, T, E, 5)
+    want = oracle.fuse_and_score(hw, Hs)
+    shifted = []
+    for h_ in Hs:
+        buf = torch.zeros(rows * d + 1, device="cuda:0")
+        buf[1:] = dev(h_).reshape(-1)
+        shifted.append(buf[1:].view(rows, d))
+        assert shifted[-1].data_ptr() % 16 == 4
+    fused = torch.empty((rows, d), device="cuda:0")
+    probs = torch.full((rows, T), float("nan"), device="cuda:0")
+    B.flame_climber_head({k: dev(v) for k, v in hw.items()}, shifted, fused, probs)
+    torch.cuda.synchronize()
+    assert np.abs(probs.cpu().numpy() - want).max() <= 2e-6
     # error paths: no blocks, too many blocks, a missing weight
     hw = {k: dev(v) for k, v in head_weights(1, 8, 1, 2, 0).items()}
     h1 = torch.zeros((4, 8), device="cuda:0")
