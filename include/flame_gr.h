@@ -74,7 +74,8 @@ typedef struct {
   float ln_eps;          /* LayerNorm epsilon; 0 selects 1e-6 */
   float attn_scale;      /* alpha; 0 selects 1.0 */
   int32_t max_requests;      /* capacity: requests per forward */
-  int32_t max_total_tokens;  /* capacity: sum over requests of (L_i + M_i) per forward */
+  int32_t max_total_tokens;  /* capacity: sum over requests of (L_i + M_i) per forward; FLAME_GR_BF16: the
+                                padded workspace must stay below 2^26 rows, else UNSUPPORTED */
   int32_t max_seq_tokens;    /* 0 = unlimited; else a request with L_i + M_i above this is split by
                                 candidates into chunks (largest first), each chunk re-running the
                                 history, as the descending-size split of Section 3.3 does */

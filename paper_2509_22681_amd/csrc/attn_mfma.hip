@@ -177,35 +177,45 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
   static_assert(NKI % NW == 0 && NVI % NW == 0, "every wavefront issues the same number of requests per tile");
   static_assert((NW * (64 / KCH)) % (KCH << KSH) == 0 && (NW * (64 / VCH)) % (VCH << VSH) == 0, "swizzle keys do not depend on the instruction");
   constexpr int REQ = NKI / NW + NVI / NW + 1;       // requests per wavefront and tile
-  const half_t *pK, *pV;
-  int dW = q_first + (QT - 1) - (wave * 64 + lane);   // distance held by window slot 64 w + lane, next tile
+  // Addresses are a wave-uniform base (advanced per tile with scalar arithmetic) plus a 32-bit lane offset that
+  // never changes: the request instruction takes them as scalar base + vector offset, and a tile costs no
+  // vector address arithmetic.  (Lane offsets stay below 2^32: at most 64 rows of d, resp. DH rows of ws_rows.)
+  const char *bK = (const char *)(Kp + (int64_t)it.kv_row * d);
+  const char *bV = (const char *)(Vt + it.kv_row);
+  uint32_t oK, oV;
+  const int dW0 = q_first + (QT - 1) - (wave * 64 + lane);   // distance held by window slot 64 w + lane in tile 0
+  int sW = 0;                                                 // keys the next tile to request lies behind tile 0 (scalar)
   {
     const int row = wave * (64 / KCH) + lane / KCH;
     const int c = (lane % KCH) ^ ((row >> KSH) & (KCH - 1));
-    pK = Kp + (int64_t)(it.kv_row + row) * d + c * 8;
+    oK = (uint32_t)(row * d + c * 8) * 2u;
   }
   {
     const int row = wave * (64 / VCH) + lane / VCH;
     const int c = (lane % VCH) ^ ((row >> VSH) & (VCH - 1));
-    pV = Vt + (int64_t)row * ws_rows + it.kv_row + c * 8;
+    oV = (uint32_t)((int64_t)row * ws_rows + c * 8) * 2u;
   }
   auto request_tile = [&](int stage) {
     char *sb = lds + stage * STAGE;
+    // (the empty asm keeps the widening of the offsets next to the requests: hoisted out of the loop, the
+    // compiler would add full 64-bit vector addresses per request again)
+    asm volatile("" : "+v"(oK), "+v"(oV));
 #pragma unroll
     for (int i = 0; i < NKI / NW; ++i)
-      __builtin_amdgcn_global_load_lds((gvoid *)(pK + (int64_t)(i * NW * (64 / KCH)) * d), (lvoid *)(sb + (wave + NW * i) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gvoid *)(bK + (int64_t)(i * NW * (64 / KCH)) * d * 2 + oK), (lvoid *)(sb + (wave + NW * i) * 1024), 16, 0, 0);
 #pragma unroll
     for (int i = 0; i < NVI / NW; ++i)
-      __builtin_amdgcn_global_load_lds((gvoid *)(pV + (int64_t)(i * NW * (64 / VCH)) * ws_rows), (lvoid *)(sb + K_BYTES + (wave + NW * i) * 1024), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((gvoid *)(bV + (int64_t)(i * NW * (64 / VCH)) * ws_rows * 2 + oV), (lvoid *)(sb + K_BYTES + (wave + NW * i) * 1024), 16, 0, 0);
     // every wavefront issues one window request, so that all of them have the same number of requests in
     // flight per tile (slots past the window are filled too and never read)
-    const int dl_ = dW < 0 ? 0 : (dW > D - 1 ? D - 1 : dW);
-    __builtin_amdgcn_global_load_lds((gvoid *)(bias + dl_), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
+    uint32_t oW = (uint32_t)max(0, min(D - 1, dW0 - sW)) * 4u;
+    asm volatile("" : "+v"(oW));
+    __builtin_amdgcn_global_load_lds((gvoid *)((const char *)bias + oW), (lvoid *)(sb + K_BYTES + V_BYTES + wave * 256), 4, 0, 0);
   };
   auto next_tile = [&]() {
-    pK += (int64_t)KT * d;
-    pV += KT;
-    dW -= KT;
+    bK += (int64_t)KT * d * 2;
+    bV += KT * 2;
+    sW += KT;
   };
 
   // Window slot of (my row, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's index in the

@@ -38,6 +38,11 @@ int validate_config(const flame_gr_config &c, std::string &err) {
       err = "bf16 path needs d_model % 64 == 0 and head width 32 or 64";
       return FLAME_GR_UNSUPPORTED;
     }
+    // the attention kernel reaches the 32 rows of a V^T request with 32-bit byte offsets from a 64-bit base
+    if (workspace_rows(c) >= (int64_t)1 << 26) {
+      err = "bf16 path: max_total_tokens (plus padding) must stay below 2^26 rows";
+      return FLAME_GR_UNSUPPORTED;
+    }
   } else if (c.d_model / c.n_heads > 256) {
     err = "fp32 path needs head width <= 256";
     return FLAME_GR_UNSUPPORTED;

@@ -143,12 +143,14 @@ def test_config_validation_codes():
     for kw, code in [(dict(n_layers=0), -1), (dict(d_model=65), -1), (dict(n_buckets=12), -1),
                      (dict(max_rel_dist=1000), -1), (dict(dtype=7), -1), (dict(n_streams=99), -1),
                      (dict(d_model=96, n_heads=2), -5), (dict(d_model=64, n_heads=4), -5),
-                     (dict(d_model=128, n_heads=1), -5)]:
+                     (dict(d_model=128, n_heads=1), -5), (dict(max_total_tokens=1 << 26), -5)]:
         with pytest.raises(B.FlameGRError) as e:
             B.flame_gr_host_plan(_cfg(**kw), ho, co)
         assert e.value.code == code, kw
     # the fp32 path has no such shape restrictions
     B.flame_gr_host_plan(_cfg(dtype="f32", d_model=96, n_heads=2), ho, co)
+    B.flame_gr_host_plan(_cfg(dtype="f32", max_total_tokens=1 << 26), ho, co)
+    B.flame_gr_host_plan(_cfg(max_total_tokens=(1 << 26) - (1 << 15)), ho, co)
 
 
 def test_destroy_null_is_a_noop_and_bad_handle_is_reported():
