@@ -40,6 +40,8 @@
 // LDS; a lane's 8 consecutive entries per accumulator half-block are read straight into the
 // accumulator registers, so the bias add costs LDS bandwidth but no VALU instruction (on this
 // chip VALU and MFMA work of one SIMD largely serialise, so every VALU instruction saved counts).
+#include <type_traits>
+
 #include "device_common.h"
 #include "kernels.h"
 
@@ -238,21 +240,19 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
     if (n_tiles > 1) next_tile();
     request_tile(1);
   }
-  int st = 0;
-  for (int t = 0; t < n_tiles; ++t) {
-    const char *sb = lds + st * STAGE;
+  // One key tile.  The stage is a compile-time constant (the tile loop below is unrolled over the ring), so
+  // every fragment address is a fixed lane offset plus an immediate and costs no instruction.
+  auto tile_step = [&](auto stage_c, const int t) {
+    constexpr int ST = decltype(stage_c)::value;
+    const char *sb = lds + ST * STAGE;
     // tile t has landed for this wavefront; past the barrier it has landed for all of them, and everybody
     // has left tile t-1, whose stage the next request overwrites
     if (REQ == 5) asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
     else if (REQ == 3) asm volatile("s_waitcnt vmcnt(3)" ::: "memory");
     else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_s_barrier();
-    {
-      const int st2 = st + 2 >= NSTAGE ? st + 2 - NSTAGE : st + 2;
-      if (t + 2 < n_tiles) next_tile();
-      request_tile(st2);
-    }
-    st = st + 1 >= NSTAGE ? 0 : st + 1;
+    if (t + 2 < n_tiles) next_tile();
+    request_tile((ST + 2) % NSTAGE);
     __builtin_amdgcn_sched_barrier(0);   // the requests stay ahead of the tile's arithmetic
 #pragma unroll 1
     for (int u = KSPLIT ? k_half : 0; u < (KSPLIT ? k_half + 1 : KT / KH); ++u) {
@@ -426,6 +426,12 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
       }
     }
     }
+  };
+  static_assert(NSTAGE == 3, "the tile loop is unrolled over a ring of three stages");
+  for (int t = 0; t < n_tiles; t += NSTAGE) {
+    tile_step(std::integral_constant<int, 0>{}, t);
+    if (t + 1 < n_tiles) tile_step(std::integral_constant<int, 1>{}, t + 1);
+    if (t + 2 < n_tiles) tile_step(std::integral_constant<int, 2>{}, t + 2);
   }
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the repeated requests of the tail have landed
   __builtin_amdgcn_s_barrier();          // everybody has left the last tile: the stages become output patches
