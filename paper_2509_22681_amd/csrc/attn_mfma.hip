@@ -261,6 +261,8 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
       const char *kb = sb + u * (KH * DH * 2);                 // K rows of this half tile
       const int vau = va0 ^ (u << 7);                          // V^T: chunks 8 u .. 8 u + 7 of each row
       const bool need_mask = k0 + KH > wave_vis_min;
+      // key 32 j + 16 (e >> 3) + 8 lhalf + (e & 7) of this half tile is visible to my row iff its constant part is below vis_lim
+      const int vis_lim = n_vis - k0 - 8 * lhalf;
       {
         // ---- S^T = K Q^T: blocks [j], j = 32-key half of the half tile.  Fragment reads run one group
         // ahead of the MFMAs that use them (and the first V^T group is fetched behind the last K group),
@@ -308,8 +310,7 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
             for (int j = 0; j < 2; ++j)
 #pragma unroll
               for (int e = 0; e < 16; ++e) {
-                const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-                sacc[j][e] = kv < n_vis ? sacc[j][e] : kNeg;
+                sacc[j][e] = 32 * j + 16 * (e >> 3) + (e & 7) < vis_lim ? sacc[j][e] : kNeg;
               }
           }
           float mx[4];
@@ -382,8 +383,7 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
               if (need_mask) {
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
-                  const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-                  w[e] = kv < n_vis ? w[e] : 0.f;
+                  w[e] = 32 * j + 16 * (e >> 3) + (e & 7) < vis_lim ? w[e] : 0.f;
                 }
               }
               __builtin_amdgcn_sched_barrier(0);
@@ -401,8 +401,7 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
             if (need_mask) {
 #pragma unroll
               for (int e = 0; e < 16; ++e) {
-                const int kv = k0 + 32 * j + 16 * (e >> 3) + 8 * lhalf + (e & 7);
-                p[e] = kv < n_vis ? p[e] : 0.f;
+                p[e] = 32 * j + 16 * (e >> 3) + (e & 7) < vis_lim ? p[e] : 0.f;
               }
             }
             fp[2 * j] = pack8(p);
