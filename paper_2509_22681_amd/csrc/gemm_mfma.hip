@@ -124,15 +124,19 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
   const int dch = (lane & 3) ^ lds_key(rloc);
   // W is k-tile blocked (64 rows x 32 k = 2048 contiguous elements, whole 128-byte lines per request);
   // A is blocked too when it is the activation copy Xh, row-major when it is G.
-  int64_t aoff[A_Q];
+  // Every request address is a wave-uniform base (64-row block and k tile: scalar arithmetic) plus a fixed 32-bit
+  // lane offset in bytes, which is the scalar-base form of the request instruction: no vector address
+  // arithmetic per k tile.  (Lane offsets are below 64 rows x K elements.)
+  const char *abase[A_Q];
 #pragma unroll
   for (int q = 0; q < A_Q; ++q) {
     const int b = blk[q] >= 0 ? blk[q] : blk[0];
-    aoff[q] = a_blocked ? (int64_t)b * kRowAlign * K + rloc * 32 + dch * 8 : ((int64_t)b * kRowAlign + rloc) * K + dch * 8;
+    abase[q] = (const char *)(A + (int64_t)b * kRowAlign * K);
   }
-  const int a_kstep = a_blocked ? 64 * BK : BK;
-  const half_t *Wn0 = W + (int64_t)n0 * K;            // n0 % 64 == 0: a block boundary
-  const int boff = rloc * 32 + dch * 8;
+  uint32_t alane = (uint32_t)(a_blocked ? rloc * 32 + dch * 8 : rloc * K + dch * 8) * 2u;
+  const int a_kstep = (a_blocked ? 64 * BK : BK) * 2;                 // bytes per k tile
+  const char *Wn0 = (const char *)(W + (int64_t)n0 * K);  // n0 % 64 == 0: a block boundary
+  uint32_t blane = (uint32_t)(rloc * 32 + dch * 8) * 2u;
   // Operand order.  Row-major outputs (U, Q, K planes, X) want each lane to hold 4 consecutive
   // features of one token, which is the transposed accumulator: W rows as the A operand.  The V
   // plane is stored feature-major for the attention kernel (V^T is its A operand) and wants 4
@@ -193,12 +197,15 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
       // all of them missing together.
       int kt_ = (tile < nk ? tile : nk - 1) + k_rot;
       kt_ = kt_ >= nk ? kt_ - nk : kt_;
+      // (the empty asm keeps the widening of the lane offsets next to the requests; hoisted out of the loop the
+      // compiler would go back to full 64-bit vector addresses)
+      asm volatile("" : "+v"(alane), "+v"(blane));
 #pragma unroll
       for (int q = 0; q < A_Q; ++q)
-        __builtin_amdgcn_global_load_lds((gvoid *)(A + aoff[q] + kt_ * a_kstep), (lvoid *)(smem + stage * STAGE + (4 * q + wave) * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((gvoid *)(abase[q] + (int64_t)kt_ * a_kstep + alane), (lvoid *)(smem + stage * STAGE + (4 * q + wave) * 1024), 16, 0, 0);
 #pragma unroll
       for (int q = 0; q < B_Q; ++q)
-        __builtin_amdgcn_global_load_lds((gvoid *)(Wn0 + (size_t)q * 64 * K + boff + kt_ * (64 * BK)),
+        __builtin_amdgcn_global_load_lds((gvoid *)(Wn0 + ((size_t)q * 64 * K + (size_t)kt_ * (64 * BK)) * 2 + blane),
                                          (lvoid *)(smem + stage * STAGE + A_BYTES + (4 * q + wave) * 1024), 16, 0, 0);
     };
 #define GEMM_MFMA(S, i, j)                                                                              \
