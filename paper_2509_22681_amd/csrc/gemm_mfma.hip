@@ -214,15 +214,16 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     request(0, 0);
     request(1, 1);
     f16x8 fa[2][MB], fb[2][NB];
-    int st = 0;
-    for (int kt = 0; kt < nk; ++kt) {
+    // One k tile.  The stage is a compile-time constant (the loop below is unrolled over the ring), so the
+    // fragment reads are a fixed lane offset plus an immediate and need no address instruction.
+    auto k_step = [&](auto stage_c, const int kt) {
+      constexpr int ST = decltype(stage_c)::value;
       // tile kt has landed for this wavefront once at most the requests of tile kt+1 are outstanding
       if (A_Q + B_Q == 6) asm volatile("s_waitcnt vmcnt(6)" ::: "memory");
       else asm volatile("s_waitcnt vmcnt(5)" ::: "memory");
       __builtin_amdgcn_s_barrier();
-      const int st2 = st + 2 >= NSTAGE ? st + 2 - NSTAGE : st + 2;
-      request(kt + 2, st2);
-      const char *sp = smem + st * STAGE;
+      request(kt + 2, (ST + 2) % NSTAGE);
+      const char *sp = smem + ST * STAGE;
 #pragma unroll
       for (int i = 0; i < MB; ++i) fa[0][i] = *(const f16x8 *)(sp + f0[0] + i * 2048);
 #pragma unroll
@@ -247,7 +248,12 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 #pragma unroll
         for (int i = 0; i < MB; ++i) GEMM_MFMA(1, i, j);
       __builtin_amdgcn_sched_barrier(0);
-      st = st + 1 >= NSTAGE ? 0 : st + 1;
+    };
+    static_assert(NSTAGE == 3, "the k loop is unrolled over a ring of three stages");
+    for (int kt = 0; kt < nk; kt += NSTAGE) {
+      k_step(std::integral_constant<int, 0>{}, kt);
+      if (kt + 1 < nk) k_step(std::integral_constant<int, 1>{}, kt + 1);
+      if (kt + 2 < nk) k_step(std::integral_constant<int, 2>{}, kt + 2);
     }
 #undef GEMM_MFMA
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");     // the clamped tail requests must not outlive the workgroup's LDS
