@@ -303,13 +303,32 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
       else to_patch(std::false_type{});
       constexpr int RPI = 64 / CPR;                   // patch rows per store instruction
       const int rl = lane / CPR, c = lane % CPR;
-      half_t *pcol = P + n_in_plane + wn * WN + c * 8;
+      // Store instruction `it` takes patch rows it * RPI + rl.  No address arithmetic per instruction: the
+      // patch address is a fixed lane offset plus an immediate (rows RPI apart share their swizzle key, except
+      // that with 8 chunks per row every other instruction flips bit 2 of it), and the global address is a
+      // scalar base (64-row block, row group, column: wave-uniform) plus the fixed lane offset of (rl, c).
+      static_assert(CPR == 8 || CPR == 4, "patch rows of 128 or 64 bytes");
+      constexpr int FLIP = CPR == 8 ? 64 : 0;
+      const int lds0 = rl * (WN * 2) + ((c ^ patch_key<CPR>(rl)) << 4);
+      uint32_t goff = (uint32_t)(rl * d + c * 8) * 2u;
+      const char *gcol = (const char *)(P + n_in_plane + wn * WN);
+      // the two 64-row blocks of the patch in turn: all reads of a block first, then its stores
+      constexpr int NI = 64 / RPI;                    // store instructions per 64-row block
 #pragma unroll
-      for (int it = 0; it < 128 / RPI; ++it) {
-        const int row = it * RPI + rl;
-        const f16x8 v = *(const f16x8 *)(pb + row * (WN * 2) + ((c ^ patch_key<CPR>(row)) << 4));
-        const int rblk = row >= 64 ? b1 : b0;
-        if (rblk >= 0) __builtin_nontemporal_store(v, (f16x8 *)(pcol + ((int64_t)rblk * kRowAlign + (row & 63)) * d));
+      for (int hb = 0; hb < 2; ++hb) {
+        const int rblk = hb ? b1 : b0;
+        if (rblk < 0) continue;
+        const char *gblk = gcol + (int64_t)rblk * kRowAlign * d * 2;
+        f16x8 v[NI];
+#pragma unroll
+        for (int k = 0; k < NI; ++k) {
+          const int it = hb * NI + k;
+          v[k] = *(const f16x8 *)(pb + it * RPI * (WN * 2) + (lds0 ^ ((it & 1) ? FLIP : 0)));
+        }
+        asm volatile("" : "+v"(goff));   // keeps the widening of the offset next to the stores (scalar base + offset form)
+#pragma unroll
+        for (int k = 0; k < NI; ++k)
+          __builtin_nontemporal_store(v[k], (f16x8 *)(gblk + (int64_t)(k * RPI) * d * 2 + goff));
       }
     } else {
       // patch[WN features][128 tokens]; lane holds feature 32j + l32, tokens 32i + 16*lhalf + 0..15
@@ -330,13 +349,26 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
       }
       const int rl = lane >> 4, c = lane & 15;
       const int rblk = c >= 8 ? b1 : b0;
-      half_t *prow = P + (int64_t)(n_in_plane + wn * WN) * ws_rows + (int64_t)rblk * kRowAlign + (c & 7) * 8;
+      // Store instruction `it` takes feature rows 4 it + rl.  As above: the patch address is a fixed lane offset
+      // XOR a constant (the swizzle key of row 4 it + rl is that of rl XOR 4 it) plus an immediate, the global
+      // address a scalar base (feature row group) plus a fixed lane offset (row rl, token block and chunk of c).
+      const int lds0 = rl * 256 + ((c ^ rl) << 4);
+      uint32_t goff = (uint32_t)((int64_t)rl * ws_rows + (int64_t)(rblk < 0 ? 0 : rblk) * kRowAlign + (c & 7) * 8) * 2u;
+      const char *gfeat = (const char *)(P + (int64_t)(n_in_plane + wn * WN) * ws_rows);
       if (rblk >= 0) {
+        constexpr int NI = 8;                           // reads in flight before their stores
 #pragma unroll
-        for (int it = 0; it < WN / 4; ++it) {
-          const int fr = it * 4 + rl;
-          const f16x8 v = *(const f16x8 *)(pb + fr * 256 + (((c ^ fr) & 15) << 4));
-          __builtin_nontemporal_store(v, (f16x8 *)(prow + (int64_t)fr * ws_rows));
+        for (int i0 = 0; i0 < WN / 4; i0 += NI) {
+          f16x8 v[NI];
+#pragma unroll
+          for (int k = 0; k < NI; ++k) {
+            const int it = i0 + k;
+            v[k] = *(const f16x8 *)(pb + it * 1024 + (lds0 ^ (((4 * it) & 15) << 4)));
+          }
+          asm volatile("" : "+v"(goff));
+#pragma unroll
+          for (int k = 0; k < NI; ++k)
+            __builtin_nontemporal_store(v[k], (f16x8 *)(gfeat + (int64_t)(4 * (i0 + k)) * ws_rows * 2 + goff));
         }
       }
     }
