@@ -67,6 +67,13 @@ __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
   return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
 }
 
+// max(a, b, c) in one instruction
+__device__ __forceinline__ float max3_f32(float a, float b, float c) {
+  float d;
+  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
+  return d;
+}
+
 // eight attention weights -> fp16 B-operand fragment (v_cvt_pk_f16_f32, round to nearest even).
 // A weight beyond the fp16 range becomes inf; the output store saturates, so nothing non-finite is
 // ever written to the workspace.
@@ -313,12 +320,20 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
                 sacc[j][e] = 32 * j + 16 * (e >> 3) + (e & 7) < vis_lim ? sacc[j][e] : kNeg;
               }
           }
-          float mx[4];
+          // maximum of the lane's 32 logits as a tree of three-input maxima, 10 + 4 + 2 instructions.  (Written as
+          // instructions: for fmaxf on accumulator values the compiler first emits one canonicalising v_max_f32 per
+          // value, 53 instructions in all.)
+          float l1[10], l2[4];
 #pragma unroll
-          for (int c = 0; c < 4; ++c) mx[c] = fmaxf(sacc[0][c], sacc[1][c]);
+          for (int k = 0; k < 10; ++k) {
+            const int e = 3 * k;   // values 0..29 in the order sacc[0][0..15], sacc[1][0..13]
+            l1[k] = max3_f32(sacc[e >> 4][e & 15], sacc[(e + 1) >> 4][(e + 1) & 15], sacc[(e + 2) >> 4][(e + 2) & 15]);
+          }
 #pragma unroll
-          for (int e = 4; e < 16; ++e) mx[e & 3] = fmaxf(mx[e & 3], fmaxf(sacc[0][e], sacc[1][e]));
-          const float mt = fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3]));
+          for (int k = 0; k < 3; ++k) l2[k] = max3_f32(l1[3 * k], l1[3 * k + 1], l1[3 * k + 2]);
+          l2[3] = max3_f32(l1[9], sacc[1][14], sacc[1][15]);
+          const float l3 = max3_f32(l2[0], l2[1], l2[2]);
+          const float mt = max3_f32(l3, l2[3], l2[3]);
           const float m_new = fmaxf(m_run, pair_max(mt) * ts);
           // the accumulators are rescaled only when some row of the wavefront has a new maximum (rare after the
           // first tiles); the branch is uniform over the wavefront
