@@ -32,6 +32,27 @@
  *   - With dtype FLAME_GR_BF16 every embedding and weight pointer must be 16-byte aligned (the kernels
  *     read 8 elements at a time; rows are multiples of 128 bytes because d % 64 == 0); a misaligned
  *     pointer is INVALID_ARGUMENT.
+ *
+ * Arithmetic of the two element types
+ *   - FLAME_GR_F32: fp32 operands, fp32 accumulation, plain FMA kernels.
+ *   - FLAME_GR_BF16 names the STORAGE type at this boundary: embeddings, W1, b1, ln_g, ln_b, W2, b2 and w_s
+ *     arrive as bf16.  Inside, the matrix instructions run on IEEE binary16 (fp16) operands with fp32
+ *     accumulation: embeddings and projection matrices are converted bf16 -> fp16 once, and the
+ *     intermediates U, V, Q, K, O, the gated rows and the operand copy of the residual stream are stored as
+ *     fp16 (11 significant bits against the 8 of bf16: the deep workloads need them to stay inside the
+ *     2e-2 score tolerance).  The residual stream itself, LayerNorm statistics, SiLU / softmax arguments,
+ *     bias adds and the score head are fp32; rab, temperature and b_s are fp32 inputs.
+ *   - Range of that path.  Every fp16 store SATURATES at +-65504 (the largest finite fp16) instead of
+ *     producing inf, so the workspaces always hold finite values: the tiled kernels multiply rows outside
+ *     a query's mask by a zero weight, which is only harmless while those rows are finite.  Consequences
+ *     the caller must know: bf16 inputs and activations beyond +-65504 in magnitude are clamped silently
+ *     (the un-normalised SiLU attention sums up to L_i terms per output, so this is reachable with
+ *     embeddings of order 1e2 and long histories; the scores then stay finite but are no longer the
+ *     model's); weights below 2^-14 in magnitude become fp16 subnormals (absolute error <= 3e-8); and a
+ *     NaN in an input is NOT propagated faithfully: the saturating store turns it into -65504, so the
+ *     request that holds it gets finite but meaningless scores (a NaN candidate embedding still yields a
+ *     NaN score for that candidate through the fp32 residual stream).  In no case does a value of one
+ *     request, however large, change another request's scores.
  */
 #ifndef FLAME_GR_H
 #define FLAME_GR_H
@@ -53,6 +74,9 @@ typedef enum {
   FLAME_GR_UNSUPPORTED = -5        /* shape outside what the kernels are built for */
 } flame_gr_status;
 
+/* Element type of embeddings and weights at this boundary.  FLAME_GR_BF16 is a storage type: see "Arithmetic
+ * of the two element types" above for what the kernels compute in (fp16 operands, fp32 accumulation) and
+ * for the saturation at +-65504 that goes with it. */
 typedef enum { FLAME_GR_F32 = 0, FLAME_GR_BF16 = 1 } flame_gr_dtype;
 
 /* Attention weights of a query row r over its allowed keys c, with logit z_rc = alpha <Q_r,K_c> +
@@ -70,7 +94,8 @@ typedef struct {
   int32_t n_heads;       /* H */
   int32_t n_buckets;     /* relative-position buckets: power of two, >= 2 */
   int32_t max_rel_dist;  /* D: power of two >= n_buckets/2; distances >= D share the last bucket */
-  int32_t dtype;         /* flame_gr_dtype of embeddings and weights (rab and b_s are always fp32) */
+  int32_t dtype;         /* flame_gr_dtype of embeddings and weights (rab and b_s are always fp32); with
+                            FLAME_GR_BF16 the arithmetic inside is fp16 x fp16 -> fp32, stores saturate at +-65504 */
   float ln_eps;          /* LayerNorm epsilon; 0 selects 1e-6 */
   float attn_scale;      /* alpha; 0 selects 1.0 */
   int32_t max_requests;      /* capacity: requests per forward */
@@ -243,6 +268,15 @@ int flame_gr_host_mask(int32_t L, int32_t M, int32_t n_buckets, int32_t max_rel_
 int flame_gr_host_plan(const flame_gr_config *cfg, const int32_t *history_offsets,
                        const int32_t *cand_offsets, int32_t n_requests, int32_t *tok_off,
                        int32_t *n_segments, int32_t *seg, int32_t cap_segments);
+
+/* Rows of every per-token workspace that flame_gr_create allocates for this configuration (HOST output):
+ * max_total_tokens, plus room for padding each request's history and candidate part to multiples of 64
+ * rows, rounded up to 256, plus 256 spare rows.  The spare rows are never part of a plan: a batch whose
+ * padded rows (flame_gr_host_plan: row_start + padded lengths of the last segment) would reach into them
+ * is CAPACITY_EXCEEDED, which can only happen when max_seq_tokens splits requests (every chunk repeats the
+ * history).  Device memory per row: 4*d bytes (residual) + 12*d bytes (fp16 planes, output, operand copy)
+ * with FLAME_GR_BF16, 28*d with FLAME_GR_F32, plus 4*d*n_layers with kv_cache. */
+int flame_gr_host_workspace_rows(const flame_gr_config *cfg, int64_t *rows);
 
 /* Plan of the two-stage path: as flame_gr_host_plan, but with candidate rows reserved for
  * cand_capacity[i] (HOST int32 [n_requests]) candidates per request, the layout that flame_gr_prefill

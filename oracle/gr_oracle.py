@@ -250,8 +250,8 @@ def climber_request(cfg: dict, block_weights: List[Dict[str, np.ndarray]], head:
 
 
 # ----------------------------------------------------------------------------------------------
-# the same definition as scalar loops (tiny inputs only); shares nothing with the code above
-# except Python's math module
+# the same definition as scalar loops (tiny inputs only).  Of the code above it calls only `bucket_scalar`
+# (pinned on its own by hand-computed values); mask, positions, SiLU, softmax and LayerNorm are written out again
 # ----------------------------------------------------------------------------------------------
 def forward_request_loops(cfg: dict, w, hist, cand) -> List[float]:
     d, H, Ly = cfg["d_model"], cfg["n_heads"], cfg["n_layers"]

@@ -76,6 +76,8 @@ _lib.flame_gr_host_mask.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_int32, 
 _lib.flame_gr_host_mask.restype = C.c_int
 _lib.flame_gr_host_plan.argtypes = [C.POINTER(flame_gr_config), _i32p, _i32p, C.c_int32, _i32p, _i32p, _i32p, C.c_int32]
 _lib.flame_gr_host_plan.restype = C.c_int
+_lib.flame_gr_host_workspace_rows.argtypes = [C.POINTER(flame_gr_config), C.POINTER(C.c_int64)]
+_lib.flame_gr_host_workspace_rows.restype = C.c_int
 _lib.flame_gr_host_plan_reserved.argtypes = [C.POINTER(flame_gr_config), _i32p, _i32p, _i32p, C.c_int32, _i32p, _i32p, C.c_int32]
 _lib.flame_gr_host_plan_reserved.restype = C.c_int
 _lib.flame_gr_debug_capture.argtypes = [C.c_void_p, C.c_int32]
@@ -140,7 +142,7 @@ DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_submit_jagged"
 
 EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_forward_hidden", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
            "flame_gr_last_error",
-           "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan", "flame_gr_host_plan_reserved",
+           "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan", "flame_gr_host_plan_reserved", "flame_gr_host_workspace_rows",
            "flame_gr_debug_capture", "flame_gr_debug_stage", "flame_gr_debug_device_mask",
            "flame_gr_debug_profile", "flame_gr_debug_profile_read")
 
@@ -303,6 +305,12 @@ def flame_gr_host_plan(cfg: flame_gr_config, history_offsets, cand_offsets):
     _check(_lib.flame_gr_host_plan(C.byref(cfg), ho.ctypes.data_as(_i32p), co.ctypes.data_as(_i32p), n,
                                    tok.ctypes.data_as(_i32p), C.byref(nseg), seg.ctypes.data_as(_i32p), len(seg)))
     return tok, seg[:nseg.value]
+
+
+def flame_gr_host_workspace_rows(cfg: flame_gr_config) -> int:
+    rows = C.c_int64(0)
+    _check(_lib.flame_gr_host_workspace_rows(C.byref(cfg), C.byref(rows)))
+    return rows.value
 
 
 def flame_gr_host_plan_reserved(cfg: flame_gr_config, history_offsets, cand_offsets, cand_capacity):

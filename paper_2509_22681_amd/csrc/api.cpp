@@ -736,6 +736,15 @@ static int host_plan(const flame_gr_config *cfg_in, const int32_t *history_offse
   return rc;
 }
 
+int flame_gr_host_workspace_rows(const flame_gr_config *cfg_in, int64_t *rows) {
+  if (!cfg_in || !rows) { g_create_error = "cfg or rows is NULL"; return FLAME_GR_INVALID_ARGUMENT; }
+  std::string err;
+  const int rc = validate_config(*cfg_in, err);
+  if (rc) { g_create_error = err; return rc; }
+  *rows = workspace_rows(*cfg_in);
+  return FLAME_GR_OK;
+}
+
 int flame_gr_host_plan(const flame_gr_config *cfg_in, const int32_t *history_offsets, const int32_t *cand_offsets,
                        int32_t n_requests, int32_t *tok_off, int32_t *n_segments, int32_t *seg, int32_t cap_segments) {
   return host_plan(cfg_in, history_offsets, cand_offsets, nullptr, n_requests, tok_off, n_segments, seg, cap_segments);

@@ -68,7 +68,7 @@ void bucket_table(int32_t nb, int32_t D, int32_t *out) {
 
 int64_t workspace_rows(const flame_gr_config &c) {
   int64_t rows = (int64_t)c.max_total_tokens + 2ll * (kRowAlign - 1) * std::max(c.max_requests, 1);
-  rows = (rows + 255) / 256 * 256 + 256;  // one spare tile so that clamped tile loads stay inside
+  rows = (rows + 255) / 256 * 256 + kSpareRows;  // spare rows that no plan uses: whole-tile loads stay inside
   return rows;
 }
 
@@ -164,7 +164,10 @@ int build_plan(const flame_gr_config &cfg, const int32_t *hoff, const int32_t *c
     G.hblk_begin = (int32_t)p.hist_blocks.size();
     for (; si < p.segs.size() && p.segs[si].group == g; ++si) {
       Segment &s = p.segs[si];
-      if (row + s.Lp + s.Mp > ws_rows) return fail(FLAME_GR_CAPACITY_EXCEEDED, "padded batch does not fit the workspace sized at create");
+      // The last kSpareRows rows of the workspace stay out of every plan: key tiles of up to 128 rows are loaded
+      // whole, so the tile that starts inside the last segment may reach that far past its end.  (Unsplit
+      // batches within the create-time capacities always fit; a split batch repeats histories and may not.)
+      if (row + s.Lp + s.Mp > ws_rows - kSpareRows) return fail(FLAME_GR_CAPACITY_EXCEEDED, "padded batch does not fit the workspace sized at create");
       s.row_start = (int32_t)row;
       for (int32_t b = 0; b < s.Lp; b += kRowAlign) {
         p.hist_blocks.push_back((int32_t)p.blocks.size());

@@ -15,6 +15,7 @@
 namespace flame {
 
 constexpr int kRowAlign = 64;  // history part and candidate part of a segment start on multiples of this
+constexpr int kSpareRows = 256;  // rows at the end of every workspace that no plan places a segment in
 
 struct Segment {
   int32_t req;        // request index in the caller's batch

@@ -6,7 +6,10 @@ results are kept as text files under tests/golden/oracle_scores/, one per reques
 of the exact inputs (configuration, the request's embeddings, all weights).  This script is the only
 writer of those files:
 
-    python tests/oracle_cache.py [workload ...]
+    python tests/oracle_cache.py [--jobs J] [workload ...]
+
+(`--jobs J` spreads the requests of a workload over J single-threaded worker processes, most expensive
+request first; the arithmetic is `oracle.forward_request` either way.)
 
 A file whose key does not match the regenerated inputs is simply not found, and the tests then
 compute the values in place.
@@ -34,8 +37,8 @@ SAMPLED = {
     "tiny_f32": None,
     "uniform": None,
     "jagged": None,
-    "long": [0, 11],
-    "production": "spread",     # smallest, median and largest request by cost, plus two seeded picks
+    "long": None,
+    "production": None,
     "production_softmax": "spread",
 }
 
@@ -102,12 +105,41 @@ def request_scores(wl: W.Workload, i: int, verbose: bool = False) -> np.ndarray:
     return s
 
 
-def main(names):
+_worker_wl = {}
+
+
+def _worker(task):
+    name, i = task
+    wl = _worker_wl.get(name)
+    if wl is None:
+        _worker_wl.clear()
+        wl = _worker_wl[name] = W.make_workload(name)
+    request_scores(wl, i, verbose=True)
+    return i
+
+
+def main(names, jobs=1):
     for name in names:
-        wl = W.make_workload(name)
-        for i in sample_requests(wl, name):
-            request_scores(wl, i, verbose=True)
+        if jobs <= 1:
+            wl = W.make_workload(name)
+            for i in sample_requests(wl, name):
+                request_scores(wl, i, verbose=True)
+            continue
+        import multiprocessing as mp
+        lens = W.make_workload(name, lengths_only=True)
+        L, M = lens.L.astype(np.int64), lens.M.astype(np.int64)
+        todo = sorted(sample_requests(lens, name), key=lambda i: -int((L[i] + M[i]) ** 2))
+        for v in ("OMP_NUM_THREADS", "OPENBLAS_NUM_THREADS", "MKL_NUM_THREADS"):
+            os.environ[v] = "1"                    # inherited by the spawned workers
+        with mp.get_context("spawn").Pool(jobs) as pool:
+            for _ in pool.imap_unordered(_worker, [(name, i) for i in todo], chunksize=1):
+                pass
 
 
 if __name__ == "__main__":
-    main(sys.argv[1:] or list(SAMPLED))
+    args = sys.argv[1:]
+    jobs = 1
+    if args and args[0] == "--jobs":
+        jobs = int(args[1])
+        args = args[2:]
+    main(args or list(SAMPLED), jobs)

@@ -219,3 +219,35 @@ def test_block_ranges_match_the_oracle():
     for args in ((10, 0, 0), (10, 2, 2), (-1, 2, 0)):
         with pytest.raises(B.FlameGRError):
             B.flame_climber_block_range(*args)
+
+
+def test_split_batches_never_reach_the_spare_rows():
+    """Key tiles are loaded whole (up to 128 rows), so the last 256 rows of the workspace must stay outside
+    every plan.  Unsplit batches fit by construction; a split batch repeats its history per chunk and is
+    rejected as soon as its padded rows would reach into the spare rows."""
+    def pad(v):
+        return (v + 63) // 64 * 64
+    L, cap = 192, 256                      # every chunk: 192 history rows + up to 64 candidates = 256 padded rows
+    for total in (1024, 1536, 4096):
+        cfg = _cfg(max_requests=1, max_total_tokens=total, max_seq_tokens=cap)
+        ws = B.flame_gr_host_workspace_rows(cfg)
+        assert ws % 256 == 0 and ws >= total + 2 * 63 + 256
+        accepted = rejected = 0
+        for M in range(64, total - L + 1, 64):
+            ho, co = np.array([0, L], np.int32), np.array([0, M], np.int32)
+            try:
+                _, seg = B.flame_gr_host_plan(cfg, ho, co)
+            except B.FlameGRError as e:
+                assert e.code == -2
+                rejected += 1
+                continue
+            accepted += 1
+            end = max(int(s[4]) + pad(int(s[1])) + pad(int(s[3])) for s in seg)
+            assert end + 256 <= ws, (total, M, end, ws)
+            assert end == 256 * len(seg)
+        assert accepted > 0 and rejected > 0, (total, accepted, rejected)
+    # the same bound for unsplit batches at the capacity limit
+    cfg = _cfg(max_requests=4, max_total_tokens=1000)
+    ws = B.flame_gr_host_workspace_rows(cfg)
+    _, seg = B.flame_gr_host_plan(cfg, np.array([0, 1, 2, 3, 501], np.int32), np.array([0, 1, 2, 3, 499], np.int32))
+    assert max(int(s[4]) + pad(int(s[1])) + pad(int(s[3])) for s in seg) + 256 <= ws
