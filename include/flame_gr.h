@@ -301,8 +301,11 @@ int flame_gr_debug_capture(flame_gr_t *h, int32_t layer);
  * before LayerNorm) 5=X (residual stream after the layer).  Only valid if no request was split. */
 int flame_gr_debug_stage(flame_gr_t *h, int32_t which, float *host_out);
 
-/* Evaluate, on the device and with the very predicate and table the attention kernel uses, the
- * mask and bucket of one request of shape (L, M); HOST outputs as flame_gr_host_mask. */
+/* Evaluate on the device the mask and bucket of one request of shape (L, M); HOST outputs as
+ * flame_gr_host_mask.  This runs a small kernel of its own: it shares the visible-history rule and the
+ * bucket table with the attention kernels, not their tile-level masking (which key tiles a wavefront
+ * skips, where it applies the per-element predicate).  That logic is verified separately, by counting the
+ * visible keys per row through the attention kernels' output with indicator values. */
 int flame_gr_debug_device_mask(flame_gr_t *h, int32_t L, int32_t M, uint8_t *mask, int32_t *bucket);
 
 /* Per-kernel timing for measurements.  With enable != 0 every kernel launch of the following
