@@ -233,6 +233,37 @@ int flame_gr_prefill(flame_gr_t *h, const flame_gr_weights *weights, const void 
 int flame_gr_score(flame_gr_t *h, const flame_gr_weights *weights, const void *cand_emb,
                    const int32_t *cand_offsets, int32_t n_requests, float *scores, void *stream);
 
+/* For callers that cannot allocate: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  flame_gr_forward_static is flame_gr_forward without a handle: the same kernels, with every
+ * workspace (residual stream, activation planes, converted weights, bias and bucket tables, plan tables) carved
+ * out of one static device array of FLAME_GR_STATIC_SCRATCH_MIB MiB that the library's code object holds on each
+ * GPU it runs on until the process ends.  The call makes no hipMalloc / hipFree / hipHostMalloc, creates no
+ * stream or event, issues no memcpy or memset: plan tables travel as kernel arguments, the bucket table is
+ * computed on the device, and only kernels are enqueued on `stream` (so the call can be captured).  Host-side
+ * planning uses the C++ heap, as in flame_gr_forward.
+ *   cfg      as for flame_gr_create; the capacity fields (max_requests, max_total_tokens) are ignored: the
+ *            capacity is the static array.  n_streams > 1 and kv_cache are UNSUPPORTED
+ *   others   as for flame_gr_forward
+ * A batch and model that need more than the array (flame_gr_static_scratch_bytes tells how much: about
+ * 16*d bytes per padded row plus 10*d*d*n_layers bytes of converted weights with FLAME_GR_BF16) is
+ * CAPACITY_EXCEEDED, with the two sizes in the message; nothing is enqueued then.  The device address of the
+ * array is looked up once per device (hipGetSymbolAddress, with that device current) and kept.
+ * All calls on one GPU share that GPU's array, which keeps the last call's contents: a call rewrites every row
+ * it reads (and clears the spare rows behind its batch), so earlier calls cannot influence its scores, but two
+ * calls that overlap in time on one GPU (different streams, or the same graph launched twice concurrently)
+ * race on the array: serialise them.  Scores equal those of flame_gr_forward on the same inputs bit for bit.
+ * Errors are reported like those of flame_gr_create: flame_gr_last_error(NULL) on the calling thread. */
+#define FLAME_GR_STATIC_SCRATCH_MIB 64
+int flame_gr_forward_static(const flame_gr_config *cfg, const flame_gr_weights *weights,
+                            const void *history_emb, const int32_t *history_offsets,
+                            const void *cand_emb, const int32_t *cand_offsets,
+                            int32_t n_requests, float *scores, void *stream);
+
+/* Bytes of the static array that flame_gr_forward_static needs for this model and a batch of `padded_rows`
+ * workspace rows (the sum over requests of history and candidate lengths, each rounded up to a multiple of 64;
+ * with max_seq_tokens splitting, over chunks).  HOST arithmetic only. */
+int flame_gr_static_scratch_bytes(const flame_gr_config *cfg, int64_t padded_rows, int64_t *bytes);
+
 /* Release the handle and its workspaces (synchronises the device work of the handle first).
  * NULL is a no-op that returns 0. */
 int flame_gr_destroy(flame_gr_t *h);

@@ -57,6 +57,11 @@ _lib.flame_gr_forward.argtypes = [C.c_void_p, C.POINTER(flame_gr_weights), C.c_v
 _lib.flame_gr_forward.restype = C.c_int
 _lib.flame_gr_forward_hidden.argtypes = _lib.flame_gr_forward.argtypes
 _lib.flame_gr_forward_hidden.restype = C.c_int
+_lib.flame_gr_forward_static.argtypes = [C.POINTER(flame_gr_config), C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
+                                         C.c_int32, C.c_void_p, C.c_void_p]
+_lib.flame_gr_forward_static.restype = C.c_int
+_lib.flame_gr_static_scratch_bytes.argtypes = [C.POINTER(flame_gr_config), C.c_int64, C.POINTER(C.c_int64)]
+_lib.flame_gr_static_scratch_bytes.restype = C.c_int
 _lib.flame_gr_capture.argtypes = [C.c_void_p, C.c_int32, C.POINTER(flame_gr_weights), C.c_void_p, _i32p, C.c_void_p, _i32p,
                                   C.c_int32, C.c_void_p, C.c_void_p]
 _lib.flame_gr_capture.restype = C.c_int
@@ -140,7 +145,7 @@ CLIMBER_EXPORTS = ("flame_climber_head", "flame_climber_block_range", "flame_cli
 DSO_EXPORTS = ("flame_dso_create", "flame_dso_submit", "flame_dso_submit_jagged", "flame_dso_wait", "flame_dso_drain", "flame_dso_flush", "flame_dso_destroy",
                "flame_dso_last_error", "flame_dso_route", "flame_dso_stats")
 
-EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_forward_hidden", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
+EXPORTS = ("flame_gr_create", "flame_gr_forward", "flame_gr_forward_hidden", "flame_gr_forward_static", "flame_gr_static_scratch_bytes", "flame_gr_capture", "flame_gr_replay", "flame_gr_prefill", "flame_gr_score", "flame_gr_destroy",
            "flame_gr_last_error",
            "flame_gr_host_bucket_table", "flame_gr_host_mask", "flame_gr_host_plan", "flame_gr_host_plan_reserved", "flame_gr_host_workspace_rows",
            "flame_gr_debug_capture", "flame_gr_debug_stage", "flame_gr_debug_device_mask",
@@ -216,6 +221,26 @@ def flame_gr_forward(h, weights, history_emb, history_offsets, cand_emb, cand_of
     rc = _lib.flame_gr_forward(h, C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
                                co.ctypes.data_as(_i32p), n, _ptr(scores), C.c_void_p(sp))
     _check(rc, h)
+
+
+def flame_gr_forward_static(cfg: flame_gr_config, weights, history_emb, history_offsets, cand_emb, cand_offsets, scores,
+                            stream=None) -> None:
+    """flame_gr_forward without a handle, in the library's static device workspace (no allocation)."""
+    ws = weights if isinstance(weights, flame_gr_weights) else pack_weights(weights)
+    ho, co = _i32(history_offsets), _i32(cand_offsets)
+    n = len(ho) - 1
+    if len(co) - 1 != n:
+        raise ValueError("offset arrays differ in length")
+    sp = torch.cuda.current_stream().cuda_stream if stream is None else getattr(stream, "cuda_stream", stream)
+    rc = _lib.flame_gr_forward_static(C.byref(cfg), C.byref(ws), _ptr(history_emb), ho.ctypes.data_as(_i32p), _ptr(cand_emb),
+                                      co.ctypes.data_as(_i32p), n, _ptr(scores), C.c_void_p(sp))
+    _check(rc)
+
+
+def flame_gr_static_scratch_bytes(cfg: flame_gr_config, padded_rows: int) -> int:
+    out = C.c_int64(0)
+    _check(_lib.flame_gr_static_scratch_bytes(C.byref(cfg), padded_rows, C.byref(out)))
+    return out.value
 
 
 def _stream_ptr(stream) -> int:

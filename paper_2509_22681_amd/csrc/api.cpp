@@ -6,6 +6,7 @@
 
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <utility>
 #include <string>
@@ -355,6 +356,19 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
   return FLAME_GR_OK;
 }
 
+// Plan tables of a workspace of nblk 64-row blocks, back to back in one buffer.
+StageLayout stage_layout(size_t nblk) {
+  StageLayout lay{};
+  lay.blocks = 0;
+  lay.items = lay.blocks + nblk * sizeof(RowBlock);
+  lay.cand_items = lay.items + nblk * sizeof(AttnItem);
+  lay.cand_blocks = lay.cand_items + nblk * sizeof(AttnItem);
+  lay.hist_items = lay.cand_blocks + nblk * sizeof(int32_t);
+  lay.hist_blocks = lay.hist_items + nblk * sizeof(AttnItem);
+  lay.total = lay.hist_blocks + nblk * sizeof(int32_t);
+  return lay;
+}
+
 // The MFMA path reads embeddings and weights 16 bytes at a time.
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 bool pointers_aligned(const flame_gr *h, const flame_gr_weights *w, const void *hist, const void *cand) {
@@ -440,14 +454,7 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
     bucket_table(cfg.n_buckets, cfg.max_rel_dist, tab.data());
     CR(hipMemcpy(h->bucket_tab, tab.data(), tab.size() * sizeof(int32_t), hipMemcpyHostToDevice));
   }
-  const size_t nblk = rows / kRowAlign;
-  h->lay.blocks = 0;
-  h->lay.items = h->lay.blocks + nblk * sizeof(RowBlock);
-  h->lay.cand_items = h->lay.items + nblk * sizeof(AttnItem);
-  h->lay.cand_blocks = h->lay.cand_items + nblk * sizeof(AttnItem);
-  h->lay.hist_items = h->lay.cand_blocks + nblk * sizeof(int32_t);
-  h->lay.hist_blocks = h->lay.hist_items + nblk * sizeof(AttnItem);
-  h->lay.total = h->lay.hist_blocks + nblk * sizeof(int32_t);
+  h->lay = stage_layout(rows / kRowAlign);
   CR(hipMalloc(&h->stage_dev, h->lay.total));
   for (int i = 0; i < kStageSlots; ++i) {
     CR(hipHostMalloc((void **)&h->stage_host[i], h->lay.total, hipHostMallocDefault));
@@ -668,6 +675,173 @@ int flame_gr_score(flame_gr_t *h, const flame_gr_weights *w, const void *cand_em
   h->cap_valid = false;
   if (sumM == 0) return FLAME_GR_OK;
   return enqueue_pass(h, w, nullptr, cand_emb, scores, (hipStream_t)stream_v, PASS_CANDIDATES);
+}
+
+}  // extern "C"
+
+// ---------------------------------------------------------------------------------------------
+// The forward in a static workspace, for callers that cannot allocate.
+// ---------------------------------------------------------------------------------------------
+namespace {
+constexpr size_t kStaticScratchBytes = (size_t)FLAME_GR_STATIC_SCRATCH_MIB << 20;
+constexpr int kMaxDevices = 64;
+}  // namespace
+
+// Every workspace of flame_gr_forward_static lives here: one copy per GPU, held until the process ends.  On the
+// host this name is only a handle for hipGetSymbolAddress; kernels get the device address obtained there.
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+std::mutex g_scratch_mu;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+
+// Device address of this device's copy of `scratch` (looked up once per device, with that device current).
+int static_scratch_base(int dev, unsigned char **out) {
+  if (dev < 0 || dev >= kMaxDevices) { g_create_error = "device index out of range for the static workspace"; return FLAME_GR_UNSUPPORTED; }
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void *p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) {
+      g_create_error = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+      return FLAME_GR_HIP_ERROR;
+    }
+    g_scratch_ptr[dev] = (unsigned char *)p;
+  }
+  *out = g_scratch_ptr[dev];
+  return FLAME_GR_OK;
+}
+
+struct Carver {   // offsets of consecutive 256-byte aligned pieces
+  size_t off = 0;
+  size_t take(size_t bytes) { const size_t o = off; off = (off + bytes + 255) & ~(size_t)255; return o; }
+};
+
+}  // namespace
+
+extern "C" {
+
+int flame_gr_static_scratch_bytes(const flame_gr_config *cfg_in, int64_t padded_rows, int64_t *bytes) {
+  if (!cfg_in || !bytes || padded_rows < 0) { g_create_error = "cfg or bytes is NULL, or padded_rows < 0"; return FLAME_GR_INVALID_ARGUMENT; }
+  flame_gr_config cfg = *cfg_in;
+  cfg.max_requests = 0; cfg.max_total_tokens = 0;      // capacities play no part here
+  std::string err;
+  const int rc = validate_config(cfg, err);
+  if (rc) { g_create_error = err; return rc; }
+  const bool bf = cfg.dtype == FLAME_GR_BF16;
+  const size_t rows = (size_t)((padded_rows + 255) / 256 * 256 + kSpareRows), d = (size_t)cfg.d_model, e = bf ? 2 : 4;
+  const size_t L = (size_t)cfg.n_layers;
+  Carver c;
+  c.take(rows * d * sizeof(float));                         // X
+  c.take(4 * rows * d * e);                                 // U, V, Q, K
+  c.take(rows * d * e);                                     // O
+  if (!bf || !k3_fused_supported(cfg.d_model)) c.take(rows * d * e);   // G
+  if (bf) {
+    c.take(rows * d * e);                                   // Xh
+    c.take(L * 4 * d * d * e);                              // W1 as fp16, k-tile blocked
+    c.take(L * d * d * e);                                  // W2 as fp16 (blocked or fragment-packed)
+  }
+  c.take(L * (size_t)cfg.n_heads * (size_t)cfg.max_rel_dist * sizeof(float));   // bias by distance
+  c.take((size_t)cfg.max_rel_dist * sizeof(int32_t));       // bucket table
+  c.take(L * (size_t)cfg.n_heads * sizeof(float));          // softmax logit scales
+  c.take(stage_layout(rows / kRowAlign).total);             // plan tables
+  *bytes = (int64_t)c.off;
+  return FLAME_GR_OK;
+}
+
+int flame_gr_forward_static(const flame_gr_config *cfg_in, const flame_gr_weights *w, const void *history_emb,
+                            const int32_t *history_offsets, const void *cand_emb, const int32_t *cand_offsets,
+                            int32_t n_requests, float *scores, void *stream_v) {
+  auto bad = [&](const char *m) { g_create_error = m; return (int)FLAME_GR_INVALID_ARGUMENT; };
+  if (!cfg_in) return bad("cfg is NULL");
+  if (!w) return bad("weights is NULL");
+  if (n_requests < 0) return bad("n_requests < 0");
+  if (n_requests > 0 && (!history_offsets || !cand_offsets)) return bad("offset arrays are NULL");
+  flame_gr h;                                     // lives for this call only; owns nothing on the device
+  h.cfg = *cfg_in;
+  flame_gr_config &cfg = h.cfg;
+  if (cfg.ln_eps == 0.f) cfg.ln_eps = 1e-6f;
+  if (cfg.attn_scale == 0.f) cfg.attn_scale = 1.0f;
+  if (cfg.n_streams > 1 || cfg.kv_cache) { g_create_error = "the static workspace serves one stream and no K/V cache (n_streams <= 1, kv_cache = 0)"; return FLAME_GR_UNSUPPORTED; }
+  // the capacity of this entry point is the static workspace, not the capacity fields of the configuration
+  cfg.max_requests = n_requests;
+  cfg.max_total_tokens = n_requests ? history_offsets[n_requests] + cand_offsets[n_requests] : 0;
+  if (cfg.max_total_tokens < 0) return bad("offsets must be non-decreasing");
+  int rc = validate_config(cfg, g_create_error);
+  if (rc) return rc;
+  const bool bf = cfg.dtype == FLAME_GR_BF16;
+  h.n_groups = 1;
+  h.q_tile = bf ? kAttnQTileBf16 : kAttnQTileF32;
+  h.elt = bf ? 2 : 4;
+  rc = build_plan(cfg, history_offsets, cand_offsets, n_requests, h.q_tile, 1, (int64_t)1 << 40, h.plan, g_create_error);
+  if (rc) return rc;
+  const Plan &P = h.plan;
+  const int64_t sumL = n_requests ? history_offsets[n_requests] : 0, sumM = n_requests ? cand_offsets[n_requests] : 0;
+  if (sumL > 0 && !history_emb) return bad("history_emb is NULL");
+  if (sumM > 0 && (!cand_emb || !scores)) return bad("cand_emb or scores is NULL");
+  if (P.total_rows == 0) return FLAME_GR_OK;
+  if (!weights_complete(&h, w) || (cfg.attn_kind == FLAME_GR_ATTN_SOFTMAX && !w->temperature)) return bad("a weight pointer is NULL");
+  if (!pointers_aligned(&h, w, history_emb, cand_emb)) return bad("bf16 embeddings and weights must be 16-byte aligned");
+  // size check first: host arithmetic only
+  int64_t need = 0;
+  rc = flame_gr_static_scratch_bytes(&cfg, P.total_rows, &need);
+  if (rc) return rc;
+  if ((size_t)need > kStaticScratchBytes) {
+    g_create_error = "batch and model need " + std::to_string(need) + " bytes of workspace; the static workspace holds " +
+                     std::to_string(kStaticScratchBytes) + " (use a handle: flame_gr_create / flame_gr_forward)";
+    return FLAME_GR_CAPACITY_EXCEEDED;
+  }
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess) { g_create_error = "hipGetDevice failed"; return FLAME_GR_HIP_ERROR; }
+  unsigned char *base = nullptr;
+  rc = static_scratch_base(dev, &base);
+  if (rc) return rc;
+  // the same pieces, in the same order, as flame_gr_static_scratch_bytes
+  h.device = dev;
+  h.ws_rows = ((int64_t)P.total_rows + 255) / 256 * 256 + kSpareRows;
+  h.sh = Shape{cfg.d_model, cfg.n_heads, cfg.d_model / cfg.n_heads, cfg.n_layers, cfg.n_buckets,
+               cfg.max_rel_dist, cfg.ln_eps, cfg.attn_scale, h.ws_rows, cfg.attn_kind == FLAME_GR_ATTN_SOFTMAX ? 1 : 0,
+               cfg.latency_mode ? 1 : 0};
+  const size_t rows = (size_t)h.ws_rows, d = (size_t)cfg.d_model, e = h.elt, L = (size_t)cfg.n_layers;
+  Carver c;
+  h.X = (float *)(base + c.take(rows * d * sizeof(float)));
+  h.plane_bytes = rows * d * e;
+  h.planes = base + c.take(4 * h.plane_bytes);
+  h.O = base + c.take(rows * d * e);
+  if (!bf || !k3_fused_supported(cfg.d_model)) h.G = base + c.take(rows * d * e);
+  if (bf) {
+    h.Xb = base + c.take(rows * d * e);
+    h.W1h = base + c.take(L * 4 * d * d * e);
+    void *w2 = base + c.take(L * d * d * e);
+    h.W2h = w2;
+    h.W2p = w2;                                   // one of the two layouts is used, by the model width
+  }
+  h.bias = (float *)(base + c.take(L * (size_t)cfg.n_heads * (size_t)cfg.max_rel_dist * sizeof(float)));
+  h.bucket_tab = (int32_t *)(base + c.take((size_t)cfg.max_rel_dist * sizeof(int32_t)));
+  h.tscale = (float *)(base + c.take(L * (size_t)cfg.n_heads * sizeof(float)));
+  if (!h.sh.softmax) h.tscale = nullptr;
+  h.lay = stage_layout(rows / kRowAlign);
+  h.stage_dev = (char *)(base + c.take(h.lay.total));
+  if ((int64_t)c.off != need) { g_create_error = "internal: static workspace layout mismatch"; return FLAME_GR_HIP_ERROR; }
+  if (h.sh.latency && bf && attn_latency_setup(h.sh) != hipSuccess) { g_create_error = "attention kernel setup failed"; return FLAME_GR_HIP_ERROR; }
+  hipStream_t s = (hipStream_t)stream_v;
+  // plan tables as kernel arguments, bucket table computed on the device: no copies, no memsets, no events
+  launch_upload_words(P.blocks.data(), P.blocks.size() * sizeof(RowBlock), h.stage_dev + h.lay.blocks, s);
+  launch_upload_words(P.items.data(), P.items.size() * sizeof(AttnItem), h.stage_dev + h.lay.items, s);
+  launch_upload_words(P.cand_items.data(), P.cand_items.size() * sizeof(AttnItem), h.stage_dev + h.lay.cand_items, s);
+  launch_upload_words(P.cand_blocks.data(), P.cand_blocks.size() * sizeof(int32_t), h.stage_dev + h.lay.cand_blocks, s);
+  launch_bucket_table(cfg.n_buckets, cfg.max_rel_dist, h.bucket_tab, s);
+  derive_weights(&h, w, s);
+  // The array keeps the last call's contents, laid out for another batch: every row of this batch's blocks is
+  // rewritten by the kernels below, and the rows behind them, which whole-tile key loads may read, are cleared.
+  if (bf) launch_clear_spare((char *)h.planes + 3 * h.plane_bytes, (char *)h.planes + h.plane_bytes, cfg.d_model, h.ws_rows,
+                             P.total_rows, (int)(h.ws_rows - P.total_rows), s);
+  run_group(&h, *w, P.groups[0], history_emb, cand_emb, scores, s, PASS_FULL);
+  const hipError_t le = hipGetLastError();
+  h.magic = 0;
+  if (le != hipSuccess) { g_create_error = std::string("kernel launch: ") + hipGetErrorString(le); return FLAME_GR_HIP_ERROR; }
+  return FLAME_GR_OK;
 }
 
 // ---------------------------------------------------------------------------------------------

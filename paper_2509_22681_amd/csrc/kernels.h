@@ -41,6 +41,17 @@ void launch_logit_scale(const float *temperature, float *out, int n, float facto
 // hidden[(src_row + i) * d ..] = X[row] for the valid rows of every candidate block (fp32).
 void launch_gather_hidden(const float *X, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk, float *hidden,
                           int d, hipStream_t s);
+// bucket(delta) for delta in [0, D), computed on the device (the integers of plan.h's bucket_of)
+void launch_bucket_table(int n_buckets, int D, int32_t *out, hipStream_t s);
+// Host words -> device memory without a copy engine or staging buffer: the words travel as kernel arguments
+// (UploadWords::kWords per launch; bytes % 4 == 0).  For small tables on paths that may not allocate or copy.
+struct UploadWords {
+  static constexpr int kWords = 960;
+  uint32_t w[kWords];
+};
+void launch_upload_words(const void *host_src, size_t bytes, void *dst, hipStream_t s);
+// rows [row0, row0 + n) of the row-major K plane and of the feature-major V plane (d features) <- 0
+void launch_clear_spare(void *K, void *Vt, int d, int64_t ws_rows, int64_t row0, int n, hipStream_t s);
 // mask / bucket of one request evaluated with the device predicate (debug export).
 void launch_debug_mask(int L, int M, const int32_t *bucket_tab, int D, uint8_t *mask, int32_t *bucket,
                        hipStream_t s);

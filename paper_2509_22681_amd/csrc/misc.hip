@@ -239,6 +239,69 @@ void launch_scores(int dtype, const float *X, const void *w_s, float b_s, const 
 }
 
 // ---------------------------------------------------------------------------------------------
+// Helpers of the entry point that works in a static workspace (no allocation, no copies): the bucket
+// table computed on the device, plan tables delivered as kernel arguments, and the spare rows behind
+// a batch cleared (whole-tile key loads may read them; they must hold finite values).
+// ---------------------------------------------------------------------------------------------
+__device__ __forceinline__ int ilog2_dev(int v) { return 31 - __builtin_clz(v); }
+
+// Same integers as the host planner's bucket function (documented in flame_gr.h).
+__global__ __launch_bounds__(256) void bucket_table_kernel(int nb, int D, int32_t *__restrict__ out) {
+  const int half = nb / 2;
+  const int lo = ilog2_dev(half), hi = ilog2_dev(D);
+  const int octaves = hi > lo ? hi - lo : 0;
+  int sub = lo;
+  while (sub > 0 && octaves * (1 << sub) > half) --sub;
+  for (int t = blockIdx.x * 256 + threadIdx.x; t < D; t += gridDim.x * 256) {
+    int b = t;
+    if (t >= half) {
+      const int oct = ilog2_dev(t);
+      b = half + (oct - lo) * (1 << sub) + ((t - (1 << oct)) >> (oct - sub));
+    }
+    out[t] = b;
+  }
+}
+
+void launch_bucket_table(int n_buckets, int D, int32_t *out, hipStream_t s) {
+  const int grid = (D + 255) / 256 > 64 ? 64 : (D + 255) / 256;
+  bucket_table_kernel<<<grid, 256, 0, s>>>(n_buckets, D, out);
+}
+
+__global__ __launch_bounds__(256) void upload_words_kernel(UploadWords src, int n, uint32_t *__restrict__ dst) {
+  for (int i = threadIdx.x; i < n; i += 256) dst[i] = src.w[i];
+}
+
+void launch_upload_words(const void *host_src, size_t bytes, void *dst, hipStream_t s) {
+  const uint32_t *src = (const uint32_t *)host_src;
+  uint32_t *out = (uint32_t *)dst;
+  size_t n = bytes / 4;                        // every plan table is an array of 32-bit integers
+  while (n > 0) {
+    UploadWords u;
+    const int m = (int)(n < (size_t)UploadWords::kWords ? n : (size_t)UploadWords::kWords);
+    for (int i = 0; i < m; ++i) u.w[i] = src[i];
+    upload_words_kernel<<<1, 256, 0, s>>>(u, m, out);
+    src += m; out += m; n -= m;
+  }
+}
+
+// K plane rows [row0, row0 + n) and the same token columns of the feature-major V plane <- 0
+__global__ __launch_bounds__(256) void clear_spare_kernel(half_t *__restrict__ K, half_t *__restrict__ Vt, int d, int64_t ws_rows,
+                                                          int64_t row0, int n) {
+  const int64_t total = (int64_t)n * d;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+    K[row0 * d + i] = (half_t)0.f;
+    Vt[(i / n) * ws_rows + row0 + i % n] = (half_t)0.f;
+  }
+}
+
+void launch_clear_spare(void *K, void *Vt, int d, int64_t ws_rows, int64_t row0, int n, hipStream_t s) {
+  if (n <= 0) return;
+  const int64_t total = (int64_t)n * d;
+  const int grid = (int)((total + 255) / 256 > 1024 ? 1024 : (total + 255) / 256);
+  clear_spare_kernel<<<grid, 256, 0, s>>>((half_t *)K, (half_t *)Vt, d, ws_rows, row0, n);
+}
+
+// ---------------------------------------------------------------------------------------------
 // Debug: the mask predicate and bucket table as the attention kernels see them.
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void debug_mask_kernel(int L, int M, const int32_t *__restrict__ tab, int D,
