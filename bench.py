@@ -33,47 +33,151 @@ def attention_flops_per_layer(cfg, L, M):
     return full, last
 
 
-def stored_traffic(workload):
-    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload (two
-    counter runs, FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size), or None if there is
-    no such summary.  A stored measurement: counters cannot be read from inside this process."""
+def source_digest(*names):
+    """sha256 over the named kernel sources: what a stored counter measurement is tied to."""
+    import hashlib
+    h = hashlib.sha256()
+    for n in names:
+        with open(os.path.join(ROOT, "paper_2509_22681_amd", "csrc", n), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+ATTN_SOURCES = ("attn_mfma.hip", "device_common.h", "plan.cpp")
+
+
+def stored_traffic(workload, launches_per_step):
+    """HBM bytes per attention launch from the committed rocprofv3 --pmc summary of this workload (two counter
+    runs, FETCH_SIZE and WRITE_SIZE, scaled by a copy kernel of known size).  A stored measurement: counters cannot
+    be read from inside this process.  It is tied to the kernel it was taken on: if the attention kernel's sources
+    or the number of attention launches per forward differ from what the summary records, it is stale and not reported."""
     path = os.path.join(ROOT, "profiles", f"{workload}_attn_hbm_traffic.json")
     try:
         with open(path) as f:
-            return float(json.load(f)["bytes_per_launch"])
+            rec = json.load(f)
+        if rec.get("kernel_sources_sha256_16") != source_digest(*ATTN_SOURCES):
+            return None, "stored measurement is of another version of the attention kernel (source digest differs)"
+        if int(rec.get("attention_launches_per_forward", -1)) != int(launches_per_step):
+            return None, "stored measurement is of another launch sequence"
+        return float(rec["bytes_per_launch"]), None
+    except (OSError, KeyError, ValueError):
+        return None, "no stored measurement for this workload"
+
+
+def measured_mfma_peak_tflops():
+    """The matrix-instruction rate this chip sustains on random data fed from LDS (profiles/chip_microbench.json, the
+    output of paper_2509_22681_amd/chip_microbench): the clock drops under matrix load, so the published peak is
+    not reachable with real operands."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "chip_microbench.json")) as f:
+            return float(json.load(f)["mfma_f16_random_data_lds_fed_tflops"])
     except (OSError, KeyError, ValueError):
         return None
 
 
-def cpu_baseline(wl, budget_s=12.0):
-    """Time the fp64 oracle on the cheapest requests of the workload until the budget is used, then
-    scale to the whole batch by the cost model (algorithmic flops)."""
+def cpu_baseline(wl, budget_s=25.0):
+    """Time the fp64 oracle, as it stands, on a stratified sample of the workload's requests: the cheapest, the median
+    and the most expensive by the cost model plus two seeded picks, taken cheapest first until the time budget is
+    used (at least two).  The whole batch is extrapolated with a two-term model fitted to the timed requests,
+    t = a * projection flops + b * N^2 * heads * layers (the oracle evaluates the full N x N score matrix per head with
+    elementwise numpy, which does not scale like the flops), falling back to flops alone with fewer than two samples."""
     import oracle
-    from paper_2509_22681_amd import workloads as W
-    L, M = wl.L.astype(np.int64), wl.M.astype(np.int64)
-    cost = np.array([W.algorithmic_flops(wl.cfg, L[i:i + 1], M[i:i + 1], pruned=False) for i in range(wl.n_requests)])
+    L, M = wl.L.astype(np.float64), wl.M.astype(np.float64)
+    c = wl.cfg
+    N = L + M
+    gemm = c.n_layers * 10.0 * N * c.d_model ** 2
+    elem = c.n_layers * c.n_heads * N * N
+    cost = gemm + 4.0 * c.d_model * c.n_layers * N * N
     order = np.argsort(cost, kind="stable")
-    cfgd = wl.cfg.to_dict()
+    picks = [int(order[0]), int(order[len(order) // 2]), int(order[-1])]
+    for r in np.random.default_rng(2024).permutation(wl.n_requests):
+        if len(picks) >= min(5, wl.n_requests):
+            break
+        if int(r) not in picks:
+            picks.append(int(r))
+    picks = sorted(set(picks), key=lambda i: cost[i])
+    cfgd = c.to_dict()
     ho, co = wl.history_offsets, wl.cand_offsets
     t0 = time.perf_counter()
-    done, flops, nsc = [], 0.0, 0
-    for i in order:
-        oracle.forward_request(cfgd, wl.weights, wl.history_emb[ho[i]:ho[i + 1]], wl.cand_emb[co[i]:co[i + 1]])
-        done.append(int(i))
-        flops += cost[i]
-        nsc += int(M[i])
-        if time.perf_counter() - t0 > budget_s:
+    done, times = [], []
+    for i in picks:
+        if len(done) >= 2 and time.perf_counter() - t0 > budget_s:
             break
+        if len(done) >= 1:
+            # do not start a request that by itself would overrun the budget several times over
+            est = times[-1] * cost[i] / cost[done[-1]]
+            if len(done) >= 2 and time.perf_counter() - t0 + est > 2.0 * budget_s:
+                break
+        t1 = time.perf_counter()
+        oracle.forward_request(cfgd, wl.weights, wl.history_emb[ho[i]:ho[i + 1]], wl.cand_emb[co[i]:co[i + 1]])
+        times.append(time.perf_counter() - t1)
+        done.append(i)
     dt = time.perf_counter() - t0
-    total_flops = float(cost.sum())
-    est_total_s = dt * total_flops / flops
+    times = np.array(times)
+    if len(done) >= 2:
+        A = np.stack([gemm[done], elem[done]], 1)
+        coef, _ = __import__("scipy.optimize", fromlist=["nnls"]).nnls(A / times[:, None], np.ones(len(done)))
+        est_total_s = float(coef[0] * gemm.sum() + coef[1] * elem.sum())
+        model = "t = a * projection flops + b * N^2 * heads * layers, non-negative least squares on the timed requests"
+    else:
+        est_total_s = float(times.sum() * cost.sum() / cost[done].sum())
+        model = "flops"
+    nsc = int(M[done].sum())
     return {
         "value": float(M.sum()) / est_total_s, "unit": "candidate scores/s", "cores": len(os.sched_getaffinity(0)),
         "kind": "oracle",
-        "sample": f"{len(done)} cheapest of {wl.n_requests} requests ({nsc} scores, {flops:.3g} flop) in {dt:.1f} s; "
-                  f"whole batch extrapolated by flops to {est_total_s:.0f} s",
-        "oracle_gflops": flops / dt * 1e-9,
+        "sample": f"{len(done)} of {wl.n_requests} requests, stratified by cost (cheapest, median, most expensive, two seeded "
+                  f"picks; cheapest first within the time budget): requests {done} with (L, M) = "
+                  f"{[(int(L[i]), int(M[i])) for i in done]}, {nsc} scores in {dt:.1f} s; whole batch extrapolated to "
+                  f"{est_total_s:.0f} s ({model})",
+        "seconds_per_timed_request": [float(t) for t in times],
     }
+
+
+def small_workloads_leg(B, steps=50):
+    """The two small workloads of the benchmark definition (one tiny fp32 request; 32 uniform requests), which are
+    bound by launches rather than by arithmetic: eager forwards against replays of the forward captured as a HIP graph
+    (the explicit-shape executor of Section 3.3), both with weights declared static."""
+    import torch
+    from paper_2509_22681_amd import workloads as W
+    out = {}
+    for name in ("tiny_f32", "uniform"):
+        wl = W.make_workload(name)
+        dw, hist, cand = B.to_device(wl)
+        ws = B.pack_weights(dw)
+        scores = torch.zeros(int(wl.cand_offsets[-1]), device="cuda:0", dtype=torch.float32)
+        res = {}
+        for static in (0, 1):
+            h = B.flame_gr_create(B.config_for(wl, weights_static=static))
+            try:
+                for _ in range(5):
+                    B.flame_gr_forward(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    B.flame_gr_forward(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores)
+                torch.cuda.synchronize()
+                res["eager_ms_per_forward" + ("_weights_static" if static else "")] = (time.perf_counter() - t0) / steps * 1e3
+                if static:
+                    eager = scores.clone()
+                    s = torch.cuda.Stream()
+                    B.flame_gr_capture(h, ws, hist, wl.history_offsets, cand, wl.cand_offsets, scores, record_stream=s)
+                    for _ in range(5):
+                        B.flame_gr_replay(h, stream=s)
+                    s.synchronize()
+                    t0 = time.perf_counter()
+                    for _ in range(steps):
+                        B.flame_gr_replay(h, stream=s)
+                    s.synchronize()
+                    ms = (time.perf_counter() - t0) / steps * 1e3
+                    res["graph_replay_ms_per_forward"] = ms
+                    res["graph_replay_scores_per_s"] = scores.numel() / (ms * 1e-3)
+                    res["replay_equals_eager"] = bool(torch.equal(scores, eager))
+            finally:
+                torch.cuda.synchronize()
+                B.flame_gr_destroy(h)
+        out[name] = res
+    return out
 
 
 def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128, latency_mode=0):
@@ -376,6 +480,7 @@ def main():
     ap.add_argument("--no-mixed-traffic", action="store_true")
     ap.add_argument("--no-climber", action="store_true")
     ap.add_argument("--no-serving", action="store_true")
+    ap.add_argument("--no-small", action="store_true")
     ap.add_argument("--executors", type=int, default=4, help="executors of the mixed-traffic orchestrator")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy kernel of this many MiB "
@@ -443,6 +548,8 @@ def main():
     attn_avg_ms = attn_ms / max(attn_launches, 1)
     attn_flops_per_launch = attn_flops_per_step / cfg.n_layers
     achieved = attn_flops_per_launch / (attn_avg_ms * 1e-3) * 1e-12 if attn_avg_ms > 0 else 0.0
+    traffic, traffic_note = stored_traffic(args.workload, attn_launches / max(args.steps, 1))
+    measured_peak = measured_mfma_peak_tflops()
     out = {
         "metric": "candidate scores/sec + p50 request latency, 1 MI355X; % of bf16 MFMA peak",
         "value": n_scores / (dt / args.steps),
@@ -463,10 +570,17 @@ def main():
         "kernel_ms_per_step": {k: v[0] / args.steps for k, v in prof.items()},
         "roofline": {"kernel": "attn_mfma_kernel" if cfg.dtype == "bf16" else "attn_f32_kernel",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": stored_traffic(args.workload),
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "avg_launch_ms": attn_avg_ms, "launches": attn_launches,
                      "algorithmic_flops_per_launch": attn_flops_per_launch},
     }
+    if traffic_note:
+        out["roofline"]["traffic_note"] = traffic_note
+    if measured_peak:
+        # beside the published peak: what the matrix pipe sustains here on random operands (power-limited clock)
+        out["measured_mfma_peak_tflops_random_data"] = measured_peak
+        out["pct_of_measured_mfma_peak"] = 100.0 * flops_pruned / (dt / args.steps) / (measured_peak * 1e12)
+        out["roofline"]["frac_of_measured_mfma_peak"] = achieved / measured_peak
     if not args.no_latency:
         # request mode: one executor (pure per-request compute latency), then eight executors in a closed loop
         # (handles created with latency_mode = 1: the attention kernel's configuration for batches that do not
@@ -482,6 +596,8 @@ def main():
         out["mixed_traffic"] = mixed_traffic_leg(B, wl, dw, n_executors=args.executors)
     if not args.no_serving and cfg.dtype == "bf16":
         out["host_serving"] = production_serving_leg(B, wl, dw)
+    if not args.no_small:
+        out["small_workloads"] = small_workloads_leg(B)
     if not args.no_climber:
         out["climber"] = climber_leg(B)
     if not args.no_cpu_baseline:

@@ -117,6 +117,12 @@ typedef struct {
                                 query tile, which halves the chain of dependent key tiles that bounds a small
                                 batch's run time.  Partial sums are grouped differently: scores agree with
                                 mode 0 to rounding (same error bars), not bit for bit.  No effect on fp32 handles */
+  int32_t weights_static;    /* 0 = the caller may change the weight values between calls: every call derives its
+                                operand copies (fp16 conversions, packed layouts, the bias table by distance) again;
+                                1 = the caller promises that the device contents behind the weight pointers do not
+                                change while the same pointers are passed: the copies are derived on the first call
+                                and again only when a pointer of the weights struct differs from the previous call.
+                                Saves a few small kernels per call, which counts for single requests and small batches */
 } flame_gr_config;
 
 /* Model weights: device pointers, caller-owned, read-only, element type = config.dtype unless

@@ -40,7 +40,7 @@ class flame_gr_config(C.Structure):
                 ("ln_eps", C.c_float), ("attn_scale", C.c_float),
                 ("max_requests", C.c_int32), ("max_total_tokens", C.c_int32),
                 ("max_seq_tokens", C.c_int32), ("n_streams", C.c_int32), ("attn_kind", C.c_int32),
-                ("kv_cache", C.c_int32), ("latency_mode", C.c_int32)]
+                ("kv_cache", C.c_int32), ("latency_mode", C.c_int32), ("weights_static", C.c_int32)]
 
 
 class flame_gr_weights(C.Structure):
@@ -179,11 +179,12 @@ def _ptr(t) -> Optional[int]:
 
 def make_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dtype, *, ln_eps=1e-6, attn_scale=1.0,
                 max_requests=0, max_total_tokens=0, max_seq_tokens=0, n_streams=0, kv_cache=0,
-                attn_kind="silu", latency_mode=0) -> flame_gr_config:
+                attn_kind="silu", latency_mode=0, weights_static=0) -> flame_gr_config:
     dt = {"f32": FLAME_GR_F32, "bf16": FLAME_GR_BF16}.get(dtype, dtype)
     ak = {"silu": FLAME_GR_ATTN_SILU, "softmax": FLAME_GR_ATTN_SOFTMAX}.get(attn_kind, attn_kind)
     return flame_gr_config(n_layers, d_model, n_heads, n_buckets, max_rel_dist, dt, ln_eps, attn_scale,
-                           max_requests, max_total_tokens, max_seq_tokens, n_streams, ak, int(kv_cache), int(latency_mode))
+                           max_requests, max_total_tokens, max_seq_tokens, n_streams, ak, int(kv_cache), int(latency_mode),
+                           int(weights_static))
 
 
 # ---------------------------------------------------------------------------------------------
@@ -526,11 +527,11 @@ def to_device(workload, device="cuda:0"):
 
 
 def config_for(workload, *, n_streams=0, max_seq_tokens=0, slack_requests=0, kv_cache=0, slack_tokens=0,
-               latency_mode=0) -> flame_gr_config:
+               latency_mode=0, weights_static=0) -> flame_gr_config:
     c = workload.cfg
     tot = int(workload.history_offsets[-1]) + int(workload.cand_offsets[-1])
     return make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype,
                        ln_eps=c.ln_eps, attn_scale=c.attn_scale,
                        max_requests=workload.n_requests + slack_requests, max_total_tokens=tot + slack_tokens,
                        max_seq_tokens=max_seq_tokens, n_streams=n_streams, kv_cache=kv_cache,
-                       attn_kind=getattr(c, "attn_kind", "silu"), latency_mode=latency_mode)
+                       attn_kind=getattr(c, "attn_kind", "silu"), latency_mode=latency_mode, weights_static=weights_static)

@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libflame_gr.so")
+MICROBENCH = os.path.join(HERE, "chip_microbench")
 SOURCES = ["api.cpp", "plan.cpp", "dso.cpp", "misc.hip", "kernels_f32.hip", "gemm_mfma.hip", "attn_mfma.hip", "k3_mfma.hip", "climber_head.hip"]
 # packed fp32 VALU instructions are switched off on purpose: the compiler forms them by itself from plain float
 # code and some of their forms have given wrong results on this hardware
@@ -47,6 +48,10 @@ def build(verbose: bool = True, jobs: int = 6) -> str:
     subprocess.run(cmd, check=True)
     if verbose:
         sys.stderr.write(f"[build] wrote {LIB}\n")
+    # the box microbenchmarks (a standalone program: profiles/chip_microbench.md is its output)
+    subprocess.run([hipcc, *FLAGS, *VGPR_FORM, os.path.join(CSRC, "chip_microbench.hip"), "-o", MICROBENCH], check=True)
+    if verbose:
+        sys.stderr.write(f"[build] wrote {MICROBENCH}\n")
     return LIB
 
 

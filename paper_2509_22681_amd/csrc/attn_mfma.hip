@@ -54,24 +54,15 @@ static_assert(QT == 128, "4 groups of 32 query rows");
 constexpr int NSTAGE = 3;           // LDS stages (ring)
 constexpr int KH = 64;              // keys per half tile (one pass of the register-level loop)
 
-// SiLU for small arguments.  silu(x) - x/2 is even: silu(x) = x/2 + x^2 r(x^2) with
-// r(u) ~ a1 + a3 u + a5 u^2 (weighted least-squares fit of (silu(x) - x/2)/x^2 on [-2, 2], approximation
-// error below 5.3e-4 at |x| = 2 and below 1e-4 for |x| <= 1.5).  On the halved logit s = x/2, with t = s^2:
+// SiLU for small arguments: the polynomial of device_common.h, silu(x) = x/2 + x^2 (a1 + a3 x^2 + a5 x^4).  On the halved
+// logit s = x/2, with t = s^2:
 //   silu(x) = s + q,   q = t (4 a1 + 16 a3 t + 64 a5 t^2).
 // t and the bracket are evaluated in packed fp16 (one multiply and two fused multiply-adds per pair of
 // weights); the last step is a mixed-precision fused multiply-add per weight, fp16 t times fp16 bracket
 // plus the fp32 logit itself, rounded to fp16 once, like the weight of the exact route.
-constexpr float kPolyA1 = 0.24916259f, kPolyA3 = -0.01916112f, kPolyA5 = 0.00112581f;
 constexpr float kPolyT2 = 1.0f;                                  // bound on t = s^2  (|x| <= 2)
 __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
   return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
-}
-
-// max(a, b, c) in one instruction
-__device__ __forceinline__ float max3_f32(float a, float b, float c) {
-  float d;
-  asm("v_max3_f32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "v"(b), "v"(c));
-  return d;
 }
 
 // eight attention weights -> fp16 B-operand fragment (v_cvt_pk_f16_f32, round to nearest even).

@@ -265,6 +265,7 @@ int flame_dso_create(const flame_gr_config *model, const flame_gr_weights *weigh
     c.max_seq_tokens = 0;
     c.n_streams = 0;
     c.kv_cache = 0;
+    c.weights_static = 1;     // the orchestrator's weights are fixed at its creation
     int rc = flame_gr_create(&c, &e.h);
     if (rc) return fail(rc, std::string("executor create: ") + flame_gr_last_error(nullptr));
     const size_t in_bytes = ((size_t)d->max_batch * d->L + e.cap) * row;

@@ -27,6 +27,7 @@ int validate_config(const flame_gr_config &c, std::string &err) {
   if (c.n_streams < 0 || c.n_streams > 16) return bad("n_streams must be in [0, 16]");
   if (c.kv_cache != 0 && c.kv_cache != 1) return bad("kv_cache must be 0 or 1");
   if (c.latency_mode != 0 && c.latency_mode != 1) return bad("latency_mode must be 0 or 1");
+  if (c.weights_static != 0 && c.weights_static != 1) return bad("weights_static must be 0 or 1");
   if (c.attn_kind != FLAME_GR_ATTN_SILU && c.attn_kind != FLAME_GR_ATTN_SOFTMAX) return bad("attn_kind must be FLAME_GR_ATTN_SILU or FLAME_GR_ATTN_SOFTMAX");
   if (c.kv_cache && c.dtype != FLAME_GR_BF16) {
     err = "the two-stage path (kv_cache) is built for the bf16 kernels only";

@@ -26,6 +26,10 @@ HOT = {
     "d512": dict(L=[3001, 129], M=[333, 65], d=512, H=8, n_layers=2, n_buckets=128, max_rel_dist=4096, seed=11),
     # the long workload's table: 512 buckets, D = 16384, distances reach the log-spaced half (>= 256) and beyond 4096
     "table512": dict(L=[4100], M=[70], d=512, H=8, n_layers=2, n_buckets=512, max_rel_dist=16384, seed=12),
+    # more than 128 row blocks in one launch: the one-workgroup-per-row-block instance of the fused output projection
+    # that the large benchmark batches run (smaller launches split a row block over two or four workgroups)
+    "many_rows": dict(L=[1500, 1700, 1300, 1901, 1600, 300], M=[100, 65, 200, 31, 129, 700], d=512, H=8, n_layers=2,
+                      n_buckets=128, max_rel_dist=2048, seed=13),
 }
 
 
