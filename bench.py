@@ -481,6 +481,9 @@ def main():
     ap.add_argument("--no-climber", action="store_true")
     ap.add_argument("--no-serving", action="store_true")
     ap.add_argument("--no-small", action="store_true")
+    ap.add_argument("--zero-embeddings", action="store_true",
+                    help="timing probe: all embeddings zero (same kernels, same launches, operands that toggle no bits); the "
+                         "chip's clock under matrix load depends on the operand data, and so does every time measured here")
     ap.add_argument("--executors", type=int, default=4, help="executors of the mixed-traffic orchestrator")
     ap.add_argument("--calibration-copy-mib", type=int, default=0,
                     help="before the timed region, run one plain device-to-device copy kernel of this many MiB "
@@ -499,6 +502,9 @@ def main():
     wl = W.make_workload(args.workload)
     cfg = wl.cfg
     dw, hist, cand = B.to_device(wl)
+    if args.zero_embeddings:
+        hist.zero_()
+        cand.zero_()
     ws = B.pack_weights(dw)
     n_scores = int(wl.cand_offsets[-1])
     scores = torch.zeros(n_scores, device="cuda:0", dtype=torch.float32)
@@ -559,7 +565,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         # arithmetic type of the MFMA path: fp16 operands with fp32 accumulation (embeddings and weights
         # are bf16 in HBM at the boundary); the fp32 workload computes in fp32
-        "dtype": "f16" if cfg.dtype == "bf16" else "f32", "storage_dtype": cfg.dtype, "data": "synthetic",
+        "dtype": "f16" if cfg.dtype == "bf16" else "f32", "storage_dtype": cfg.dtype, "data": "synthetic" if not args.zero_embeddings else "synthetic lengths, ALL-ZERO embeddings (timing probe, not a result)",
         "config": {"workload": args.workload, "requests": wl.n_requests, "sum_L": int(wl.L.sum()), "sum_M": n_scores,
                    "d_model": cfg.d_model, "n_heads": cfg.n_heads, "n_layers": cfg.n_layers,
                    "batcher_streams": max(args.streams, 1)},

@@ -10,3 +10,16 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu on the GPU box)")
+
+
+def progress(msg: str) -> None:
+    """One line into gpurun_out/pytest_progress.log (created on demand): long GPU tests say where they are, also when
+    pytest captures their output, so that a slow step is not taken for a hang by whoever watches the run."""
+    import time
+    try:
+        d = os.path.join(ROOT, "gpurun_out")
+        os.makedirs(d, exist_ok=True)
+        with open(os.path.join(d, "pytest_progress.log"), "a") as f:
+            f.write(f"{time.strftime('%H:%M:%S')} {msg}\n")
+    except OSError:
+        pass

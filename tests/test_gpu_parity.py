@@ -11,6 +11,7 @@ import pytest
 
 import oracle
 from paper_2509_22681_amd import workloads as W
+from tests.conftest import progress
 from tests.oracle_cache import request_scores, sample_requests
 
 pytestmark = pytest.mark.gpu
@@ -192,14 +193,19 @@ def workload_stats(B, name):
     """GPU scores of the whole named workload against the stored oracle scores of every request (computed once)."""
     if name in _workload_stats:
         return _workload_stats[name]
+    progress(f"workload_stats {name}: generating inputs")
     wl = W.make_workload(name)
+    progress(f"workload_stats {name}: forward on the GPU")
     g, _ = run_gpu(B, wl)
+    progress(f"workload_stats {name}: comparing with the stored oracle scores")
     assert np.isfinite(g).all()
     co = wl.cand_offsets
     picks = sample_requests(wl, name)
     assert picks == list(range(wl.n_requests))          # all requests, not a sample
     worst, strict_max, near_zero, rels, n_scores, n_over, worst_rms = 0.0, 0.0, 0, [], 0, 0, 0.0
     for i in picks:
+        if i % 32 == 31:
+            progress(f"workload_stats {name}: request {i + 1} of {len(picks)}")
         o = request_scores(wl, i)
         gi = g[co[i]:co[i + 1]]
         e = score_err(gi, o)
