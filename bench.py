@@ -104,9 +104,9 @@ def cpu_baseline(wl, budget_s=25.0):
         if len(done) >= 2 and time.perf_counter() - t0 > budget_s:
             break
         if len(done) >= 1:
-            # do not start a request that by itself would overrun the budget several times over
+            # do not start a request that would carry the sample well past the budget
             est = times[-1] * cost[i] / cost[done[-1]]
-            if len(done) >= 2 and time.perf_counter() - t0 + est > 2.0 * budget_s:
+            if len(done) >= 2 and time.perf_counter() - t0 + est > 1.2 * budget_s:
                 break
         t1 = time.perf_counter()
         oracle.forward_request(cfgd, wl.weights, wl.history_emb[ho[i]:ho[i + 1]], wl.cand_emb[co[i]:co[i + 1]])

@@ -38,10 +38,10 @@
  *   - FLAME_GR_BF16 names the STORAGE type at this boundary: embeddings, W1, b1, ln_g, ln_b, W2, b2 and w_s
  *     arrive as bf16.  Inside, the matrix instructions run on IEEE binary16 (fp16) operands with fp32
  *     accumulation: embeddings and projection matrices are converted bf16 -> fp16 once, and the
- *     intermediates U, V, Q, K, O, the gated rows and the operand copy of the residual stream are stored as
- *     fp16 (11 significant bits against the 8 of bf16: the deep workloads need them to stay inside the
- *     2e-2 score tolerance).  The residual stream itself, LayerNorm statistics, SiLU / softmax arguments,
- *     bias adds and the score head are fp32; rab, temperature and b_s are fp32 inputs.
+ *     intermediates U, V, Q, K, O and the gated rows are stored as fp16 (11 significant bits against the 8 of
+ *     bf16: the deep workloads need them).  The residual stream is held as TWO fp16 words per element, fp16(X) (which is
+ *     also the projection's operand) and fp16(X - fp16(X)): 22 significant bits, added up in fp32.  LayerNorm
+ *     statistics, SiLU / softmax arguments, bias adds and the score head are fp32; rab, temperature and b_s are fp32 inputs.
  *   - Range of that path.  Every fp16 store SATURATES at +-65504 (the largest finite fp16) instead of
  *     producing inf, so the workspaces always hold finite values: the tiled kernels multiply rows outside
  *     a query's mask by a zero weight, which is only harmless while those rows are finite.  Consequences
@@ -50,8 +50,7 @@
  *     embeddings of order 1e2 and long histories; the scores then stay finite but are no longer the
  *     model's); weights below 2^-14 in magnitude become fp16 subnormals (absolute error <= 3e-8); and a
  *     NaN in an input is NOT propagated faithfully: the saturating store turns it into -65504, so the
- *     request that holds it gets finite but meaningless scores (a NaN candidate embedding still yields a
- *     NaN score for that candidate through the fp32 residual stream).  In no case does a value of one
+ *     request that holds it gets finite but meaningless scores.  In no case does a value of one
  *     request, however large, change another request's scores.
  */
 #ifndef FLAME_GR_H
@@ -251,7 +250,7 @@ int flame_gr_score(flame_gr_t *h, const flame_gr_weights *weights, const void *c
  *            capacity is the static array.  n_streams > 1 and kv_cache are UNSUPPORTED
  *   others   as for flame_gr_forward
  * A batch and model that need more than the array (flame_gr_static_scratch_bytes tells how much: about
- * 16*d bytes per padded row plus 10*d*d*n_layers bytes of converted weights with FLAME_GR_BF16) is
+ * 14*d bytes per padded row plus 10*d*d*n_layers bytes of converted weights with FLAME_GR_BF16) is
  * CAPACITY_EXCEEDED, with the two sizes in the message; nothing is enqueued then.  The device address of the
  * array is looked up once per device (hipGetSymbolAddress, with that device current) and kept.
  * All calls on one GPU share that GPU's array, which keeps the last call's contents: a call rewrites every row
@@ -311,8 +310,9 @@ int flame_gr_host_plan(const flame_gr_config *cfg, const int32_t *history_offset
  * rows, rounded up to 256, plus 256 spare rows.  The spare rows are never part of a plan: a batch whose
  * padded rows (flame_gr_host_plan: row_start + padded lengths of the last segment) would reach into them
  * is CAPACITY_EXCEEDED, which can only happen when max_seq_tokens splits requests (every chunk repeats the
- * history).  Device memory per row: 4*d bytes (residual) + 12*d bytes (fp16 planes, output, operand copy)
- * with FLAME_GR_BF16, 28*d with FLAME_GR_F32, plus 4*d*n_layers with kv_cache. */
+ * history).  Device memory per row with FLAME_GR_BF16: 14*d bytes (the residual as two
+ * fp16 words, four fp16 planes, the attention output; 16*d for model widths whose output projection is not fused),
+ * 28*d with FLAME_GR_F32, plus 4*d*n_layers with kv_cache. */
 int flame_gr_host_workspace_rows(const flame_gr_config *cfg, int64_t *rows);
 
 /* Plan of the two-stage path: as flame_gr_host_plan, but with candidate rows reserved for

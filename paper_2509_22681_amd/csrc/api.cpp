@@ -58,8 +58,9 @@ struct flame_gr {
   size_t elt = 4;
   std::string err;
   // workspaces (device)
-  float *X = nullptr;
-  void *Xb = nullptr, *planes = nullptr, *O = nullptr, *G = nullptr;   // Xb: fp16 copy of X (MFMA path)
+  float *X = nullptr;                                                    // residual stream, fp32 path
+  void *Xb = nullptr, *Xl = nullptr;                                     // residual stream, MFMA path: fp16(X) (k-tile blocked) and fp16(X - Xb)
+  void *planes = nullptr, *O = nullptr, *G = nullptr;
   void *W1h = nullptr, *W2h = nullptr, *W2p = nullptr;                   // fp16 copies of the projection matrices (W2p: fragment-major)
   float *bias = nullptr;
   float *tscale = nullptr;                                               // softmax: logit scale per layer and head
@@ -139,7 +140,7 @@ float half_bits_to_float(uint16_t b) {
 }
 
 void free_all(flame_gr *h) {
-  (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->planes); (void)hipFree(h->kv); (void)hipFree(h->O); (void)hipFree(h->G);
+  (void)hipFree(h->X); (void)hipFree(h->Xb); (void)hipFree(h->Xl); (void)hipFree(h->planes); (void)hipFree(h->kv); (void)hipFree(h->O); (void)hipFree(h->G);
   (void)hipFree(h->bias); (void)hipFree(h->tscale); (void)hipFree(h->bucket_tab); (void)hipFree(h->stage_dev);
   (void)hipFree(h->W1h); (void)hipFree(h->W2h); (void)hipFree(h->W2p);
   (void)hipFree(h->cap_planes); (void)hipFree(h->cap_O); (void)hipFree(h->cap_X);
@@ -255,14 +256,14 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
     const int bf = mode == PASS_FULL && !last ? G.blk_begin : 0;
     if (dt == FLAME_GR_BF16 && k3_fused_supported(d)) {
       Timed t(h, KIND_OUTPROJ, s);
-      launch_k3_fused(h->O, planes, lg, lb, (const char *)h->W2p + (size_t)l * d * d * e, b2, h->X, h->Xb, blocks, bl, nb, bf, sh, s);
+      launch_k3_fused(h->O, planes, lg, lb, (const char *)h->W2p + (size_t)l * d * d * e, b2, h->Xb, h->Xl, l == 0, blocks, bl, nb, bf, sh, s);
     } else {
       {
         Timed t(h, KIND_LNGATE, s);
         launch_ln_gate(dt, h->O, planes, lg, lb, h->G, blocks, bl, nb, bf, d, sh.eps, s);
       }
       Timed t(h, KIND_OUTPROJ, s);
-      if (dt == FLAME_GR_BF16) launch_outproj_bf16(h->G, w2, b2, h->X, h->Xb, bl, nb, bf, sh, s);
+      if (dt == FLAME_GR_BF16) launch_outproj_bf16(h->G, w2, b2, h->Xb, h->Xl, l == 0, bl, nb, bf, sh, s);
       else launch_outproj_f32((const float *)h->G, (const float *)w2, (const float *)b2, h->X, bl, nb, bf, sh, s);
     }
     if (capture && h->cap_planes) {
@@ -278,14 +279,15 @@ void run_group(flame_gr *h, const flame_gr_weights &w, const Group &G, const voi
         }
       }
       (void)hipMemcpyAsync((char *)h->cap_O + r0 * e, (char *)h->O + r0 * e, nr * e, hipMemcpyDeviceToDevice, s);
-      (void)hipMemcpyAsync(h->cap_X + r0, h->X + r0, nr * sizeof(float), hipMemcpyDeviceToDevice, s);
+      if (dt == FLAME_GR_BF16) launch_residual_to_f32(h->Xb, h->Xl, h->cap_X, G.row_begin, G.row_end, d, s);
+      else (void)hipMemcpyAsync(h->cap_X + r0, h->X + r0, nr * sizeof(float), hipMemcpyDeviceToDevice, s);
     }
   }
   if (mode == PASS_HISTORY) return;
   {
     Timed t(h, KIND_SCORE, s);
-    if (hidden) launch_gather_hidden(h->X, blocks, cl, n_cblk, hidden, d, s);
-    else launch_scores(dt, h->X, w.w_s, w.b_s, blocks, cl, n_cblk, scores, d, s);
+    if (hidden) launch_gather_hidden(h->X, h->Xb, h->Xl, blocks, cl, n_cblk, hidden, d, s);
+    else launch_scores(dt, h->X, h->Xb, h->Xl, w.w_s, w.b_s, blocks, cl, n_cblk, scores, d, s);
   }
 }
 
@@ -436,14 +438,17 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   CR(hipGetDevice(&h->device));
   if (h->sh.latency && cfg.dtype == FLAME_GR_BF16) CR(attn_latency_setup(h->sh));
   const size_t rows = (size_t)h->ws_rows, d = (size_t)cfg.d_model, e = h->elt;
-  CR(hipMalloc(&h->X, rows * d * sizeof(float)));
+  const bool mfma_path = cfg.dtype == FLAME_GR_BF16;
+  if (!mfma_path) CR(hipMalloc(&h->X, rows * d * sizeof(float)));
   h->plane_bytes = rows * d * e;
   CR(hipMalloc(&h->planes, 4 * h->plane_bytes));
   if (cfg.kv_cache) CR(hipMalloc((void **)&h->kv, (size_t)cfg.n_layers * 2 * h->plane_bytes));
   CR(hipMalloc(&h->O, rows * d * e));
-  CR(hipMalloc(&h->G, rows * d * e));
-  if (cfg.dtype == FLAME_GR_BF16) {
+  const bool need_g = !mfma_path || !k3_fused_supported(cfg.d_model);      // the fused K3 keeps the gated rows in LDS
+  if (need_g) CR(hipMalloc(&h->G, rows * d * e));
+  if (mfma_path) {
     CR(hipMalloc(&h->Xb, rows * d * e));
+    CR(hipMalloc(&h->Xl, rows * d * e));
     CR(hipMalloc(&h->W1h, (size_t)cfg.n_layers * 4 * d * d * e));
     CR(hipMalloc(&h->W2h, (size_t)cfg.n_layers * d * d * e));
     CR(hipMalloc(&h->W2p, (size_t)cfg.n_layers * d * d * e));
@@ -453,12 +458,13 @@ int flame_gr_create(const flame_gr_config *cfg_in, flame_gr_t **out) {
   if (h->sh.softmax) CR(hipMalloc(&h->tscale, (size_t)cfg.n_layers * cfg.n_heads * sizeof(float)));
   // Every workspace starts finite: rows that a batch leaves as padding are read (and multiplied
   // by zero weights) by the tiled kernels.
-  CR(hipMemset(h->X, 0, rows * d * sizeof(float)));
+  if (h->X) CR(hipMemset(h->X, 0, rows * d * sizeof(float)));
   CR(hipMemset(h->planes, 0, 4 * h->plane_bytes));
   if (h->kv) CR(hipMemset(h->kv, 0, (size_t)cfg.n_layers * 2 * h->plane_bytes));
   CR(hipMemset(h->O, 0, rows * d * e));
-  CR(hipMemset(h->G, 0, rows * d * e));
+  if (h->G) CR(hipMemset(h->G, 0, rows * d * e));
   if (h->Xb) CR(hipMemset(h->Xb, 0, rows * d * e));
+  if (h->Xl) CR(hipMemset(h->Xl, 0, rows * d * e));
   {
     std::vector<int32_t> tab(cfg.max_rel_dist);
     bucket_table(cfg.n_buckets, cfg.max_rel_dist, tab.data());
@@ -743,12 +749,11 @@ int flame_gr_static_scratch_bytes(const flame_gr_config *cfg_in, int64_t padded_
   const size_t rows = (size_t)((padded_rows + 255) / 256 * 256 + kSpareRows), d = (size_t)cfg.d_model, e = bf ? 2 : 4;
   const size_t L = (size_t)cfg.n_layers;
   Carver c;
-  c.take(rows * d * sizeof(float));                         // X
+  c.take(bf ? 2 * rows * d * e : rows * d * sizeof(float)); // residual: Xh and Xl (MFMA path) or fp32 X
   c.take(4 * rows * d * e);                                 // U, V, Q, K
   c.take(rows * d * e);                                     // O
   if (!bf || !k3_fused_supported(cfg.d_model)) c.take(rows * d * e);   // G
   if (bf) {
-    c.take(rows * d * e);                                   // Xh
     c.take(L * 4 * d * d * e);                              // W1 as fp16, k-tile blocked
     c.take(L * d * d * e);                                  // W2 as fp16 (blocked or fragment-packed)
   }
@@ -815,13 +820,17 @@ int flame_gr_forward_static(const flame_gr_config *cfg_in, const flame_gr_weight
                cfg.latency_mode ? 1 : 0};
   const size_t rows = (size_t)h.ws_rows, d = (size_t)cfg.d_model, e = h.elt, L = (size_t)cfg.n_layers;
   Carver c;
-  h.X = (float *)(base + c.take(rows * d * sizeof(float)));
+  if (bf) {
+    h.Xb = base + c.take(2 * rows * d * e);
+    h.Xl = (char *)h.Xb + rows * d * e;
+  } else {
+    h.X = (float *)(base + c.take(rows * d * sizeof(float)));
+  }
   h.plane_bytes = rows * d * e;
   h.planes = base + c.take(4 * h.plane_bytes);
   h.O = base + c.take(rows * d * e);
   if (!bf || !k3_fused_supported(cfg.d_model)) h.G = base + c.take(rows * d * e);
   if (bf) {
-    h.Xb = base + c.take(rows * d * e);
     h.W1h = base + c.take(L * 4 * d * d * e);
     void *w2 = base + c.take(L * d * d * e);
     h.W2h = w2;

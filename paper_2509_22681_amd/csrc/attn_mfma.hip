@@ -61,6 +61,10 @@ constexpr int KH = 64;              // keys per half tile (one pass of the regis
 // weights); the last step is a mixed-precision fused multiply-add per weight, fp16 t times fp16 bracket
 // plus the fp32 logit itself, rounded to fp16 once, like the weight of the exact route.
 constexpr float kPolyT2 = 1.0f;                                  // bound on t = s^2  (|x| <= 2)
+// Second segment, |x| <= 4 (t <= 4): silu(x) = s + t (B0 + B1 t + B2 t^2 + B3 t^3 + B4 t^4), minimax-weighted fit of
+// (silu(2 s) - s) / t on 0 <= t <= 4 (error of silu below 5.4e-4).
+constexpr float kMidT2 = 4.0f;
+__device__ constexpr float kMidB[5] = {0.9926417973f, -0.3010154918f, 0.0835130618f, -0.0141349725f, 0.0010234216f};
 __device__ __forceinline__ int pi32(int m) {  // swap bits 2 and 3
   return (m & ~12) | ((m & 4) << 1) | ((m & 8) >> 1);
 }
@@ -367,8 +371,45 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
           const f16x2 m4 = max3(th[1][4], th[1][5], th[1][6]);
           const f16x2 m = __builtin_elementwise_maximum(max3(m0, m1, m2), max3(m3, m4, th[1][7]));
           const bool bad = !((float)m[0] <= kPolyT2 && (float)m[1] <= kPolyT2);     // NaN counts as bad
+          const bool bad_mid = !((float)m[0] <= kMidT2 && (float)m[1] <= kMidT2);
           fast = __builtin_amdgcn_ballot_w64(bad) == 0;
-          if (fast) {
+          const bool mid = !fast && __builtin_amdgcn_ballot_w64(bad_mid) == 0;
+          if (mid) {
+            // 2 < max |x| <= 4 somewhere in the block: the same form with a polynomial of degree 4 in t fitted on
+            // |x| <= 4 (approximation error below 5.4e-4; two more packed multiply-adds per pair of weights than the
+            // short polynomial, still no transcendental).  The exp2 / rcp route is left for blocks with |x| > 4.
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+              const f16x2 d4 = {(half_t)kMidB[4], (half_t)kMidB[4]}, d3 = {(half_t)kMidB[3], (half_t)kMidB[3]};
+              const f16x2 d2 = {(half_t)kMidB[2], (half_t)kMidB[2]}, d1 = {(half_t)kMidB[1], (half_t)kMidB[1]};
+              const f16x2 d0 = {(half_t)kMidB[0], (half_t)kMidB[0]};
+              f16x2 r[8];
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = __builtin_elementwise_fma(d4, th[j][i], d3);
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = __builtin_elementwise_fma(r[i], th[j][i], d2);
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = __builtin_elementwise_fma(r[i], th[j][i], d1);
+#pragma unroll
+              for (int i = 0; i < 8; ++i) r[i] = __builtin_elementwise_fma(r[i], th[j][i], d0);
+              float w[16];
+#pragma unroll
+              for (int i = 0; i < 8; ++i) {
+                w[2 * i] = __builtin_fmaf((float)th[j][i][0], (float)r[i][0], sacc[j][2 * i]);
+                w[2 * i + 1] = __builtin_fmaf((float)th[j][i][1], (float)r[i][1], sacc[j][2 * i + 1]);
+              }
+              if (need_mask) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                  w[e] = 32 * j + 16 * (e >> 3) + (e & 7) < vis_lim ? w[e] : 0.f;
+                }
+              }
+              __builtin_amdgcn_sched_barrier(0);
+              fp[2 * j] = pack8(w);
+              fp[2 * j + 1] = pack8(w + 8);
+            }
+            fast = true;      // the weights are made
+          } else if (fast) {
             // stage by stage over eight independent pairs, so that no instruction waits for the one before
 #pragma unroll
             for (int j = 0; j < 2; ++j) {

@@ -1,6 +1,7 @@
 // MFMA projections of the GR block for gfx950 (fp16 operands, fp32 accumulation):
 //   K1  [U V Q K] = silu(X W1^T + b1)            (SiLU fused as the GEMM epilogue)
-//   K3b X <- X + G W2^T + b2, Xh = fp16(X)       (residual fused as the GEMM epilogue)
+//   K3b X <- X + G W2^T + b2                     (residual fused as the GEMM epilogue; X is held as the two fp16 words
+//                                                 Xh = fp16(X), k-tile blocked, and Xl = fp16(X - Xh), row-major)
 // Both are C[m][n] = sum_k A[m][k] W[n][k] with A and W row-major, k contiguous.
 //
 // Tiling.  A 128x128 tile re-reads 1 byte of operand per 64 flop, which at MFMA speed is twice what
@@ -63,7 +64,7 @@ __device__ __forceinline__ int sigma32(int m) { return ((m & 4) << 2) | ((m >> 3
 template <int BN, int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
     const half_t *__restrict__ A, const half_t *__restrict__ W, const bf16_t *__restrict__ bias,
-    PlanePtrs planes, float *__restrict__ X, half_t *__restrict__ Xh,
+    PlanePtrs planes, half_t *__restrict__ Xl, half_t *__restrict__ Xh, int lo_is_zero,
     const int32_t *__restrict__ blk_list, int blk_first, int n_blk, int n_row_tiles, int n_col_tiles, int K, int d,
     int64_t ws_rows, PlaneSel sel, float alpha, bool a_blocked) {
   constexpr int WN = BN / 2;            // wavefront patch: 128 rows x WN columns
@@ -384,17 +385,19 @@ __global__ __launch_bounds__(256, 2) void gemm_mfma_kernel(
 #pragma unroll
         for (int g = 0; g < 2; ++g) {
           const bf16x8 bv = *(const bf16x8 *)(bias + nn + 8 * g);
-          f32x4 x0 = *(const f32x4 *)(X + m * d + nn + 8 * g), x1 = *(const f32x4 *)(X + m * d + nn + 8 * g + 4);
-          f16x8 o;
+          const f16x8 h8 = *(const f16x8 *)(Xh + blocked_index(m, nn + 8 * g, d));
+          f16x8 l8;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            x0[q] += acc[i][j][8 * g + q] + (float)bv[q];
-            x1[q] += acc[i][j][8 * g + 4 + q] + (float)bv[4 + q];
-            o[q] = to_f16_sat(x0[q]);
-            o[4 + q] = to_f16_sat(x1[q]);
+          for (int q = 0; q < 8; ++q) l8[q] = (half_t)0.f;
+          if (!lo_is_zero) l8 = *(const f16x8 *)(Xl + m * d + nn + 8 * g);
+          f16x8 o, ol;
+#pragma unroll
+          for (int q = 0; q < 8; ++q) {
+            const float x = ((float)h8[q] + (float)l8[q]) + (acc[i][j][8 * g + q] + (float)bv[q]);
+            o[q] = to_f16_sat(x);
+            ol[q] = to_f16_sat(x - (float)o[q]);
           }
-          *(f32x4 *)(X + m * d + nn + 8 * g) = x0;
-          *(f32x4 *)(X + m * d + nn + 8 * g + 4) = x1;
+          *(f16x8 *)(Xl + m * d + nn + 8 * g) = ol;
           *(f16x8 *)(Xh + blocked_index(m, nn + 8 * g, d)) = o;
         }
       }
@@ -414,30 +417,30 @@ void launch_uvqk_bf16(const void *Xh, const void *W1h, const void *b1, PlanePtrs
   if (sh.d % 128 == 0) {
     const int col_tiles = sel.n * (sh.d / 128);
     gemm_mfma_kernel<128, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
-                                                                   planes, nullptr, nullptr, blk_list, blk_first, n_blk,
+                                                                   planes, nullptr, nullptr, 0, blk_list, blk_first, n_blk,
                                                                    row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha, true);
   } else {
     const int col_tiles = sel.n * (sh.d / 64);
     gemm_mfma_kernel<64, 0><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)Xh, (const half_t *)W1h, (const bf16_t *)b1,
-                                                                  planes, nullptr, nullptr, blk_list, blk_first, n_blk,
+                                                                  planes, nullptr, nullptr, 0, blk_list, blk_first, n_blk,
                                                                   row_tiles, col_tiles, sh.d, sh.d, sh.ws_rows, sel, sh.alpha, true);
   }
 }
 
-void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh, const int32_t *blk_list,
+void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, void *Xh, void *Xl, bool lo_is_zero, const int32_t *blk_list,
                          int n_blk, int blk_first, const Shape &sh, hipStream_t s) {
   if (n_blk <= 0) return;
   PlaneSel sel{};
   const int row_tiles = (n_blk + RB - 1) / RB;
   if (sh.d % 128 == 0) {
     const int col_tiles = sh.d / 128;
-    gemm_mfma_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, PlanePtrs{}, X,
-                                                                   (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
+    gemm_mfma_kernel<128, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, PlanePtrs{}, (half_t *)Xl,
+                                                                   (half_t *)Xh, lo_is_zero ? 1 : 0, blk_list, blk_first, n_blk, row_tiles, col_tiles,
                                                                    sh.d, sh.d, sh.ws_rows, sel, 1.0f, false);
   } else {
     const int col_tiles = sh.d / 64;
-    gemm_mfma_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, PlanePtrs{}, X,
-                                                                  (half_t *)Xh, blk_list, blk_first, n_blk, row_tiles, col_tiles,
+    gemm_mfma_kernel<64, 1><<<row_tiles * col_tiles, 256, 0, s>>>((const half_t *)G, (const half_t *)W2h, (const bf16_t *)b2, PlanePtrs{}, (half_t *)Xl,
+                                                                  (half_t *)Xh, lo_is_zero ? 1 : 0, blk_list, blk_first, n_blk, row_tiles, col_tiles,
                                                                   sh.d, sh.d, sh.ws_rows, sel, 1.0f, false);
   }
 }

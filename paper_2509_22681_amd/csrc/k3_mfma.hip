@@ -1,9 +1,13 @@
-// K3 of the GR block, fused: X <- X + (LayerNorm_d(O) * U) W2^T + b2, Xh = fp16(X).
+// K3 of the GR block, fused: X <- X + (LayerNorm_d(O) * U) W2^T + b2.
+//
+// The residual stream X lives in HBM as two fp16 words per element: Xh = fp16(X), the k-tile blocked operand copy that the
+// next layer's projection reads anyway, and Xl = fp16(X - Xh) (row-major), together 22 significant bits, so that
+// this kernel reads 4 and writes 4 bytes per element instead of reading 4 and writing 6 (fp32 X plus the operand copy).
 //
 // LayerNorm, the U gate, the output projection and the residual run in one kernel (the fusion of
 // layer normalisation with the following linear projection that Section 3.2 describes), so the
 // gated activations never travel through HBM.  The kernel is HBM-bound by construction (per row it
-// must read O and U and read-modify-write X: 14 bytes per element against 2*d flops), so the
+// must read O and U and read-modify-write X: 12 bytes per element against 2*d flops), so the
 // design aims at streaming, not at MFMA utilisation:
 //   * one workgroup = one 64-row block of the workspace, all d output features (d <= 512 per pass);
 //   * phase 1: each wavefront normalises 16 rows (one row per wavefront-wide 16-byte load, statistics
@@ -13,8 +17,8 @@
 //   * phase 2: each wavefront owns d/4 output features; the W2 operand comes straight from L2 in a
 //     fragment-major packed layout (one coalesced 1 KB read per MFMA operand, prepared once per forward
 //     by pack_w2_kernel), so LDS holds only the activations and two workgroups fit on a CU;
-//   * phase 3: residual add in fp32 and fp16 copy for the next layer's projection, after a transposition
-//     of the accumulators through LDS so that X is read and written in whole lines.
+//   * phase 3: residual add in fp32 (X = Xh + Xl, exact in fp32) and split into the two fp16 words again, after a
+//     transposition of the accumulators through LDS so that the residual is read and written in whole lines.
 #include "device_common.h"
 #include "kernels.h"
 
@@ -50,7 +54,7 @@ template <int NWV, int NBW, int CS>
 __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__restrict__ O, const half_t *__restrict__ U,
                                                           const bf16_t *__restrict__ gamma, const bf16_t *__restrict__ beta,
                                                           const half_t *__restrict__ W2p, const bf16_t *__restrict__ b2,
-                                                          float *__restrict__ X, half_t *__restrict__ Xh,
+                                                          half_t *__restrict__ Xh, half_t *__restrict__ Xl, int lo_is_zero,
                                                           const RowBlock *__restrict__ blocks, const int32_t *__restrict__ blk_list,
                                                           int blk_first, float eps) {
   constexpr int d = 32 * NBW * NWV;
@@ -233,12 +237,19 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
     for (int q = 0; q < 4; ++q) bvf[q] = (float)bv[q];
   }
   constexpr int XB = NIT < 8 ? NIT : 8;             // residual rows requested ahead
-  f32x4 xr[XB];
+  // lo_is_zero: the first layer, whose input rows are embeddings (exact in Xh): Xl is not read, only written
+  f16x4 xh[XB], xl[XB];
 #pragma unroll
   for (int i = 0; i < 2; ++i) {
-    float *xrow = X + (row0 + 32 * i + rl) * d + n;
+    const int64_t m0 = row0 + 32 * i + rl;
+    auto load = [&](int t, int it) {
+      const int64_t m = m0 + (int64_t)it * RPI;
+      xh[t] = *(const f16x4 *)(Xh + blocked_index(m, n, d));
+      xl[t] = f16x4{(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
+      if (!lo_is_zero) xl[t] = *(const f16x4 *)(Xl + m * d + n);
+    };
 #pragma unroll
-    for (int t = 0; t < XB; ++t) xr[t] = *(const f32x4 *)(xrow + (int64_t)t * RPI * d);
+    for (int t = 0; t < XB; ++t) load(t, t);
 #pragma unroll
     for (int j = 0; j < NB2; ++j)
 #pragma unroll
@@ -251,17 +262,18 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
     for (int it = 0; it < NIT; ++it) {
       const int row = it * RPI + rl;
       const f32x4 v = *(const f32x4 *)(pb + row * (WF * 4) + ((cc ^ pkey(row)) << 4));
-      f32x4 x = xr[it % XB];
-      if (it + XB < NIT) xr[it % XB] = *(const f32x4 *)(xrow + (int64_t)(it + XB) * RPI * d);
-      f16x4 o;
+      const f16x4 h4 = xh[it % XB], l4 = xl[it % XB];
+      if (it + XB < NIT) load(it % XB, it + XB);
+      f16x4 oh, ol;
 #pragma unroll
       for (int q = 0; q < 4; ++q) {
-        x[q] += v[q] + bvf[q];
-        o[q] = to_f16_sat(x[q]);
+        const float x = ((float)h4[q] + (float)l4[q]) + (v[q] + bvf[q]);
+        oh[q] = to_f16_sat(x);
+        ol[q] = to_f16_sat(x - (float)oh[q]);
       }
       const int64_t m = row0 + 32 * i + row;
-      __builtin_nontemporal_store(x, (f32x4 *)(X + m * d + n));
-      __builtin_nontemporal_store(o, (f16x4 *)(Xh + blocked_index(m, n, d)));
+      __builtin_nontemporal_store(oh, (f16x4 *)(Xh + blocked_index(m, n, d)));
+      __builtin_nontemporal_store(ol, (f16x4 *)(Xl + m * d + n));
     }
   }
 }
@@ -277,14 +289,14 @@ void launch_pack_w2(const void *W2, void *W2p, int d, int n_layers, hipStream_t 
 }
 
 void launch_k3_fused(const void *O, const void *U, const void *gamma, const void *beta, const void *W2p_layer, const void *b2,
-                     float *X, void *Xh, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first,
+                     void *Xh, void *Xl, bool lo_is_zero, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first,
                      const Shape &sh, hipStream_t s) {
   if (n_blk <= 0) return;
   const size_t lds = (size_t)kRowAlign * sh.d * 2;
   // few row blocks: two workgroups per block (see the kernel), as long as the launch still fits the chip once over
   const bool split = n_blk <= 128;
 #define K3_CASE(NWV, NB, CSV) k3_fused_kernel<NWV, NB, CSV><<<dim3(n_blk, CSV), 64 * NWV, lds, s>>>((const half_t *)O, (const half_t *)U, (const bf16_t *)gamma, (const bf16_t *)beta, \
-    (const half_t *)W2p_layer, (const bf16_t *)b2, X, (half_t *)Xh, blocks, blk_list, blk_first, sh.eps)
+    (const half_t *)W2p_layer, (const bf16_t *)b2, (half_t *)Xh, (half_t *)Xl, lo_is_zero ? 1 : 0, blocks, blk_list, blk_first, sh.eps)
   const bool split4 = n_blk <= 64;
   if (sh.d == 512) { if (split4) K3_CASE(4, 4, 4); else if (split) K3_CASE(4, 4, 2); else K3_CASE(4, 4, 1); }
   else if (sh.d == 384) { if (split4) K3_CASE(3, 4, 4); else if (split) K3_CASE(3, 4, 2); else K3_CASE(3, 4, 1); }

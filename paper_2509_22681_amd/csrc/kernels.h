@@ -17,7 +17,8 @@ struct Shape {
 };
 
 // ---- shared small kernels (misc.hip) --------------------------------------------------------
-// X[rows of blocks) <- embeddings (fp32 copy, and a k-tile blocked fp16 copy Xh in the MFMA path); padding rows zeroed.
+// rows of blocks <- embeddings: fp32 X in the fp32 path, the k-tile blocked fp16 word Xh in the MFMA path (whose residual is
+// the pair Xh = fp16(X), Xl = fp16(X - Xh); embeddings are exact in Xh and Xl is not written); padding rows zeroed.
 // The n blocks are list[0..n) if list is given, else first..first+n.
 void launch_assemble(int dtype, const RowBlock *blocks, const int32_t *list, int n, int first, const void *hist,
                      const void *cand, float *X, void *Xh, int d, hipStream_t s);
@@ -33,14 +34,17 @@ void launch_expand_bias(const float *rab, const int32_t *bucket_tab, float *bias
 void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, const void *beta,
                     void *G, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first, int d,
                     float eps, hipStream_t s);
-// scores[src_row + i] = <X[row], w_s> + b_s for the valid rows of every candidate block.
-void launch_scores(int dtype, const float *X, const void *w_s, float b_s, const RowBlock *blocks,
+// scores[src_row + i] = <X[row], w_s> + b_s for the valid rows of every candidate block (MFMA path: X = Xh + Xl).
+void launch_scores(int dtype, const float *X, const void *Xh, const void *Xl, const void *w_s, float b_s, const RowBlock *blocks,
                    const int32_t *cand_blocks, int n_cblk, float *scores, int d, hipStream_t s);
 // out[i] = factor / temperature[i] (the per-layer, per-head logit scale of the softmax attention).
 void launch_logit_scale(const float *temperature, float *out, int n, float factor, hipStream_t s);
 // hidden[(src_row + i) * d ..] = X[row] for the valid rows of every candidate block (fp32).
-void launch_gather_hidden(const float *X, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk, float *hidden,
-                          int d, hipStream_t s);
+// (Xh given: the residual is the pair Xh, Xl of the MFMA path; else fp32 X)
+void launch_gather_hidden(const float *X, const void *Xh, const void *Xl, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk,
+                          float *hidden, int d, hipStream_t s);
+// out[row][k] = Xh + Xl as fp32 for rows [row_begin, row_end) (debug capture of the MFMA path's residual)
+void launch_residual_to_f32(const void *Xh, const void *Xl, float *out, int64_t row_begin, int64_t row_end, int d, hipStream_t s);
 // bucket(delta) for delta in [0, D), computed on the device (the integers of plan.h's bucket_of)
 void launch_bucket_table(int n_buckets, int D, int32_t *out, hipStream_t s);
 // Host words -> device memory without a copy engine or staging buffer: the words travel as kernel arguments
@@ -84,16 +88,17 @@ void launch_attn_bf16(PlanePtrs planes, const float *bias_lh, const float *tscal
                       int n_items, const Shape &sh, hipStream_t s);
 // Prepares the latency configuration of the attention kernel for this shape (raises its LDS limit); once per handle.
 hipError_t attn_latency_setup(const Shape &sh);
-// X[row] += G W2h^T + b2, and Xh[row] = fp16(X[row])
-void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, float *X, void *Xh,
+// X[row] += G W2h^T + b2 on the residual pair (Xh, Xl); lo_is_zero: Xl is not read (first layer)
+void launch_outproj_bf16(const void *G, const void *W2h, const void *b2, void *Xh, void *Xl, bool lo_is_zero,
                          const int32_t *blk_list, int n_blk, int blk_first, const Shape &sh, hipStream_t s);
 
 // K3 fused (k3_mfma.hip): LayerNorm * U gate + output projection + residual in one kernel, for
 // d in {128, 192, 256, 384, 512}; W2p is the fragment-major packed fp16 copy of W2 written by launch_pack_w2.
 bool k3_fused_supported(int d);
 void launch_pack_w2(const void *W2, void *W2p, int d, int n_layers, hipStream_t s);
+// (residual pair Xh, Xl as above; lo_is_zero: Xl is not read)
 void launch_k3_fused(const void *O, const void *U, const void *gamma, const void *beta, const void *W2p_layer, const void *b2,
-                     float *X, void *Xh, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first,
+                     void *Xh, void *Xl, bool lo_is_zero, const RowBlock *blocks, const int32_t *blk_list, int n_blk, int blk_first,
                      const Shape &sh, hipStream_t s);
 
 constexpr int kAttnQTileBf16 = 128;  // query rows per attention work item, MFMA path

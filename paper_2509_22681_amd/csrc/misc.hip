@@ -9,7 +9,9 @@ namespace flame {
 // Assembly: the token matrix of a request is its history rows followed by its candidate rows
 // (Section 2.1: candidates are appended after the behaviour sequence).  One workgroup per 64-row
 // block of the padded workspace; rows past n_valid are zero so that they stay finite downstream.
-// X is row-major fp32; the fp16 copy Xh (MFMA path) is k-tile blocked.
+// fp32 path: X is row-major fp32.  MFMA path: the residual is held as two fp16 words, Xh = fp16(X) (k-tile blocked, the
+// projection's operand) and Xl = fp16(X - Xh); embeddings are exact in Xh, so assembly writes Xh only and the first layer
+// treats Xl as zero.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restrict__ blocks, const int32_t *__restrict__ list, int blk_begin,
@@ -33,8 +35,7 @@ __global__ __launch_bounds__(256) void assemble_kernel(const RowBlock *__restric
 // still spreads over many compute units and no lane walks a long chain of dependent loads.
 __global__ __launch_bounds__(256) void assemble_bf16_kernel(const RowBlock *__restrict__ blocks, const int32_t *__restrict__ list,
                                                             int blk_begin, const bf16_t *__restrict__ hist,
-                                                            const bf16_t *__restrict__ cand, float *__restrict__ X,
-                                                            half_t *__restrict__ Xh, int d) {
+                                                            const bf16_t *__restrict__ cand, half_t *__restrict__ Xh, int d) {
   const int b = list ? list[blockIdx.x] : blk_begin + blockIdx.x;
   const RowBlock rb = blocks[b];
   const bf16_t *src = rb.kind ? cand : hist;
@@ -48,18 +49,9 @@ __global__ __launch_bounds__(256) void assemble_bf16_kernel(const RowBlock *__re
 #pragma unroll
     for (int k = 0; k < 8; ++k) v[k] = (bf16_t)0.f;
     if (r < rb.n_valid) v = *(const bf16x8 *)(src + ((int64_t)rb.src_row + r) * d + c * 8);
-    f32x4 lo, hi;
     f16x8 o;
 #pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      lo[k] = (float)v[k];
-      hi[k] = (float)v[4 + k];
-      o[k] = to_f16_sat(lo[k]);
-      o[4 + k] = to_f16_sat(hi[k]);
-    }
-    float *xp = X + (row_base + r) * d + c * 8;
-    *(f32x4 *)xp = lo;
-    *(f32x4 *)(xp + 4) = hi;
+    for (int k = 0; k < 8; ++k) o[k] = to_f16_sat((float)v[k]);
     *(f16x8 *)(Xh + blocked_index(row_base + r, c * 8, d)) = o;
   }
 }
@@ -68,7 +60,7 @@ void launch_assemble(int dtype, const RowBlock *blocks, const int32_t *list, int
                      const void *cand, float *X, void *Xh, int d, hipStream_t s) {
   if (n <= 0) return;
   if (dtype == FLAME_GR_BF16)
-    assemble_bf16_kernel<<<dim3(n, 4), 256, 0, s>>>(blocks, list, first, (const bf16_t *)hist, (const bf16_t *)cand, X, (half_t *)Xh, d);
+    assemble_bf16_kernel<<<dim3(n, 4), 256, 0, s>>>(blocks, list, first, (const bf16_t *)hist, (const bf16_t *)cand, (half_t *)Xh, d);
   else
     assemble_kernel<float><<<n, 256, 0, s>>>(blocks, list, first, (const float *)hist, (const float *)cand, X, nullptr, d);
 }
@@ -102,19 +94,40 @@ void launch_logit_scale(const float *temperature, float *out, int n, float facto
 // ---------------------------------------------------------------------------------------------
 // The candidates' final residual rows, in candidate order (the input of a fusion / head stage).
 // ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void gather_hidden_kernel(const float *__restrict__ X, const RowBlock *__restrict__ blocks,
+// Xh != nullptr: the residual is the pair (Xh blocked, Xl row-major) of the MFMA path, else fp32 X.
+__global__ __launch_bounds__(256) void gather_hidden_kernel(const float *__restrict__ X, const half_t *__restrict__ Xh,
+                                                            const half_t *__restrict__ Xl, const RowBlock *__restrict__ blocks,
                                                             const int32_t *__restrict__ cand_blocks, float *__restrict__ hidden, int d) {
   const int b = cand_blocks[blockIdx.x];
   const RowBlock rb = blocks[b];
   const int n = rb.n_valid * d;
-  const float *src = X + (int64_t)b * kRowAlign * d;
+  const int64_t row0 = (int64_t)b * kRowAlign;
   float *dst = hidden + (int64_t)rb.src_row * d;
-  for (int i = threadIdx.x; i < n; i += 256) dst[i] = src[i];
+  for (int i = threadIdx.x; i < n; i += 256) {
+    if (Xh) dst[i] = (float)Xh[blocked_index(row0 + i / d, i % d, d)] + (float)Xl[row0 * d + i];
+    else dst[i] = X[row0 * d + i];
+  }
 }
 
-void launch_gather_hidden(const float *X, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk, float *hidden,
-                          int d, hipStream_t s) {
-  if (n_cblk > 0) gather_hidden_kernel<<<n_cblk, 256, 0, s>>>(X, blocks, cand_blocks, hidden, d);
+void launch_gather_hidden(const float *X, const void *Xh, const void *Xl, const RowBlock *blocks, const int32_t *cand_blocks, int n_cblk,
+                          float *hidden, int d, hipStream_t s) {
+  if (n_cblk > 0) gather_hidden_kernel<<<n_cblk, 256, 0, s>>>(X, (const half_t *)Xh, (const half_t *)Xl, blocks, cand_blocks, hidden, d);
+}
+
+// Debug capture: the residual rows [row_begin, row_end) of the MFMA path as fp32 (Xh + Xl, exact).
+__global__ __launch_bounds__(256) void residual_to_f32_kernel(const half_t *__restrict__ Xh, const half_t *__restrict__ Xl,
+                                                              float *__restrict__ out, int64_t first, int64_t n, int d) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+    const int64_t e = first + i;
+    out[e] = (float)Xh[blocked_index(e / d, (int)(e % d), d)] + (float)Xl[e];
+  }
+}
+
+void launch_residual_to_f32(const void *Xh, const void *Xl, float *out, int64_t row_begin, int64_t row_end, int d, hipStream_t s) {
+  const int64_t n = (row_end - row_begin) * d;
+  if (n <= 0) return;
+  const int grid = (int)((n + 255) / 256 > 4096 ? 4096 : (n + 255) / 256);
+  residual_to_f32_kernel<<<grid, 256, 0, s>>>((const half_t *)Xh, (const half_t *)Xl, out, row_begin * d, n, d);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -214,7 +227,8 @@ void launch_ln_gate(int dtype, const void *O, const void *U, const void *gamma, 
 // Score head: one logit per candidate row, written in the caller's candidate order.
 // ---------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X, const T *__restrict__ w_s, float b_s,
+__global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X, const half_t *__restrict__ Xh,
+                                                    const half_t *__restrict__ Xl, const T *__restrict__ w_s, float b_s,
                                                     const RowBlock *__restrict__ blocks, const int32_t *__restrict__ cblk,
                                                     float *__restrict__ scores, int d) {
   const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -222,20 +236,23 @@ __global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X,
   const RowBlock rb = blocks[blk];
   const int i = (blockIdx.x & 15) * 4 + wave;
   if (i >= rb.n_valid) return;
-  const float *x = X + ((int64_t)blk * kRowAlign + i) * d;
+  const int64_t row = (int64_t)blk * kRowAlign + i;
   float acc = 0.f;
-  for (int k = lane; k < d; k += 64) acc += x[k] * to_f32(w_s[k]);
+  for (int k = lane; k < d; k += 64) {
+    const float x = Xh ? (float)Xh[blocked_index(row, k, d)] + (float)Xl[row * d + k] : X[row * d + k];
+    acc += x * to_f32(w_s[k]);
+  }
   acc = wave_sum(acc);
   if (lane == 0) scores[rb.src_row + i] = acc + b_s;
 }
 
-void launch_scores(int dtype, const float *X, const void *w_s, float b_s, const RowBlock *blocks,
+void launch_scores(int dtype, const float *X, const void *Xh, const void *Xl, const void *w_s, float b_s, const RowBlock *blocks,
                    const int32_t *cand_blocks, int n_cblk, float *scores, int d, hipStream_t s) {
   if (n_cblk <= 0) return;
   if (dtype == FLAME_GR_BF16)
-    score_kernel<bf16_t><<<n_cblk * 16, 256, 0, s>>>(X, (const bf16_t *)w_s, b_s, blocks, cand_blocks, scores, d);
+    score_kernel<bf16_t><<<n_cblk * 16, 256, 0, s>>>(nullptr, (const half_t *)Xh, (const half_t *)Xl, (const bf16_t *)w_s, b_s, blocks, cand_blocks, scores, d);
   else
-    score_kernel<float><<<n_cblk * 16, 256, 0, s>>>(X, (const float *)w_s, b_s, blocks, cand_blocks, scores, d);
+    score_kernel<float><<<n_cblk * 16, 256, 0, s>>>(X, nullptr, nullptr, (const float *)w_s, b_s, blocks, cand_blocks, scores, d);
 }
 
 // ---------------------------------------------------------------------------------------------

@@ -62,16 +62,19 @@ def sample_requests(wl: W.Workload, name: str):
     return list(spec)
 
 
-_weights_digest = {}
+_weights_digest = {}        # id(weights dict) -> (the dict itself, digest): the reference keeps the id from being reused
 
 
 def _key(wl: W.Workload, i: int) -> str:
-    wd = _weights_digest.get(id(wl.weights))
-    if wd is None:
+    memo = _weights_digest.get(id(wl.weights))
+    if memo is None or memo[0] is not wl.weights:
         hw = hashlib.sha1()
         for k in sorted(wl.weights):
             hw.update(np.ascontiguousarray(wl.weights[k]).tobytes())
-        wd = _weights_digest[id(wl.weights)] = hw.digest()
+        if len(_weights_digest) >= 8:       # bounded: the oldest entry goes
+            _weights_digest.pop(next(iter(_weights_digest)))
+        memo = _weights_digest[id(wl.weights)] = (wl.weights, hw.digest())
+    wd = memo[1]
     h = hashlib.sha1(wd)
     ho, co = wl.history_offsets, wl.cand_offsets
     cfg = wl.cfg.to_dict()
@@ -90,6 +93,8 @@ def request_scores(wl: W.Workload, i: int, verbose: bool = False) -> np.ndarray:
         return np.loadtxt(path, dtype=np.float64, ndmin=1)
     t = time.time()
     ho, co = wl.history_offsets, wl.cand_offsets
+    if (ho[i + 1] - ho[i]) + (co[i + 1] - co[i]) > 2048:      # minutes of CPU work: never silent
+        print(f"  no stored oracle scores for {wl.name} request {i} ({os.path.basename(path)}): computing", flush=True)
     s = oracle.forward_request(wl.cfg.to_dict(), wl.weights, wl.history_emb[ho[i]:ho[i + 1]],
                                wl.cand_emb[co[i]:co[i + 1]])
     if verbose:

@@ -183,7 +183,8 @@ def strict_stats(g, o):
 # instructions (a second, low-order operand word would double the projection or the attention arithmetic); what is not
 # an operand (U and O in transit) is a sixth of it.  The bar is left where the benchmark definition puts it.
 PRODUCTION_FLOOR = pytest.mark.xfail(
-    strict=False, reason="fp16 operand floor at 16 layers: worst request 2.4e-2 against the 2e-2 bar (120 of 128 requests inside)")
+    strict=False, reason="fp16 operand floor at 16 layers: worst request 2.4e-2 to 3.0e-2 against the 2e-2 bar, depending on the build "
+           "(112 to 120 of 128 requests inside; the rms error of every request stays below 7e-3)")
 
 
 _workload_stats = {}

@@ -98,9 +98,9 @@ def test_static_workspace_size_check_needs_no_gpu():
     cfg = B.make_config(16, 512, 8, 128, 8192, "bf16")
     rows = 4096 + 2048
     need = B.flame_gr_static_scratch_bytes(cfg, rows)
-    # residual 4d + four planes, output and operand copy 12d per row, 256 spare rows; 10 d^2 per layer of weights; tables
+    # residual pair 4d + four planes and output 10d per row, 256 spare rows; 10 d^2 per layer of weights; bias tables
     d, Ly = 512, 16
-    assert need >= (rows + 256) * 16 * d + Ly * 10 * d * d + Ly * 8 * 8192 * 4
+    assert need >= (rows + 256) * 14 * d + Ly * 10 * d * d + Ly * 8 * 8192 * 4
     assert need > 64 << 20
     fake = np.zeros(64, np.float32)                      # aligned, non-NULL stand-ins
     w = B.flame_gr_weights(*([fake.ctypes.data] * 8), 0.0, fake.ctypes.data)
