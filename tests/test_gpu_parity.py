@@ -184,7 +184,8 @@ def strict_stats(g, o):
 # an operand (U and O in transit) is a sixth of it.  The bar is left where the benchmark definition puts it.
 PRODUCTION_FLOOR = pytest.mark.xfail(
     strict=False, reason="fp16 operand floor at 16 layers: worst request 2.4e-2 to 3.0e-2 against the 2e-2 bar, depending on the build "
-           "(112 to 120 of 128 requests inside; the rms error of every request stays below 7e-3)")
+           "(112 to 120 of 128 requests inside; the rms error of every request stays below 7e-3); fp64 arithmetic on fp16 "
+           "operands gives 2.8e-2 on the worst request (test_production_error_is_the_floor_of_fp16_operands)")
 
 
 _workload_stats = {}
@@ -239,6 +240,30 @@ def test_benchmark_workload_scores(B, name):
     """The gate of the benchmark definition on every score of every request: max_j |g_j - o_j| / max(|o_j|, rms(o)) <= 2e-2."""
     st = workload_stats(B, name)
     assert st["worst"] <= TOL["bf16"], st
+
+
+def test_production_error_is_the_floor_of_fp16_operands(B):
+    """Why the gate above is an expected failure: the request of the production workload with the largest error
+    (request 42: 1040 history items, 1440 candidates), run through the oracle's own fp64 arithmetic with nothing but
+    the roundings to fp16 that the matrix instructions' operands and the stored planes need (tests/fp16_floor.py),
+    shows the error the GPU shows.  The GPU may not be worse than that floor by more than a quarter in rms; both
+    maxima are printed."""
+    from tests.fp16_floor import forward_request_rounded
+    wl = W.make_workload("production")
+    i = 42
+    sub = wl.subset([i])
+    o = request_scores(wl, i)
+    g, _ = run_gpu(B, sub)
+    ho, co = wl.history_offsets, wl.cand_offsets
+    progress(f"fp16 floor of production request {i}: emulating {wl.cfg.n_layers} layers on the CPU")
+    f = forward_request_rounded(wl.cfg.to_dict(), wl.weights, wl.history_emb[ho[i]:ho[i + 1]], wl.cand_emb[co[i]:co[i + 1]],
+                                on_layer=lambda l: progress(f"fp16 floor: layer {l} done"))
+    rms = np.sqrt(np.mean(o * o))
+    gpu_rms, floor_rms = np.sqrt(np.mean((g - o) ** 2)) / rms, np.sqrt(np.mean((f - o) ** 2)) / rms
+    print(f"production request {i}: rms error of the GPU {gpu_rms:.3e}, of fp64 arithmetic with fp16 operands {floor_rms:.3e}; "
+          f"gate statistic (max) {score_err(g, o):.3e} against {score_err(f, o):.3e}")
+    assert gpu_rms <= 1.25 * floor_rms
+    assert score_err(f, o) > TOL["bf16"]      # exact arithmetic on fp16 operands is itself outside the bar on this request
 
 
 # ------------------------------------------------------------------ invariants on the GPU
