@@ -55,7 +55,10 @@ __global__ __launch_bounds__(256) void mfma_reg_kernel(float *out, int iters, lo
 
 // ---- matrix instructions fed from LDS (the way the GEMM and attention kernels run them) ----------------------
 // per iteration and wavefront: 8 matrix instructions (4 x 2 blocks), 6 fragment reads prefetched one iteration ahead
-template <bool RANDOM>
+// IDLE > 0: every wavefront sleeps 64 * IDLE cycles after each group of 8 matrix instructions (256 cycles of the pipe), which
+// lowers the duty of the matrix pipe with nothing else running: how the clock answers tells how much of the chip's power is
+// there whether or not the pipe works.
+template <bool RANDOM, int IDLE = 0>
 __global__ __launch_bounds__(256, 2) void mfma_lds_kernel(float *out, int iters, const _Float16 *src, long long *clk) {
   __shared__ __attribute__((aligned(16))) _Float16 lds[2][6 * 512 * 4];     // 2 x 24 KB
   const int tid = threadIdx.x, lane = tid & 63;
@@ -85,6 +88,7 @@ __global__ __launch_bounds__(256, 2) void mfma_lds_kernel(float *out, int iters,
       acc[2][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[q][2], f[q][5], acc[2][1], 0, 0, 0);
       acc[3][1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(f[q][3], f[q][5], acc[3][1], 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
+      if (IDLE > 0) __builtin_amdgcn_s_sleep(IDLE);
     }
   }
   float s = 0.f;
@@ -259,6 +263,22 @@ int main() {
       const double fl = (double)kCU * 2 * 4 * iters * 8 * 32768.0;
       printf("mfma fed by 6 LDS fragment reads per 8 instructions, %s data, 2 wavefronts per SIMD: %.1f TFLOP/s at %.2f GHz\n",
              rnd ? "random" : "constant", fl / ms * 1e-9, shader_ghz(clk));
+    }
+    // the same random-data stream at reduced duty of the matrix pipe
+    {
+      const int it2 = iters / 4;
+      const double fl = (double)kCU * 2 * 4 * it2 * 8 * 32768.0;
+      const float m1 = time_ms([&] { mfma_lds_kernel<true, 4><<<kCU * 2, 256>>>(o, it2, src, clk); });
+      const double g1 = shader_ghz(clk);
+      const float m2 = time_ms([&] { mfma_lds_kernel<true, 12><<<kCU * 2, 256>>>(o, it2, src, clk); });
+      const double g2 = shader_ghz(clk);
+      const float m3 = time_ms([&] { mfma_lds_kernel<true, 28><<<kCU * 2, 256>>>(o, it2, src, clk); });
+      const double g3 = shader_ghz(clk);
+      // duty = matrix cycles / all cycles of a SIMD = flop / (1024 SIMDs x 1024 flop per cycle x cycles)
+      auto duty = [&](float ms, double ghz) { return fl / (1024.0 * 1024.0 * ms * 1e-3 * ghz * 1e9); };
+      printf("random data, wavefronts sleeping 256 / 768 / 1792 cycles per 8 instructions: %.1f TFLOP/s at %.2f GHz (pipe duty %.2f), "
+             "%.1f at %.2f GHz (%.2f), %.1f at %.2f GHz (%.2f)\n",
+             fl / m1 * 1e-9, g1, duty(m1, g1), fl / m2 * 1e-9, g2, duty(m2, g2), fl / m3 * 1e-9, g3, duty(m3, g3));
     }
     CK(hipFree(src));
   }
