@@ -174,16 +174,21 @@ __global__ __launch_bounds__(256) void valu_kernel(float *out, int iters, long l
 }
 
 // ---- LDS fragment reads: 16-byte reads of 32 rows x 2 chunk columns, rows of 64 bytes ----------------------------
-template <bool SWIZZLE>
+// ORDER 0: unswizzled; 1: the swizzle, rows in lane order; 2: the same swizzle with the rows in the order in which the
+// projection kernel's second operand is read (lane m reads row 16 bit2(m) + 4 (m / 8) + m % 4); 3: another key.
+template <int ORDER>
 __global__ __launch_bounds__(256, 2) void lds_kernel(float *out, int iters, long long *clk) {
   __shared__ __attribute__((aligned(16))) char lds[65536];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   for (int i = tid; i < 65536 / 16; i += 256) ((f16x8 *)lds)[i] = f16x8{1, 2, 3, 4, 5, 6, 7, 8};
   __syncthreads();
   ClockProbe p; p.start();
-  const int row = lane & 31, c = lane >> 5;
-  // 64-byte rows, four to a 256-byte group; swizzled: chunk index XOR two row bits (rows 4 apart land in different slots)
-  const int off = SWIZZLE ? (row >> 2) * 256 + ((((row & 3) << 2) | (c ^ ((row >> 2) & 3))) << 4) : row * 64 + c * 16;
+  const int m = lane & 31, c = lane >> 5;
+  const int row = ORDER == 2 ? (((m & 4) << 2) | ((m >> 3) << 2) | (m & 3)) : m;
+  // 64-byte rows, four to a 256-byte group; swizzled: chunk index XOR row bits 2 and 3 (ORDER 3: bit 3 XOR bit 4 instead
+  // of bit 3, which is free of conflicts if 16 consecutive lanes are served per clock, and is not on this chip)
+  const int key = ORDER == 3 ? ((row >> 2) & 1) | ((((row >> 3) ^ (row >> 4)) & 1) << 1) : (row >> 2) & 3;
+  const int off = ORDER ? (row >> 2) * 256 + ((((row & 3) << 2) | (c ^ key)) << 4) : row * 64 + c * 16;
   // LDS addresses are the low 32 bits of the generic pointer
   const uint32_t a0 = (uint32_t)(uintptr_t)(lds + wave * 16384 + off);
   f16x8 r[8];
@@ -324,13 +329,15 @@ int main() {
       printf("\n");
     }
   }
-  for (int sw = 0; sw < 2; ++sw) {
+  for (int sw = 0; sw < 4; ++sw) {
     const int it2 = 20000;
-    const float ms = sw ? time_ms([&] { lds_kernel<true><<<kCU * 2, 256>>>(o, it2, clk); })
-                        : time_ms([&] { lds_kernel<false><<<kCU * 2, 256>>>(o, it2, clk); });
+    const float ms = sw == 3 ? time_ms([&] { lds_kernel<3><<<kCU * 2, 256>>>(o, it2, clk); })
+                     : sw == 2 ? time_ms([&] { lds_kernel<2><<<kCU * 2, 256>>>(o, it2, clk); })
+                     : sw    ? time_ms([&] { lds_kernel<1><<<kCU * 2, 256>>>(o, it2, clk); })
+                             : time_ms([&] { lds_kernel<0><<<kCU * 2, 256>>>(o, it2, clk); });
     const double ghz = shader_ghz(clk);
     const double bytes = (double)kCU * 2 * 256 * 16 * 8 * it2;
-    printf("ds_read_b128 of 64-byte rows, %s: %.1f bytes per cycle per CU at %.2f GHz\n", sw ? "XOR-swizzled" : "unswizzled",
+    printf("ds_read_b128 of 64-byte rows, %s: %.1f bytes per cycle per CU at %.2f GHz\n", sw == 3 ? "XOR-swizzled with row bit 3 ^ bit 4 in the key" : sw == 2 ? "XOR-swizzled, rows in the permuted order of the projection kernel's second operand" : sw ? "XOR-swizzled" : "unswizzled",
            bytes / (ms * 1e-3 * ghz * 1e9) / kCU, ghz);
   }
   {
