@@ -101,8 +101,8 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
         if (ch < NCHUNK) {
           const int rr = wave * RPW + batch * RB4 + q;
           const int64_t off = (row0 + (EVEN || rr < kRowAlign ? rr : kRowAlign - 1)) * d + ch * 8;
-          ov[set][q][c] = *(const f16x8 *)(O + off);
-          uv[set][q][c] = *(const f16x8 *)(U + off);
+          ov[set][q][c] = __builtin_nontemporal_load((const f16x8 *)(O + off));
+          uv[set][q][c] = __builtin_nontemporal_load((const f16x8 *)(U + off));
         }
       }
   };
@@ -244,9 +244,9 @@ __global__ __launch_bounds__(64 * NWV, 2) void k3_fused_kernel(const half_t *__r
     const int64_t m0 = row0 + 32 * i + rl;
     auto load = [&](int t, int it) {
       const int64_t m = m0 + (int64_t)it * RPI;
-      xh[t] = *(const f16x4 *)(Xh + blocked_index(m, n, d));
+      xh[t] = __builtin_nontemporal_load((const f16x4 *)(Xh + blocked_index(m, n, d)));
       xl[t] = f16x4{(half_t)0.f, (half_t)0.f, (half_t)0.f, (half_t)0.f};
-      if (!lo_is_zero) xl[t] = *(const f16x4 *)(Xl + m * d + n);
+      if (!lo_is_zero) xl[t] = __builtin_nontemporal_load((const f16x4 *)(Xl + m * d + n));
     };
 #pragma unroll
     for (int t = 0; t < XB; ++t) load(t, t);
