@@ -192,7 +192,7 @@ def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128,
     c = wl.cfg
     cfg = B.make_config(c.n_layers, c.d_model, c.n_heads, c.n_buckets, c.max_rel_dist, c.dtype, ln_eps=c.ln_eps,
                         attn_scale=c.attn_scale, max_requests=1, max_total_tokens=int((L + M).max()),
-                        latency_mode=latency_mode)
+                        latency_mode=latency_mode, weights_static=1)      # serving: the weights are frozen (Section 3.3)
     ws = B.pack_weights(dw)
     ho, co = wl.history_offsets, wl.cand_offsets
     E = max(1, concurrency)
@@ -231,7 +231,7 @@ def request_mode_latency(B, wl, dw, hist, cand, concurrency=1, max_requests=128,
         for h in handles:
             B.flame_gr_destroy(h)
     lat = np.array(lat)
-    return {"concurrency": E, "attention_latency_configuration": bool(latency_mode), "p50_ms": float(np.percentile(lat, 50)), "p99_ms": float(np.percentile(lat, 99)),
+    return {"concurrency": E, "attention_latency_configuration": bool(latency_mode), "weights_static": True, "p50_ms": float(np.percentile(lat, 50)), "p99_ms": float(np.percentile(lat, 99)),
             "mean_ms": float(lat.mean()), "requests": len(idx),
             "scores_per_s": float(M[idx].sum() / wall)}
 
