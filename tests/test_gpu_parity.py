@@ -266,6 +266,42 @@ def test_production_error_is_the_floor_of_fp16_operands(B):
     assert score_err(f, o) > TOL["bf16"]      # exact arithmetic on fp16 operands is itself outside the bar on this request
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_weights_declared_static(B, dtype):
+    """weights_static = 1: the operand copies are derived on the first call and again only when a weight pointer
+    differs from the previous call.  Same pointers, several calls: the scores of a handle that derives every time;
+    other tensors (other values): derived again, the scores a fresh handle gives for those weights."""
+    import torch
+    wl = stress(dtype=dtype, name="S4", hot=True, **STRESS["S4"])
+    other = stress(dtype=dtype, name="S4", hot=True, seed=77, **STRESS["S4"])           # other values, same shapes
+    want, _ = run_gpu(B, wl)
+    want_other, _ = run_gpu(B, W.Workload("o", wl.cfg, wl.history_offsets, wl.cand_offsets, wl.history_emb, wl.cand_emb, other.weights))
+    assert not np.array_equal(want, want_other)
+    h = B.flame_gr_create(B.config_for(wl, weights_static=1))
+    try:
+        dw, hist, cand = B.to_device(wl)
+        dw_other, _, _ = B.to_device(other)
+        out = torch.zeros(int(wl.cand_offsets[-1]), device="cuda:0")
+
+        def fwd(weights):
+            out.fill_(float("nan"))
+            B.flame_gr_forward(h, weights, hist, wl.history_offsets, cand, wl.cand_offsets, out)
+            torch.cuda.synchronize()
+            return out.cpu().numpy().copy()
+        ws = B.pack_weights(dw)
+        for _ in range(3):
+            assert np.array_equal(fwd(ws), want)
+        assert np.array_equal(fwd(B.pack_weights(dw_other)), want_other)       # new pointers: derived again
+        assert np.array_equal(fwd(ws), want)                                   # and back
+    finally:
+        B.flame_gr_destroy(h)
+    cfg = B.config_for(wl)
+    cfg.weights_static = 2
+    with pytest.raises(B.FlameGRError) as e:
+        B.flame_gr_create(cfg)
+    assert e.value.code == -1
+
+
 # ------------------------------------------------------------------ invariants on the GPU
 def test_determinism_and_batch_independence(B):
     wl = stress(dtype="bf16", name="S4", hot=True, **STRESS["S4"])
