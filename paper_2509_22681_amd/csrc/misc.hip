@@ -238,9 +238,16 @@ __global__ __launch_bounds__(256) void score_kernel(const float *__restrict__ X,
   if (i >= rb.n_valid) return;
   const int64_t row = (int64_t)blk * kRowAlign + i;
   float acc = 0.f;
-  for (int k = lane; k < d; k += 64) {
-    const float x = Xh ? (float)Xh[blocked_index(row, k, d)] + (float)Xl[row * d + k] : X[row * d + k];
-    acc += x * to_f32(w_s[k]);
+  if constexpr (sizeof(T) == 2) {
+    // MFMA path: 8 features per lane and step, 16-byte loads (8 consecutive k sit together in the blocked word too)
+    for (int k = lane * 8; k < d; k += 512) {
+      const f16x8 h8 = *(const f16x8 *)(Xh + blocked_index(row, k, d)), l8 = *(const f16x8 *)(Xl + row * d + k);
+      const bf16x8 w8 = *(const bf16x8 *)(w_s + k);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) acc += ((float)h8[q] + (float)l8[q]) * (float)w8[q];
+    }
+  } else {
+    for (int k = lane; k < d; k += 64) acc += X[row * d + k] * to_f32(w_s[k]);
   }
   acc = wave_sum(acc);
   if (lane == 0) scores[rb.src_row + i] = acc + b_s;
