@@ -60,3 +60,62 @@ def test_random_ragged_batch(B, seed):
     worst = score_err(g, want)
     print(f"seed {seed}: {c}: score error {worst:.3e}")
     assert worst <= TOL_HOT[c["dtype"]], (c, worst)
+
+
+@pytest.mark.parametrize("seed", range(100, 118))
+def test_every_way_of_running_a_batch_gives_the_same_bits(B, seed):
+    """The same seeded ragged batches through the other entry points and configurations: a captured graph replayed,
+    history prefill + candidate scoring, the static-workspace forward, stream groups, and requests split by
+    max_seq_tokens.  None of them changes an operand or the order of a sum: every one must equal the plain forward bit
+    for bit (SiLU attention; for softmax the split of a request regroups the normalisation and is left out)."""
+    import torch
+    from tests.test_gpu_two_stage import two_stage
+    c = draw_case(seed)
+    c["latency_mode"] = 0
+    wl = W.make_custom(c["L"], c["M"], d=c["d"], H=c["H"], n_layers=c["layers"], n_buckets=c["nb"], max_rel_dist=c["D"],
+                       dtype=c["dtype"], seed=seed, emb_std=1.0, rab_std=1.0, bias_amp=0.1, affine_random=True,
+                       attn_scale=c["attn_scale"], attn_kind=c["kind"], name=f"ways{seed}")
+    n = int(wl.cand_offsets[-1])
+    dw, hist, cand = B.to_device(wl)
+
+    def forward(**kw):
+        grow = kw.pop("grow", False)
+        cfg = B.config_for(wl, **kw)
+        if grow:                                   # splitting repeats histories: room for the copies
+            cfg.max_total_tokens = int(cfg.max_total_tokens * 8 + 1024)
+            cfg.max_requests = int(cfg.max_requests * 16 + 16)
+        h = B.flame_gr_create(cfg)
+        try:
+            out = torch.full((n,), float("nan"), device="cuda:0")
+            B.flame_gr_forward(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, out)
+            torch.cuda.synchronize()
+            return out.cpu().numpy().copy()
+        finally:
+            B.flame_gr_destroy(h)
+
+    ref = forward()
+    assert np.isfinite(ref).all()
+    ways = {"stream groups": forward(n_streams=3)}
+    # a captured graph, replayed twice
+    h = B.flame_gr_create(B.config_for(wl))
+    try:
+        out = torch.zeros(n, device="cuda:0")
+        B.flame_gr_capture(h, dw, hist, wl.history_offsets, cand, wl.cand_offsets, out)
+        for rep in range(2):
+            out.fill_(float("nan"))
+            B.flame_gr_replay(h)
+            torch.cuda.synchronize()
+            ways[f"graph replay {rep}"] = out.cpu().numpy().copy()
+    finally:
+        B.flame_gr_destroy(h)
+    if c["dtype"] == "bf16":                      # the two-stage path is built for the MFMA kernels only
+        (ways["prefill + score"],) = two_stage(B, wl)
+    out = torch.full((n,), float("nan"), device="cuda:0")
+    B.flame_gr_forward_static(B.config_for(wl), dw, hist, wl.history_offsets, cand, wl.cand_offsets, out)
+    torch.cuda.synchronize()
+    ways["static workspace"] = out.cpu().numpy().copy()
+    if c["kind"] == "silu" and max(c["L"]) + 1 <= 400 and max(c["M"]) > 3:
+        ways["split by max_seq_tokens"] = forward(max_seq_tokens=max(c["L"]) + max(2, max(c["M"]) // 3), grow=True)
+    for name, g in ways.items():
+        assert np.array_equal(g, ref), (name, c, float(np.nanmax(np.abs(g - ref))))
+    print(f"seed {seed}: {sorted(ways)} equal the plain forward on {c}")
