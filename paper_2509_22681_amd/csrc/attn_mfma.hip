@@ -141,12 +141,12 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
   const bool row_valid = my_q_local < it.n_q;
   f16x8 fq[KS];                        // Q fragments (B operand of S^T): row = my query, k = 16*s + 8*lhalf + 0..7
   int n_vis;
+  int64_t q_row_clamped;
   {
     const int64_t row = it.q_row + (row_valid ? my_q_local : it.n_q - 1);   // clamped for loads
     const int q_index = it.is_cand ? it.L : it.q_pos + my_q_local;
     n_vis = visible_history(it.is_cand, q_index, it.L);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) fq[s] = *(const f16x8 *)(Qp + row * d + s * 16 + lhalf * 8);
+    q_row_clamped = row;
   }
   const int wave_vis_min = it.is_cand ? it.L : it.q_pos + q_local0 + 1;
   const int wave_vis_max = it.is_cand ? it.L : it.q_pos + q_local0 + 32;
@@ -242,6 +242,11 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
     if (n_tiles > 1) next_tile();
     request_tile(1);
   }
+  // The query fragments are requested behind the first two tiles, not ahead of them: the tiles are what the first
+  // step waits for.  (The waits below count requests in order: with at most REQ outstanding, the query loads and
+  // every tile before the newest have landed.)
+#pragma unroll
+  for (int s = 0; s < KS; ++s) fq[s] = *(const f16x8 *)(Qp + q_row_clamped * d + s * 16 + lhalf * 8);
   // One key tile.  The stage is a compile-time constant (the tile loop below is unrolled over the ring), so
   // every fragment address is a fixed lane offset plus an immediate and costs no instruction.
   auto tile_step = [&](auto stage_c, const int t) {
