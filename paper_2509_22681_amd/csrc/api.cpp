@@ -22,6 +22,7 @@ namespace {
 
 constexpr uint32_t kMagic = 0x464c4752u;  // "FLGR"
 constexpr int kStageSlots = 2;
+constexpr size_t kStageOneCopyBytes = 64 << 10;   // plan tables up to this size are staged with one copy
 constexpr int kMaxGroups = 16;
 constexpr int kMaxGraphs = FLAME_GR_MAX_GRAPHS;
 enum { KIND_ASSEMBLE = 0, KIND_BIAS, KIND_UVQK, KIND_ATTN, KIND_LNGATE, KIND_OUTPROJ, KIND_SCORE, KIND_COUNT };
@@ -326,10 +327,15 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
   char *sh_ = h->stage_host[slot];
   // a pass on another stream must not overtake the previous one on this handle
   if (h->has_prev) HIP_TRY(h, hipStreamWaitEvent(s0, h->ev_done, 0));
-  // the tables are copied separately, only as far as they are filled and only those the pass reads
+  // The tables are copied separately, only as far as they are filled and only those the pass reads; on a handle whose
+  // tables are small altogether (one or a few requests) they leave as one copy instead, what lies between them included:
+  // every copy is a few microseconds in front of the first kernel.
+  const bool one_copy = h->lay.total <= kStageOneCopyBytes;
+  size_t staged_end = 0;
   auto stage = [&](size_t off, const void *src, size_t bytes) -> hipError_t {
     if (bytes == 0) return hipSuccess;
     std::memcpy(sh_ + off, src, bytes);
+    if (one_copy) { staged_end = std::max(staged_end, off + bytes); return hipSuccess; }
     return hipMemcpyAsync(h->stage_dev + off, sh_ + off, bytes, hipMemcpyHostToDevice, s0);
   };
   HIP_TRY(h, stage(h->lay.blocks, P.blocks.data(), P.blocks.size() * sizeof(RowBlock)));
@@ -342,6 +348,7 @@ int enqueue_pass(flame_gr *h, const flame_gr_weights *w, const void *history_emb
     HIP_TRY(h, stage(h->lay.hist_items, P.hist_items.data(), P.hist_items.size() * sizeof(AttnItem)));
     HIP_TRY(h, stage(h->lay.hist_blocks, P.hist_blocks.data(), P.hist_blocks.size() * sizeof(int32_t)));
   }
+  if (one_copy && staged_end > 0) HIP_TRY(h, hipMemcpyAsync(h->stage_dev, sh_, staged_end, hipMemcpyHostToDevice, s0));
   HIP_TRY(h, hipEventRecord(h->stage_done[slot], s0));
   h->stage_used[slot] = true;
   {
