@@ -187,7 +187,9 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
   const char *bK = (const char *)(Kp + (int64_t)it.kv_row * d);
   const char *bV = (const char *)(Vt + it.kv_row);
   uint32_t oK, oV;
-  const int dW0 = q_first + (QT - 1) - (wave * 64 + lane);   // distance held by window slot 64 w + lane in tile 0
+  // (candidate tiles shift the window by one slot: all their rows read it at the same slots, which then start on a
+  // 16-byte boundary and leave as four-float reads)
+  const int dW0 = q_first + (QT - 1) + (it.is_cand ? 1 : 0) - (wave * 64 + lane);   // distance held by window slot 64 w + lane in tile 0
   int sW = 0;                                                 // keys the next tile to request lies behind tile 0 (scalar)
   {
     const int row = wave * (64 / KCH) + lane / KCH;
@@ -223,9 +225,9 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
   };
 
   // Window slot of (my row, key 0 of the tile) is QT-1 - m + 8*lhalf with m the row's index in the
-  // workgroup tile (0 for candidate rows: they all sit at the same distance from a key); keys further
-  // right sit at increasing slots.
-  const int bias_idx = (QT - 1) - (it.is_cand ? 0 : my_q_local) + 8 * lhalf;
+  // workgroup tile; keys further right sit at increasing slots.  Candidate rows all sit at the same distance
+  // from a key (m = 0), and their window is shifted by one slot: QT + 8*lhalf, a 16-byte boundary.
+  const int bias_idx = it.is_cand ? QT + 8 * lhalf : (QT - 1) - my_q_local + 8 * lhalf;
   // fragment byte offsets inside a stage.  K (A operand of S^T): MFMA row m takes key pi32(m); per 32-key
   // block j the row advances by 32 (key bits 0..4 unchanged, so the swizzle key is the same).  V^T (A
   // operand of O^T): row = feature 32 b + l32, chunk = key / 8.
@@ -281,10 +283,22 @@ __global__ __launch_bounds__(KSPLIT ? 512 : 256, KSPLIT ? 1 : 3) void attn_mfma_
           typedef const __attribute__((address_space(3))) float *lds_cfloat;
           lds_cfloat bp = (lds_cfloat)(sb + K_BYTES + V_BYTES) + (bias_idx + u * KH);
           asm volatile("" : "+v"(bp));
+          if (it.is_cand) {
+            typedef const __attribute__((address_space(3))) f32x4 *lds_cf4;
 #pragma unroll
-          for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < 2; ++j)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) sacc[j][e] = bp[32 * j + 16 * (e >> 3) + (e & 7)];
+              for (int g = 0; g < 4; ++g) {
+                const f32x4 v = *(lds_cf4)(bp + 32 * j + 16 * (g >> 1) + 4 * (g & 1));
+#pragma unroll
+                for (int q = 0; q < 4; ++q) sacc[j][4 * g + q] = v[q];
+              }
+          } else {
+#pragma unroll
+            for (int j = 0; j < 2; ++j)
+#pragma unroll
+              for (int e = 0; e < 16; ++e) sacc[j][e] = bp[32 * j + 16 * (e >> 3) + (e & 7)];
+          }
         }
         f16x8 fk[2][2], fv[2][DB];
 #pragma unroll
